@@ -1,0 +1,209 @@
+"""Python face of the CPU oracle (test infrastructure, never the product path).
+
+Loads ``libgalore_oracle.so`` (plain C, fp64, built from ``galore_oracle.c`` in
+this directory) and composes its routines into one GaLore step in the order of
+Algorithm 2 of arXiv 2403.03507.  Only the tests, the smoke check and the
+benchmark's cpu_baseline leg use this module.  It imports nothing from the HIP
+package.
+
+Readings of the paper taken here (the paper is silent or inconsistent):
+  * M and V have the shape of R = P^T G (Algorithm 2 prints n x r for the
+    initial moments but r x n for R).
+  * The refresh test uses the 0-based counter t (first step refreshes); the
+    bias correction uses k = t + 1, and corrected moments are temporaries.
+  * eps is added after the square root of the corrected second moment
+    (Algorithm 2 / the N_t equation, not the form in Sec. 3.1).
+  * The caller passes the positive gradient and the update is subtracted; the
+    paper negates the gradient and adds.  Same trajectory.
+  * m > n mirrors Algorithm 2 with Q = V[:, :r], R = G Q, update N Q^T
+    (Sec. 4.2, one-sided projection rule).
+  * M and V are kept as they are when the projector changes.
+  * Weight decay, not printed in the paper, is decoupled and not scaled by
+    alpha: W <- (1 - lr*wd) W - lr*alpha*P N.  Parity unpinned beyond wd = 0.
+  * Storage: the algorithm's state lives in the caller's dtypes, so after each
+    step W and the projector are rounded (nearest-even) to the weight dtype and
+    M, V to fp32; all arithmetic in between is fp64.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "galore_oracle.c")
+_LIB = os.path.join(_HERE, "libgalore_oracle.so")
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (OpenMP on outer loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+_dp = ctypes.POINTER(ctypes.c_double)
+_i64 = ctypes.c_int64
+_f64 = ctypes.c_double
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        L = _lib
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_round_bf16.argtypes = [_dp, _i64]
+        L.oracle_round_f32.argtypes = [_dp, _i64]
+        L.oracle_project_left.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64]
+        L.oracle_project_right.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64]
+        L.oracle_adam.argtypes = [_dp, _dp, _dp, _dp, _i64, _f64, _f64, _f64, _i64]
+        L.oracle_apply_left.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64, _f64, _f64, _f64]
+        L.oracle_apply_right.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64, _f64, _f64, _f64]
+        L.oracle_top_left_singular_vectors.argtypes = [_dp, _i64, _i64, _i64, _dp, _dp, _f64, ctypes.c_int]
+        L.oracle_top_left_singular_vectors.restype = ctypes.c_int
+        L.oracle_projector.argtypes = [_dp, _i64, _i64, _i64, _dp, _dp, _f64, ctypes.c_int]
+        L.oracle_projector.restype = ctypes.c_int
+    return _lib
+
+
+def _c(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a
+
+
+def _p(a):
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_dp)
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
+def round_storage(x, dtype):
+    """Nearest-even rounding of an fp64 array to 'f32' or 'bf16' values (kept as fp64)."""
+    y = _c(x).copy()
+    if dtype == "bf16":
+        lib().oracle_round_bf16(_p(y), y.size)
+    elif dtype == "f32":
+        lib().oracle_round_f32(_p(y), y.size)
+    elif dtype != "f64":
+        raise ValueError(dtype)
+    return y
+
+
+def project(proj, G):
+    """R = P^T G (m <= n) or G Q (m > n)."""
+    G = _c(G)
+    proj = _c(proj)
+    m, n = G.shape
+    r = proj.shape[1]
+    if m <= n:
+        assert proj.shape[0] == m
+        R = np.empty((r, n))
+        lib().oracle_project_left(_p(proj), _p(G), _p(R), m, n, r)
+    else:
+        assert proj.shape[0] == n
+        R = np.empty((m, r))
+        lib().oracle_project_right(_p(G), _p(proj), _p(R), m, n, r)
+    return R
+
+
+def adam(R, M, V, beta1, beta2, eps, k):
+    """In-place moment update; returns N.  k is the 1-based step number."""
+    R = _c(R)
+    assert M.shape == R.shape and V.shape == R.shape
+    N = np.empty_like(R)
+    lib().oracle_adam(_p(R), _p(M), _p(V), _p(N), R.size, beta1, beta2, eps, int(k))
+    return N
+
+
+def apply_update(W, proj, N, lr, alpha, weight_decay=0.0):
+    """In place: W <- (1 - lr*wd) W - lr*alpha * (P N  or  N Q^T)."""
+    m, n = W.shape
+    proj = _c(proj)
+    N = _c(N)
+    r = proj.shape[1]
+    if m <= n:
+        assert N.shape == (r, n)
+        lib().oracle_apply_left(_p(W), _p(proj), _p(N), m, n, r, lr, alpha, weight_decay)
+    else:
+        assert N.shape == (m, r)
+        lib().oracle_apply_right(_p(W), _p(N), _p(proj), m, n, r, lr, alpha, weight_decay)
+    return W
+
+
+def top_left_singular_vectors(A, r, tol=1e-12, max_sweeps=60):
+    A = _c(A)
+    p, q = A.shape
+    U = np.empty((p, r))
+    s = np.empty(p)
+    sweeps = lib().oracle_top_left_singular_vectors(_p(A), p, q, r, _p(U), _p(s), tol, max_sweeps)
+    if sweeps < 0:
+        raise RuntimeError("Jacobi SVD did not converge")
+    return U, s
+
+
+def projector(G, r, tol=1e-12, max_sweeps=60):
+    """P = U[:, :r] (m <= n) or Q = V[:, :r] (m > n), plus all singular values."""
+    G = _c(G)
+    m, n = G.shape
+    k = min(m, n)
+    proj = np.empty((k, r))
+    s = np.empty(k)
+    sweeps = lib().oracle_projector(_p(G), m, n, r, _p(proj), _p(s), tol, max_sweeps)
+    if sweeps < 0:
+        raise RuntimeError("Jacobi SVD did not converge")
+    return proj, s
+
+
+class GaLoreTensor:
+    """One weight matrix under Algorithm 2, fp64 arithmetic, storage-dtype state."""
+
+    def __init__(self, W, rank, update_gap=200, scale=0.25, beta1=0.9, beta2=0.999,
+                 eps=1e-8, weight_decay=0.0, dtype="f32", auto_refresh=True):
+        self.dtype = dtype
+        self.W = round_storage(W, dtype)
+        self.m, self.n = self.W.shape
+        self.r = int(rank)
+        assert 1 <= self.r <= min(self.m, self.n)
+        self.T = int(update_gap)
+        self.alpha, self.beta1, self.beta2 = float(scale), float(beta1), float(beta2)
+        self.eps, self.wd = float(eps), float(weight_decay)
+        self.auto_refresh = auto_refresh
+        self.left = self.m <= self.n
+        shape = (self.r, self.n) if self.left else (self.m, self.r)
+        self.M = np.zeros(shape)
+        self.V = np.zeros(shape)
+        self.proj = None
+        self.sigma = None
+        self.t = 0
+        self.last_R = None
+        self.last_N = None
+
+    def refresh(self, G):
+        P, s = projector(G, self.r)
+        self.proj = round_storage(P, self.dtype)
+        self.sigma = s
+        return self.proj
+
+    def set_projector(self, proj):
+        self.proj = round_storage(proj, self.dtype)
+
+    def step(self, G, lr):
+        G = round_storage(G, self.dtype)
+        if self.auto_refresh and self.t % self.T == 0:
+            self.refresh(G)
+        R = project(self.proj, G)
+        N = adam(R, self.M, self.V, self.beta1, self.beta2, self.eps, self.t + 1)
+        self.last_R, self.last_N = R, N
+        apply_update(self.W, self.proj, N, lr, self.alpha, self.wd)
+        self.W = round_storage(self.W, self.dtype)
+        self.M = round_storage(self.M, "f32")
+        self.V = round_storage(self.V, "f32")
+        self.t += 1
+        return self.W
