@@ -1,0 +1,172 @@
+/*
+ * galore.h - C ABI of the MI355X (gfx950) GaLore optimizer-step library.
+ *
+ * The library performs, for a list of 2-D weights, the step of "Adam with GaLore"
+ * (arXiv 2403.03507, Algorithm 2):
+ *
+ *     if t mod T == 0:  P <- leading r singular vectors of G          (refresh)
+ *     R = P^T G                                                       (project)
+ *     M <- b1 M + (1-b1) R ;  V <- b2 V + (1-b2) R^2                  (Adam moments)
+ *     N = (M / (1-b1^k)) / (sqrt(V / (1-b2^k)) + eps),  k = t+1       (normalised update)
+ *     W <- (1 - lr*wd) W - lr * alpha * P N                           (project back + apply)
+ *     t <- t+1
+ *
+ * Orientation (Sec. 4.2, one-sided projection): a tensor with rows <= cols is LEFT
+ * (projector P is rows x r; R, M, V, N are r x cols); a tensor with rows > cols is
+ * RIGHT (projector Q is cols x r; R = G Q, M, V, N are rows x r; update is N Q^T).
+ *
+ * Conventions common to every call
+ *   - All tensor data pointers are DEVICE pointers (HIP global memory of the current
+ *     device), row-major, leading dimension `ld` in elements (ld >= cols).  They are
+ *     BORROWED: the library never allocates, frees or keeps device memory of its own
+ *     except through the caller's workspace.  Argument structs and arrays of structs
+ *     are HOST memory and are copied during the call.
+ *   - The gradient is the positive gradient of the loss; the update is subtracted.
+ *     (The paper negates the gradient and adds; the trajectory is the same.)
+ *   - Work is enqueued on the HIP stream given to galore_init (or to the stateless
+ *     stage calls) and the call returns without synchronising.
+ *   - Every call returns a galore_status.  Arguments are validated on the host before
+ *     anything is launched; on a validation error nothing has been enqueued.
+ *   - Results are deterministic: no atomics, fixed reduction order.
+ */
+#ifndef GALORE_H
+#define GALORE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GALORE_OK = 0,
+  GALORE_ERR_INVALID_ARG = 1, /* null pointer, bad count/range, bad hyper-parameter */
+  GALORE_ERR_SHAPE = 2,       /* tensor shapes inconsistent with each other / with init */
+  GALORE_ERR_DTYPE = 3,       /* dtype combination not supported */
+  GALORE_ERR_RANK = 4,        /* rank outside 1..min(rows, cols) */
+  GALORE_ERR_ALIGN = 5,       /* state / workspace pointer not 16-byte aligned */
+  GALORE_ERR_WORKSPACE = 6,   /* workspace too small for even one tensor */
+  GALORE_ERR_STATE = 7,       /* call order wrong (e.g. step before any projector exists) */
+  GALORE_ERR_HIP = 8,         /* a HIP runtime call or kernel launch failed */
+  GALORE_ERR_UNIMPLEMENTED = 9
+} galore_status;
+
+typedef enum { GALORE_F32 = 0, GALORE_BF16 = 1 } galore_dtype;
+
+/* A row-major matrix in device memory.  BORROWED. */
+typedef struct {
+  void* data;   /* device pointer */
+  int64_t rows;
+  int64_t cols;
+  int64_t ld;   /* elements between consecutive rows, >= cols */
+  int32_t dtype; /* galore_dtype */
+} galore_tensor;
+
+/* Optimizer state of one weight.  BORROWED, caller-allocated, survives across steps
+ * (this is what a checkpoint saves, together with the step counter).
+ *   proj : P (rows x r) for LEFT, Q (cols x r) for RIGHT; dtype = dtype of W.
+ *   m, v : fp32, r x cols (LEFT) or rows x r (RIGHT), ld == cols, 16-byte aligned.
+ * Element count is min(rows,cols)*r + 2*max(rows,cols)*r, the paper's mr + 2nr (Sec. 4.2). */
+typedef struct {
+  galore_tensor proj;
+  galore_tensor m;
+  galore_tensor v;
+} galore_state;
+
+/* Hyper-parameters (Algorithm 2 inputs; Sec. 4.4).  Paper defaults: update_gap 200,
+ * scale 0.25, betas (0.9, 0.999), eps 1e-8. */
+typedef struct {
+  int32_t rank;          /* r */
+  int32_t update_gap;    /* T, >= 1 */
+  float scale;           /* alpha */
+  float beta1;
+  float beta2;
+  float eps;
+  float weight_decay;    /* decoupled, multiplies lr only (not alpha); 0 = Algorithm 2 as printed */
+  int32_t refresh_iters; /* subspace iterations per refresh, >= 1 */
+  int32_t auto_refresh;  /* 1: galore_step refreshes the projector itself when t mod T == 0;
+                            0: the caller owns the projector contents (writes state.proj or
+                               calls galore_refresh_subspace) */
+  uint64_t seed;         /* seed of the Gaussian start block of the first refresh */
+} galore_hparams;
+
+typedef struct galore_ctx galore_ctx; /* opaque; OWNED by the library; host memory only */
+
+/* Human-readable text for a status code (static storage). */
+const char* galore_status_string(galore_status s);
+
+/* Workspace, in bytes, that lets one call process up to 8 consecutive tensors of the
+ * list per kernel launch (transients R and N of the step; Gram matrix, iteration blocks
+ * and reflector storage of the refresh).  Any 256-byte-aligned workspace at least as
+ * large as the largest single-tensor need is accepted by galore_init; a smaller one
+ * only means more, smaller launches.  No device access. */
+galore_status galore_workspace_bytes(const galore_hparams* hp, const galore_tensor* W,
+                                     int32_t n_tensors, size_t* out_bytes);
+
+/* Create a context for a list of n_tensors weights and their states (Algorithm 2,
+ * initialisation lines): validates everything, records shapes and state pointers,
+ * zero-fills every M and V on `hip_stream` (hipStream_t, may be NULL for the default
+ * stream) and sets every step counter t to 0.  Projectors are left untouched.
+ * The W entries are used for shape/dtype only; data pointers are given per step.
+ * On error *out is NULL. */
+galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galore_tensor* W,
+                          const galore_state* S, int32_t n_tensors, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/* One optimizer step (the loop body of Algorithm 2) for tensors first..first+count-1 of
+ * the list, in list order.  W[i], G[i] (i = 0..count-1) describe tensor first+i; shapes and
+ * dtypes must match those given at init.  W is updated in place; G is read only.  With
+ * auto_refresh, tensors whose counter satisfies t mod T == 0 first get a new projector
+ * from this G.  Each tensor's counter advances by one.  Calling with a sub-range lets a
+ * training loop update one layer at a time during back-propagation (Sec. 4.3). */
+galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G,
+                          int32_t first, int32_t count, float lr);
+
+/* Recompute the projectors of tensors first..first+count-1 from the gradients G
+ * (Algorithm 2, refresh branch; Sec. 3.3 SVD equation): the leading r left (LEFT) or right
+ * (RIGHT) singular vectors of G, obtained from the Gram matrix of the short side by
+ * blocked subspace iteration with Householder QR and a final Rayleigh-Ritz rotation, so
+ * columns are ordered by decreasing singular value; each column's sign makes its
+ * largest-magnitude entry positive.  Writes state.proj only; M, V, W and t are untouched. */
+galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, int32_t first,
+                                      int32_t count);
+
+/* Step counter t of one tensor (number of steps taken); set is for checkpoint resume. */
+galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t);
+galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t);
+
+/* Message of the last failing call on this context ("" if none).  With ctx == NULL,
+ * the message of the last failing galore_init / stateless call of this thread. */
+const char* galore_last_error(const galore_ctx* ctx);
+
+/* Free the host-side context.  Device memory is the caller's. */
+void galore_destroy(galore_ctx* ctx);
+
+/* ---- Stateless stage calls: the three per-step stages of Algorithm 2 on one tensor. ----
+ * They run the same kernels galore_step runs and exist so each stage can be checked and
+ * timed alone. */
+
+/* R = P^T G (LEFT) or G Q (RIGHT) (Algorithm 2, projection line).  R is fp32, r x cols or
+ * rows x r, ld == its cols.  proj dtype == G dtype. */
+galore_status galore_project(const galore_tensor* proj, const galore_tensor* G,
+                             const galore_tensor* R, void* hip_stream);
+
+/* Adam on the projected gradient (Algorithm 2, update block): updates fp32 M, V in place
+ * and writes N (fp32 or bf16), all with R's shape and ld == cols.  k >= 1 is the 1-based
+ * step used by the bias correction. */
+galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V,
+                          const galore_tensor* N, float beta1, float beta2, float eps, int64_t k,
+                          void* hip_stream);
+
+/* W <- (1 - lr*weight_decay) W - lr*scale * (P N  or  N Q^T) (Algorithm 2, last lines),
+ * applied inside the GEMM epilogue; the full-size update is never stored.  N dtype ==
+ * proj dtype == W dtype. */
+galore_status galore_project_back(const galore_tensor* proj, const galore_tensor* N,
+                                  const galore_tensor* W, float lr, float scale,
+                                  float weight_decay, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GALORE_H */

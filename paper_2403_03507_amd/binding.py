@@ -1,0 +1,207 @@
+"""ctypes face of ``libgalore.so`` (the C ABI in ``include/galore.h``).
+
+Argument marshalling only: every step of the optimizer runs inside the HIP library.
+PyTorch is used for device memory and for the current HIP stream.  There is no fallback:
+if the library is missing this module raises.
+"""
+import ctypes
+import os
+
+import torch  # also loads the HIP runtime the library binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgalore.so")
+
+GALORE_OK = 0
+STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "DTYPE", 4: "RANK", 5: "ALIGN",
+                6: "WORKSPACE", 7: "STATE", 8: "HIP", 9: "UNIMPLEMENTED"}
+GALORE_F32, GALORE_BF16 = 0, 1
+_DTYPES = {torch.float32: GALORE_F32, torch.bfloat16: GALORE_BF16}
+
+
+class galore_tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+
+
+class galore_state(ctypes.Structure):
+    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("v", galore_tensor)]
+
+
+class galore_hparams(ctypes.Structure):
+    _fields_ = [("rank", ctypes.c_int32), ("update_gap", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("refresh_iters", ctypes.c_int32),
+                ("auto_refresh", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+
+
+class GaloreError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("galore status %d (%s): %s" % (status, STATUS_NAMES.get(status, "?"), message))
+        self.status = status
+
+
+EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
+           "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
+           "galore_destroy", "galore_project", "galore_adam", "galore_project_back"]
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libgalore.so is not built: run `python -m paper_2403_03507_amd.build` "
+                               "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+        tp, sp, hp = ctypes.POINTER(galore_tensor), ctypes.POINTER(galore_state), ctypes.POINTER(galore_hparams)
+        L.galore_status_string.argtypes = [ctypes.c_int]
+        L.galore_status_string.restype = ctypes.c_char_p
+        L.galore_workspace_bytes.argtypes = [hp, tp, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.galore_init.argtypes = [ctypes.POINTER(vp), hp, tp, sp, i32, vp, ctypes.c_size_t, vp]
+        L.galore_step.argtypes = [vp, tp, tp, i32, i32, f32]
+        L.galore_refresh_subspace.argtypes = [vp, tp, i32, i32]
+        L.galore_get_step.argtypes = [vp, i32, ctypes.POINTER(i64)]
+        L.galore_set_step.argtypes = [vp, i32, i64]
+        L.galore_last_error.argtypes = [vp]
+        L.galore_last_error.restype = ctypes.c_char_p
+        L.galore_destroy.argtypes = [vp]
+        L.galore_destroy.restype = None
+        L.galore_project.argtypes = [tp, tp, tp, vp]
+        L.galore_adam.argtypes = [tp, tp, tp, tp, f32, f32, f32, i64, vp]
+        L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status, ctx=None):
+    if status != GALORE_OK:
+        msg = lib().galore_last_error(ctx)
+        raise GaloreError(status, msg.decode() if msg else "")
+
+
+def desc(t):
+    """galore_tensor view of a 2-D torch tensor with unit column stride."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("need a 2-D row-major tensor")
+    return galore_tensor(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]),
+                         _DTYPES[t.dtype])
+
+
+def shape_desc(rows, cols, dtype, ld=None, data=None):
+    return galore_tensor(data, rows, cols, cols if ld is None else ld, _DTYPES[dtype] if not isinstance(dtype, int) else dtype)
+
+
+def _arr(items, typ):
+    return (typ * len(items))(*items)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_hparams(rank, update_gap=200, scale=0.25, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                 refresh_iters=6, auto_refresh=True, seed=0):
+    return galore_hparams(rank, update_gap, scale, beta1, beta2, eps, weight_decay, refresh_iters,
+                          1 if auto_refresh else 0, seed)
+
+
+# ---- the C calls, same names -------------------------------------------------------------------
+
+def galore_workspace_bytes(hp, w_descs):
+    out = ctypes.c_size_t(0)
+    _check(lib().galore_workspace_bytes(ctypes.byref(hp), _arr(w_descs, galore_tensor), len(w_descs), ctypes.byref(out)))
+    return out.value
+
+
+def galore_init(hp, w_descs, states, workspace_ptr, workspace_bytes, stream=None):
+    ctx = ctypes.c_void_p(None)
+    st = lib().galore_init(ctypes.byref(ctx), ctypes.byref(hp), _arr(w_descs, galore_tensor), _arr(states, galore_state),
+                           len(w_descs), ctypes.c_void_p(workspace_ptr), workspace_bytes,
+                           stream if stream is not None else _stream())
+    _check(st)
+    return ctx
+
+
+def galore_step(ctx, w_descs, g_descs, first, count, lr):
+    _check(lib().galore_step(ctx, _arr(w_descs, galore_tensor), _arr(g_descs, galore_tensor), first, count, lr), ctx)
+
+
+def galore_refresh_subspace(ctx, g_descs, first, count):
+    _check(lib().galore_refresh_subspace(ctx, _arr(g_descs, galore_tensor), first, count), ctx)
+
+
+def galore_get_step(ctx, tensor):
+    t = ctypes.c_int64(0)
+    _check(lib().galore_get_step(ctx, tensor, ctypes.byref(t)))
+    return t.value
+
+
+def galore_set_step(ctx, tensor, t):
+    _check(lib().galore_set_step(ctx, tensor, t), ctx)
+
+
+def galore_destroy(ctx):
+    lib().galore_destroy(ctx)
+
+
+def galore_project(proj, G, R):
+    _check(lib().galore_project(ctypes.byref(desc(proj)), ctypes.byref(desc(G)), ctypes.byref(desc(R)), _stream()))
+
+
+def galore_adam(R, M, V, N, beta1, beta2, eps, k):
+    _check(lib().galore_adam(ctypes.byref(desc(R)), ctypes.byref(desc(M)), ctypes.byref(desc(V)), ctypes.byref(desc(N)),
+                             beta1, beta2, eps, k, _stream()))
+
+
+def galore_project_back(proj, N, W, lr, scale, weight_decay=0.0):
+    _check(lib().galore_project_back(ctypes.byref(desc(proj)), ctypes.byref(desc(N)), ctypes.byref(desc(W)), lr, scale,
+                                     weight_decay, _stream()))
+
+
+class GaLore:
+    """Owns the device memory of a tensor list's optimizer state (allocated with torch) and a
+    library context bound to torch's current stream.  All arithmetic happens in the library."""
+
+    def __init__(self, weights, rank, device="cuda", workspace_bytes=None, **hparams):
+        self.hp = make_hparams(rank, **hparams)
+        self.shapes = [(w.shape[0], w.shape[1]) for w in weights]
+        self.dtypes = [w.dtype for w in weights]
+        self.proj, self.M, self.V = [], [], []
+        for (m, n), dt in zip(self.shapes, self.dtypes):
+            k, l = (m, n) if m <= n else (n, m)
+            self.proj.append(torch.zeros(k, rank, dtype=dt, device=device))
+            shape = (rank, l) if m <= n else (l, rank)
+            self.M.append(torch.empty(shape, dtype=torch.float32, device=device))
+            self.V.append(torch.empty(shape, dtype=torch.float32, device=device))
+        w_descs = [shape_desc(m, n, dt) for (m, n), dt in zip(self.shapes, self.dtypes)]
+        if workspace_bytes is None:
+            workspace_bytes = galore_workspace_bytes(self.hp, w_descs)
+        self.workspace = torch.empty(max(workspace_bytes, 256), dtype=torch.uint8, device=device)
+        states = [galore_state(desc(p), desc(m), desc(v)) for p, m, v in zip(self.proj, self.M, self.V)]
+        self.ctx = galore_init(self.hp, w_descs, states, self.workspace.data_ptr(), workspace_bytes)
+
+    def step(self, weights, grads, lr, first=0):
+        galore_step(self.ctx, [desc(w) for w in weights], [desc(g) for g in grads], first, len(weights), lr)
+
+    def refresh(self, grads, first=0):
+        galore_refresh_subspace(self.ctx, [desc(g) for g in grads], first, len(grads))
+
+    def get_step(self, i):
+        return galore_get_step(self.ctx, i)
+
+    def set_step(self, i, t):
+        galore_set_step(self.ctx, i, t)
+
+    def close(self):
+        if self.ctx is not None:
+            galore_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

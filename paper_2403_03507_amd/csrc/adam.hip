@@ -1,0 +1,103 @@
+// Fused low-rank Adam (Algorithm 2, update block): one pass over R, M, V that updates the
+// fp32 moments in place, applies the bias correction and writes the normalised update N
+// in the dtype the back-projection GEMM consumes.  Pure streaming: 16-byte vectors.
+#include "common.hpp"
+
+namespace galore {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float adam_entry(float g, float& m, float& v, float beta1, float beta2,
+                                            float eps, float inv_c1, float inv_c2) {
+  m = beta1 * m + (1.f - beta1) * g;
+  v = beta2 * v + (1.f - beta2) * g * g;
+  return (m * inv_c1) / (sqrtf(v * inv_c2) + eps);
+}
+
+__device__ __forceinline__ void store_n(float* N, int64_t i, f32x4 n) { *reinterpret_cast<f32x4*>(N + i) = n; }
+__device__ __forceinline__ void store_n(__bf16* N, int64_t i, f32x4 n) {
+  bf16x4 o;
+  o[0] = (__bf16)n[0]; o[1] = (__bf16)n[1]; o[2] = (__bf16)n[2]; o[3] = (__bf16)n[3];
+  *reinterpret_cast<bf16x4*>(N + i) = o;
+}
+
+template <class TN>
+__global__ __launch_bounds__(256) void adam_group_kernel(const AdamGroup grp) {
+  const AdamProblem& pr = grp.p[blockIdx.y];
+  const float beta1 = grp.beta1, beta2 = grp.beta2, eps = grp.eps;
+  const float ic1 = pr.inv_c1, ic2 = pr.inv_c2;
+  const float* __restrict__ R = pr.R;
+  float* __restrict__ M = pr.M;
+  float* __restrict__ V = pr.V;
+  TN* __restrict__ N = static_cast<TN*>(pr.N);
+  const int64_t count = pr.count;
+  const int64_t nvec = count >> 2;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nvec; q += stride) {
+    const int64_t i = q << 2;
+    const f32x4 g = *reinterpret_cast<const f32x4*>(R + i);
+    f32x4 m = *reinterpret_cast<const f32x4*>(M + i);
+    f32x4 v = *reinterpret_cast<const f32x4*>(V + i);
+    f32x4 n;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float me = m[e], ve = v[e];
+      n[e] = adam_entry(g[e], me, ve, beta1, beta2, eps, ic1, ic2);
+      m[e] = me; v[e] = ve;
+    }
+    *reinterpret_cast<f32x4*>(M + i) = m;
+    *reinterpret_cast<f32x4*>(V + i) = v;
+    store_n(N, i, n);
+  }
+  // ragged tail (count not a multiple of 4)
+  if (blockIdx.x == 0) {
+    const int64_t i = (nvec << 2) + threadIdx.x;
+    if (threadIdx.x < 4 && i < count) {
+      float me = M[i], ve = V[i];
+      const float n = adam_entry(R[i], me, ve, beta1, beta2, eps, ic1, ic2);
+      M[i] = me; V[i] = ve;
+      N[i] = (TN)n;
+    }
+  }
+}
+
+hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream) {
+  if (g.count <= 0) return hipSuccess;
+  if (g.count > kMaxGroup) return hipErrorInvalidValue;
+  int64_t maxcount = 0;
+  for (int i = 0; i < g.count; ++i) maxcount = g.p[i].count > maxcount ? g.p[i].count : maxcount;
+  if (maxcount == 0) return hipSuccess;
+  // 4 elements per thread per trip; enough blocks for ~4 trips each, capped to fill the chip a few times over
+  int64_t blocks = (maxcount / 4 + 256 * 4 - 1) / (256 * 4);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 2048) blocks = 2048;
+  dim3 grid((unsigned)blocks, (unsigned)g.count);
+  if (n_dtype == DType::BF16) hipLaunchKernelGGL(adam_group_kernel<__bf16>, grid, dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL(adam_group_kernel<float>, grid, dim3(256), 0, stream, g);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(unsigned char* p, size_t bytes) {
+  const size_t nvec = bytes / 16;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint4* pv = reinterpret_cast<uint4*>(p);
+  for (size_t i = first; i < nvec; i += stride) pv[i] = make_uint4(0u, 0u, 0u, 0u);
+  const size_t tail = nvec * 16 + first;  // fewer than 16 trailing bytes
+  if (tail < bytes) p[tail] = 0;
+}
+
+// Zero `bytes` at a 16-byte-aligned pointer with a plain kernel (not a memset node), so the
+// call can be recorded in a HIP graph like every other piece of the library's work.
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
+  if (bytes == 0) return hipSuccess;
+  size_t blocks = (bytes / 16 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     static_cast<unsigned char*>(ptr), bytes);
+  return hipGetLastError();
+}
+
+}  // namespace galore

@@ -1,0 +1,516 @@
+// Host side of the C ABI: context, validation, chunking of tensor lists into grouped
+// launches, and the per-step orchestration of Algorithm 2.  No kernels here.
+#include "../../include/galore.h"
+#include "common.hpp"
+#include "refresh.hpp"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace galore;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct TensorInfo {
+  int64_t rows, cols;
+  DType dt;
+  bool left;       // rows <= cols: projector on the left (P^T G), else on the right (G Q)
+  int64_t kdim;    // short side = rows of the projector
+  int64_t ldim;    // long side
+  galore_state st;
+  int64_t t;
+};
+
+}  // namespace
+
+struct galore_ctx {
+  galore_hparams hp;
+  std::vector<TensorInfo> tensors;
+  unsigned char* ws;
+  size_t ws_bytes;
+  hipStream_t stream;
+  std::string err;
+};
+
+namespace {
+
+galore_status fail(galore_ctx* ctx, galore_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  g_last_error = buf;
+  return s;
+}
+
+bool valid_dtype(int32_t d) { return d == GALORE_F32 || d == GALORE_BF16; }
+
+size_t step_need(int64_t ldim, int64_t r, DType dt) {
+  return align_up((size_t)r * ldim * 4) + align_up((size_t)r * ldim * dtype_size(dt));
+}
+
+size_t tensor_need(const galore_hparams& hp, int64_t kdim, int64_t ldim, DType dt) {
+  const size_t a = step_need(ldim, hp.rank, dt);
+  const size_t b = refresh_workspace_bytes(kdim, hp.rank);
+  return a > b ? a : b;
+}
+
+galore_status check_hparams(galore_ctx* ctx, const galore_hparams* hp) {
+  if (!hp) return fail(ctx, GALORE_ERR_INVALID_ARG, "hparams is NULL");
+  if (hp->rank < 1) return fail(ctx, GALORE_ERR_RANK, "rank %d < 1", hp->rank);
+  if (hp->update_gap < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "update_gap %d < 1", hp->update_gap);
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "betas must lie in [0, 1)");
+  if (!(hp->eps >= 0.f) || !std::isfinite(hp->scale) || !(hp->weight_decay >= 0.f))
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "eps / scale / weight_decay out of range");
+  if (hp->refresh_iters < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_iters %d < 1", hp->refresh_iters);
+  return GALORE_OK;
+}
+
+galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* what, int idx, bool need_data) {
+  if (need_data && !t.data) return fail(ctx, GALORE_ERR_INVALID_ARG, "%s[%d].data is NULL", what, idx);
+  if (t.rows < 1 || t.cols < 1) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] has empty shape %lld x %lld", what, idx,
+                                            (long long)t.rows, (long long)t.cols);
+  if (t.ld < t.cols) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d].ld %lld < cols %lld", what, idx, (long long)t.ld,
+                                 (long long)t.cols);
+  if (t.rows > INT32_MAX / 2 || t.ld > INT32_MAX / 2)
+    return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] dimension too large", what, idx);
+  if (!valid_dtype(t.dtype)) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d].dtype %d unknown", what, idx, t.dtype);
+  return GALORE_OK;
+}
+
+galore_status check_weight_shape(galore_ctx* ctx, const galore_hparams& hp, const galore_tensor& w, int idx) {
+  galore_status s = check_matrix(ctx, w, "W", idx, false);
+  if (s) return s;
+  const int64_t k = w.rows <= w.cols ? w.rows : w.cols;
+  if (hp.rank > k) return fail(ctx, GALORE_ERR_RANK, "rank %d exceeds min(rows, cols) = %lld of W[%d]", hp.rank,
+                               (long long)k, idx);
+  return GALORE_OK;
+}
+
+galore_status hip_fail(galore_ctx* ctx, hipError_t e, const char* where) {
+  if (e == hipErrorNotSupported) return fail(ctx, GALORE_ERR_UNIMPLEMENTED, "%s: not implemented", where);
+  return fail(ctx, GALORE_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+// ---- one chunk of the step: tensors idx[0..n) with their W, G -------------------------------
+struct StepItem {
+  int tensor;
+  const galore_tensor* W;
+  const galore_tensor* G;
+  float* R;
+  void* N;
+};
+
+galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, float lr) {
+  const galore_hparams& hp = ctx->hp;
+  const int r = hp.rank;
+  // workspace carve-up
+  size_t off = 0;
+  for (StepItem& it : items) {
+    const TensorInfo& ti = ctx->tensors[it.tensor];
+    it.R = reinterpret_cast<float*>(ctx->ws + off);
+    off += align_up((size_t)r * ti.ldim * 4);
+    it.N = ctx->ws + off;
+    off += align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+  }
+  // The list may mix dtypes; launches are split by (dtype, orientation).
+  for (int dti = 0; dti < 2; ++dti) {
+    const DType dt = dti == 0 ? DType::F32 : DType::BF16;
+    // K1: project
+    for (int left = 1; left >= 0; --left) {
+      GemmGroup g{};
+      for (const StepItem& it : items) {
+        const TensorInfo& ti = ctx->tensors[it.tensor];
+        if (ti.dt != dt || (int)ti.left != left) continue;
+        GemmProblem& p = g.p[g.count++];
+        if (left) {  // R (r x n) = P^T G : A = P as [K=m][M=r], B = G as [K=m][N=n]
+          p.A = ti.st.proj.data; p.lda = (int)ti.st.proj.ld;
+          p.B = it.G->data; p.ldb = (int)it.G->ld;
+          p.M = r; p.N = (int)ti.cols; p.K = (int)ti.rows;
+          p.C = it.R; p.ldc = (int)ti.cols;
+        } else {     // R (m x r) = G Q : A = G as [M=m][K=n], B = Q as [K=n][N=r]
+          p.A = it.G->data; p.lda = (int)it.G->ld;
+          p.B = ti.st.proj.data; p.ldb = (int)ti.st.proj.ld;
+          p.M = (int)ti.rows; p.N = r; p.K = (int)ti.cols;
+          p.C = it.R; p.ldc = r;
+        }
+      }
+      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/!left, /*b_kcontig=*/false, Epilogue::StoreF32, ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
+    }
+    // K2: Adam on R
+    {
+      AdamGroup g{};
+      g.beta1 = hp.beta1; g.beta2 = hp.beta2; g.eps = hp.eps;
+      for (const StepItem& it : items) {
+        const TensorInfo& ti = ctx->tensors[it.tensor];
+        if (ti.dt != dt) continue;
+        AdamProblem& p = g.p[g.count++];
+        const double k = (double)(ti.t + 1);
+        p.R = it.R;
+        p.M = static_cast<float*>(ti.st.m.data);
+        p.V = static_cast<float*>(ti.st.v.data);
+        p.N = it.N;
+        p.count = (int64_t)r * ti.ldim;
+        p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
+        p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
+      }
+      hipError_t e = launch_adam_group(g, dt, ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "Adam launch");
+    }
+    // K3: project back + apply
+    for (int left = 1; left >= 0; --left) {
+      GemmGroup g{};
+      for (const StepItem& it : items) {
+        const TensorInfo& ti = ctx->tensors[it.tensor];
+        if (ti.dt != dt || (int)ti.left != left) continue;
+        GemmProblem& p = g.p[g.count++];
+        if (left) {  // W (m x n) -= P N : A = P as [M=m][K=r], B = N as [K=r][N=n]
+          p.A = ti.st.proj.data; p.lda = (int)ti.st.proj.ld;
+          p.B = it.N; p.ldb = (int)ti.cols;
+        } else {     // W (m x n) -= N Q^T : A = N as [M=m][K=r], B = Q as [N=n][K=r]
+          p.A = it.N; p.lda = r;
+          p.B = ti.st.proj.data; p.ldb = (int)ti.st.proj.ld;
+        }
+        p.M = (int)ti.rows; p.N = (int)ti.cols; p.K = r;
+        p.C = it.W->data; p.ldc = (int)it.W->ld;
+        p.s0 = 1.f - lr * hp.weight_decay;
+        p.s1 = lr * hp.scale;
+      }
+      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::ApplyW, ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "back-projection GEMM launch");
+    }
+  }
+  return GALORE_OK;
+}
+
+galore_status check_step_tensor(galore_ctx* ctx, const TensorInfo& ti, const galore_tensor& x, const char* what, int i) {
+  galore_status s = check_matrix(ctx, x, what, i, true);
+  if (s) return s;
+  if (x.rows != ti.rows || x.cols != ti.cols)
+    return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] is %lld x %lld but the tensor was initialised as %lld x %lld", what, i,
+                (long long)x.rows, (long long)x.cols, (long long)ti.rows, (long long)ti.cols);
+  if ((DType)x.dtype != ti.dt) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d] dtype differs from init", what, i);
+  return GALORE_OK;
+}
+
+galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first, const std::vector<int>& local) {
+  // local: indices i (relative to `first`) of tensors to refresh, in order.
+  size_t pos = 0;
+  while (pos < local.size()) {
+    std::vector<RefreshItem> chunk;
+    size_t used = 0;
+    while (pos < local.size() && (int)chunk.size() < kMaxGroup) {
+      const int i = local[pos];
+      TensorInfo& ti = ctx->tensors[first + i];
+      const size_t need = refresh_workspace_bytes(ti.kdim, ctx->hp.rank);
+      if (!chunk.empty() && used + need > ctx->ws_bytes) break;
+      RefreshItem it{};
+      it.G = G[i].data; it.ldg = G[i].ld; it.rows = ti.rows; it.cols = ti.cols;
+      it.dt = ti.dt;
+      it.proj = ti.st.proj.data; it.ldp = ti.st.proj.ld;
+      it.ws = ctx->ws + used;
+      it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
+      chunk.push_back(it);
+      used += need;
+      ++pos;
+    }
+    hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
+  }
+  return GALORE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* galore_status_string(galore_status s) {
+  switch (s) {
+    case GALORE_OK: return "ok";
+    case GALORE_ERR_INVALID_ARG: return "invalid argument";
+    case GALORE_ERR_SHAPE: return "shape mismatch";
+    case GALORE_ERR_DTYPE: return "unsupported dtype";
+    case GALORE_ERR_RANK: return "rank out of range";
+    case GALORE_ERR_ALIGN: return "pointer alignment";
+    case GALORE_ERR_WORKSPACE: return "workspace too small";
+    case GALORE_ERR_STATE: return "bad call order";
+    case GALORE_ERR_HIP: return "HIP error";
+    case GALORE_ERR_UNIMPLEMENTED: return "not implemented";
+  }
+  return "unknown status";
+}
+
+galore_status galore_workspace_bytes(const galore_hparams* hp, const galore_tensor* W, int32_t n_tensors,
+                                     size_t* out_bytes) {
+  galore_status s = check_hparams(nullptr, hp);
+  if (s) return s;
+  if (!W || !out_bytes || n_tensors < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "W / out_bytes NULL or n_tensors < 1");
+  std::vector<size_t> need(n_tensors);
+  for (int i = 0; i < n_tensors; ++i) {
+    s = check_weight_shape(nullptr, *hp, W[i], i);
+    if (s) return s;
+    const bool left = W[i].rows <= W[i].cols;
+    need[i] = tensor_need(*hp, left ? W[i].rows : W[i].cols, left ? W[i].cols : W[i].rows, (DType)W[i].dtype);
+  }
+  size_t best = 0;
+  for (int i = 0; i < n_tensors; ++i) {
+    size_t sum = 0;
+    for (int j = i; j < n_tensors && j < i + 8; ++j) sum += need[j];
+    best = sum > best ? sum : best;
+  }
+  *out_bytes = best;
+  return GALORE_OK;
+}
+
+galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galore_tensor* W, const galore_state* S,
+                          int32_t n_tensors, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!out) return fail(nullptr, GALORE_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  galore_status s = check_hparams(nullptr, hp);
+  if (s) return s;
+  if (!W || !S || n_tensors < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "W / S NULL or n_tensors < 1");
+  if (!workspace) return fail(nullptr, GALORE_ERR_INVALID_ARG, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
+    return fail(nullptr, GALORE_ERR_ALIGN, "workspace must be %zu-byte aligned", kAlign);
+
+  std::vector<TensorInfo> infos(n_tensors);
+  const int64_t r = hp->rank;
+  for (int i = 0; i < n_tensors; ++i) {
+    s = check_weight_shape(nullptr, *hp, W[i], i);
+    if (s) return s;
+    TensorInfo& ti = infos[i];
+    ti.rows = W[i].rows; ti.cols = W[i].cols; ti.dt = (DType)W[i].dtype;
+    ti.left = ti.rows <= ti.cols;
+    ti.kdim = ti.left ? ti.rows : ti.cols;
+    ti.ldim = ti.left ? ti.cols : ti.rows;
+    ti.st = S[i];
+    ti.t = 0;
+    const galore_tensor& p = S[i].proj;
+    s = check_matrix(nullptr, p, "S.proj", i, true);
+    if (s) return s;
+    if (p.rows != ti.kdim || p.cols != r)
+      return fail(nullptr, GALORE_ERR_SHAPE, "S[%d].proj must be %lld x %lld", i, (long long)ti.kdim, (long long)r);
+    if ((DType)p.dtype != ti.dt) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d].proj dtype must equal the weight dtype", i);
+    const int64_t mr = ti.left ? r : ti.rows, mc = ti.left ? ti.cols : r;
+    const galore_tensor* mv[2] = {&S[i].m, &S[i].v};
+    for (int q = 0; q < 2; ++q) {
+      const galore_tensor& x = *mv[q];
+      s = check_matrix(nullptr, x, q ? "S.v" : "S.m", i, true);
+      if (s) return s;
+      if (x.dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d] moments must be fp32", i);
+      if (x.rows != mr || x.cols != mc || x.ld != mc)
+        return fail(nullptr, GALORE_ERR_SHAPE, "S[%d] moments must be dense %lld x %lld", i, (long long)mr, (long long)mc);
+      if (reinterpret_cast<uintptr_t>(x.data) & 15)
+        return fail(nullptr, GALORE_ERR_ALIGN, "S[%d] moments must be 16-byte aligned", i);
+    }
+    if (tensor_need(*hp, ti.kdim, ti.ldim, ti.dt) > workspace_bytes)
+      return fail(nullptr, GALORE_ERR_WORKSPACE, "workspace of %zu bytes cannot hold tensor %d (needs %zu)", workspace_bytes,
+                  i, tensor_need(*hp, ti.kdim, ti.ldim, ti.dt));
+  }
+
+  galore_ctx* ctx = new (std::nothrow) galore_ctx;
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "out of host memory");
+  ctx->hp = *hp;
+  ctx->tensors = std::move(infos);
+  ctx->ws = static_cast<unsigned char*>(workspace);
+  ctx->ws_bytes = workspace_bytes;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  // M_0 = V_0 = 0 (Algorithm 2, initialisation)
+  for (const TensorInfo& ti : ctx->tensors) {
+    const size_t bytes = (size_t)r * ti.ldim * 4;
+    hipError_t e = launch_fill_zero(ti.st.m.data, bytes, ctx->stream);
+    if (e == hipSuccess) e = launch_fill_zero(ti.st.v.data, bytes, ctx->stream);
+    if (e != hipSuccess) {
+      galore_status st = hip_fail(nullptr, e, "zero-filling moments");
+      delete ctx;
+      return st;
+    }
+  }
+  *out = ctx;
+  return GALORE_OK;
+}
+
+galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G, int32_t first, int32_t count,
+                          float lr) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  const int n = (int)ctx->tensors.size();
+  if (first < 0 || count < 0 || first > n || count > n - first)
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "range [%d, %d+%d) outside the %d tensors", first, first, count, n);
+  if (count == 0) return GALORE_OK;
+  if (!W || !G) return fail(ctx, GALORE_ERR_INVALID_ARG, "W or G is NULL");
+  if (!std::isfinite(lr)) return fail(ctx, GALORE_ERR_INVALID_ARG, "lr is not finite");
+  for (int i = 0; i < count; ++i) {
+    const TensorInfo& ti = ctx->tensors[first + i];
+    galore_status s = check_step_tensor(ctx, ti, W[i], "W", i);
+    if (s) return s;
+    s = check_step_tensor(ctx, ti, G[i], "G", i);
+    if (s) return s;
+  }
+  // Refresh branch of Algorithm 2: t mod T == 0, on this step's gradient, before projecting.
+  if (ctx->hp.auto_refresh) {
+    std::vector<int> due;
+    for (int i = 0; i < count; ++i)
+      if (ctx->tensors[first + i].t % ctx->hp.update_gap == 0) due.push_back(i);
+    if (!due.empty()) {
+      galore_status s = run_refresh(ctx, G, first, due);
+      if (s) return s;
+    }
+  }
+  int pos = 0;
+  while (pos < count) {
+    std::vector<StepItem> items;
+    size_t used = 0;
+    while (pos < count && (int)items.size() < kMaxGroup) {
+      const TensorInfo& ti = ctx->tensors[first + pos];
+      const size_t need = step_need(ti.ldim, ctx->hp.rank, ti.dt);
+      if (!items.empty() && used + need > ctx->ws_bytes) break;
+      items.push_back(StepItem{first + pos, &W[pos], &G[pos], nullptr, nullptr});
+      used += need;
+      ++pos;
+    }
+    galore_status s = run_step_chunk(ctx, items, lr);
+    if (s) return s;
+  }
+  for (int i = 0; i < count; ++i) ctx->tensors[first + i].t += 1;
+  return GALORE_OK;
+}
+
+galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, int32_t first, int32_t count) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  const int n = (int)ctx->tensors.size();
+  if (first < 0 || count < 0 || first > n || count > n - first)
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "range [%d, %d+%d) outside the %d tensors", first, first, count, n);
+  if (count == 0) return GALORE_OK;
+  if (!G) return fail(ctx, GALORE_ERR_INVALID_ARG, "G is NULL");
+  std::vector<int> all(count);
+  for (int i = 0; i < count; ++i) {
+    galore_status s = check_step_tensor(ctx, ctx->tensors[first + i], G[i], "G", i);
+    if (s) return s;
+    all[i] = i;
+  }
+  return run_refresh(ctx, G, first, all);
+}
+
+galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t) {
+  if (!ctx || !t) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx or t is NULL");
+  if (tensor < 0 || tensor >= (int)ctx->tensors.size())
+    return fail(nullptr, GALORE_ERR_INVALID_ARG, "tensor index %d out of range", tensor);
+  *t = ctx->tensors[tensor].t;
+  return GALORE_OK;
+}
+
+galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  if (tensor < 0 || tensor >= (int)ctx->tensors.size())
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "tensor index %d out of range", tensor);
+  if (t < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "step counter must be >= 0");
+  ctx->tensors[tensor].t = t;
+  return GALORE_OK;
+}
+
+const char* galore_last_error(const galore_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
+
+void galore_destroy(galore_ctx* ctx) { delete ctx; }
+
+// ---- stateless stage calls ---------------------------------------------------------------------
+
+galore_status galore_project(const galore_tensor* proj, const galore_tensor* G, const galore_tensor* R, void* hip_stream) {
+  if (!proj || !G || !R) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+  galore_status s;
+  if ((s = check_matrix(nullptr, *proj, "proj", 0, true)) || (s = check_matrix(nullptr, *G, "G", 0, true)) ||
+      (s = check_matrix(nullptr, *R, "R", 0, true)))
+    return s;
+  if (proj->dtype != G->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj and G dtypes differ");
+  if (R->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "R must be fp32");
+  const bool left = G->rows <= G->cols;
+  const int64_t r = proj->cols;
+  if (r > (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
+  if (proj->rows != (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj rows must equal the short side of G");
+  if (R->rows != (left ? r : G->rows) || R->cols != (left ? G->cols : r))
+    return fail(nullptr, GALORE_ERR_SHAPE, "R has the wrong shape");
+  GemmGroup g{};
+  g.count = 1;
+  GemmProblem& p = g.p[0];
+  if (left) {
+    p.A = proj->data; p.lda = (int)proj->ld; p.B = G->data; p.ldb = (int)G->ld;
+    p.M = (int)r; p.N = (int)G->cols; p.K = (int)G->rows;
+  } else {
+    p.A = G->data; p.lda = (int)G->ld; p.B = proj->data; p.ldb = (int)proj->ld;
+    p.M = (int)G->rows; p.N = (int)r; p.K = (int)G->cols;
+  }
+  p.C = R->data; p.ldc = (int)R->ld;
+  hipError_t e = launch_gemm_group(g, (DType)G->dtype, !left, false, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "projection GEMM launch");
+}
+
+galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V, const galore_tensor* N,
+                          float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
+  if (!R || !M || !V || !N) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+  const galore_tensor* all[4] = {R, M, V, N};
+  const char* names[4] = {"R", "M", "V", "N"};
+  for (int i = 0; i < 4; ++i) {
+    galore_status s = check_matrix(nullptr, *all[i], names[i], 0, true);
+    if (s) return s;
+    if (all[i]->rows != R->rows || all[i]->cols != R->cols || all[i]->ld != all[i]->cols)
+      return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense with R's shape", names[i]);
+    if (i < 3 && all[i]->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "%s must be fp32", names[i]);
+    if (reinterpret_cast<uintptr_t>(all[i]->data) & 15) return fail(nullptr, GALORE_ERR_ALIGN, "%s must be 16-byte aligned", names[i]);
+  }
+  if (k < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "k must be >= 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+    return fail(nullptr, GALORE_ERR_INVALID_ARG, "betas / eps out of range");
+  AdamGroup g{};
+  g.count = 1; g.beta1 = beta1; g.beta2 = beta2; g.eps = eps;
+  AdamProblem& p = g.p[0];
+  p.R = static_cast<const float*>(R->data); p.M = static_cast<float*>(M->data); p.V = static_cast<float*>(V->data);
+  p.N = N->data; p.count = R->rows * R->cols;
+  p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
+  p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
+  hipError_t e = launch_adam_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "Adam launch");
+}
+
+galore_status galore_project_back(const galore_tensor* proj, const galore_tensor* N, const galore_tensor* W, float lr,
+                                  float scale, float weight_decay, void* hip_stream) {
+  if (!proj || !N || !W) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+  galore_status s;
+  if ((s = check_matrix(nullptr, *proj, "proj", 0, true)) || (s = check_matrix(nullptr, *N, "N", 0, true)) ||
+      (s = check_matrix(nullptr, *W, "W", 0, true)))
+    return s;
+  if (proj->dtype != W->dtype || N->dtype != W->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj, N and W dtypes must agree");
+  const bool left = W->rows <= W->cols;
+  const int64_t r = proj->cols;
+  if (r > (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
+  if (proj->rows != (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj rows must equal the short side of W");
+  if (N->rows != (left ? r : W->rows) || N->cols != (left ? W->cols : r))
+    return fail(nullptr, GALORE_ERR_SHAPE, "N has the wrong shape");
+  GemmGroup g{};
+  g.count = 1;
+  GemmProblem& p = g.p[0];
+  if (left) {
+    p.A = proj->data; p.lda = (int)proj->ld; p.B = N->data; p.ldb = (int)N->ld;
+  } else {
+    p.A = N->data; p.lda = (int)N->ld; p.B = proj->data; p.ldb = (int)proj->ld;
+  }
+  p.M = (int)W->rows; p.N = (int)W->cols; p.K = (int)r;
+  p.C = W->data; p.ldc = (int)W->ld;
+  p.s0 = 1.f - lr * weight_decay;
+  p.s1 = lr * scale;
+  hipError_t e = launch_gemm_group(g, (DType)W->dtype, true, !left, Epilogue::ApplyW, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "back-projection GEMM launch");
+}
+
+}  // extern "C"

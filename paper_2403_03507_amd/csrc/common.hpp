@@ -1,0 +1,71 @@
+// Shared declarations of the GaLore HIP library (gfx950 only): grouped-launch
+// descriptors passed by value as kernel arguments, and the host launchers the C ABI calls.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace galore {
+
+constexpr int kMaxGroup = 16;  // problems per grouped launch (descriptor table lives in kernarg)
+
+enum class DType : int32_t { F32 = 0, BF16 = 1 };
+
+inline size_t dtype_size(DType d) { return d == DType::F32 ? 4 : 2; }
+
+// ---- grouped GEMM ------------------------------------------------------------------------
+// C[M x N] (+epilogue) = A * B, fp32 accumulate.  A is read as a_kcontig ? [M][K] : [K][M],
+// B as b_kcontig ? [N][K] : [K][N]; lda/ldb are the strides (elements) of the outer index.
+struct GemmProblem {
+  const void* A;
+  const void* B;
+  void* C;        // output / in-place operand of the epilogue
+  void* aux0;     // epilogue extra pointers
+  void* aux1;
+  void* aux2;
+  int32_t M, N, K;
+  int32_t lda, ldb, ldc;
+  int32_t tile_begin;  // first block of this problem in the launch
+  int32_t tiles_m;     // tiles along M (tile id within problem: tm fastest)
+  float s0, s1, s2, s3;  // epilogue scalars
+};
+
+struct GemmGroup {
+  int32_t count;
+  int32_t total_tiles;
+  GemmProblem p[kMaxGroup];
+};
+
+enum class Epilogue : int32_t {
+  StoreF32 = 0,   // C (fp32) = acc
+  ApplyW = 1,     // C (T) = s0 * C - s1 * acc            (weight update, s0 = 1 - lr*wd, s1 = lr*alpha)
+  StoreSymF32 = 2 // C (fp32) = acc, written to (i,j) and (j,i); tiles with tm > tn skipped (M == N)
+};
+
+// Launch one grouped GEMM on `stream`.  All problems share dtype / layouts / epilogue.
+// Host fills everything except tile_begin / tiles_m / total_tiles.
+hipError_t launch_gemm_group(GemmGroup& g, DType dt, bool a_kcontig, bool b_kcontig, Epilogue epi,
+                             hipStream_t stream);
+
+// ---- grouped low-rank Adam -----------------------------------------------------------------
+struct AdamProblem {
+  const float* R;
+  float* M;
+  float* V;
+  void* N;        // fp32 or bf16
+  int64_t count;
+  float inv_c1;   // 1 / (1 - beta1^k)
+  float inv_c2;   // 1 / (1 - beta2^k)
+};
+
+struct AdamGroup {
+  int32_t count;
+  float beta1, beta2, eps;
+  AdamProblem p[kMaxGroup];
+};
+
+hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream);
+
+// ---- small utilities -----------------------------------------------------------------------
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
+
+}  // namespace galore

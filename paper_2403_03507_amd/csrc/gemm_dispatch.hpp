@@ -1,0 +1,43 @@
+// Layout / epilogue dispatch shared by the per-dtype GEMM translation units.
+#pragma once
+#include "gemm_mfma.hpp"
+
+namespace galore {
+
+using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
+
+template <class T, bool AK, bool BKC, Epilogue EPI>
+inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
+  plan_tiles<CfgDefault>(g);
+  if (g.total_tiles == 0) return hipSuccess;
+  if (group_is_aligned<T>(g, AK, BKC))
+    return launch_gemm_instance<T, AK, BKC, true, EPI, CfgDefault>(g, stream);
+  return launch_gemm_instance<T, AK, BKC, false, EPI, CfgDefault>(g, stream);
+}
+
+// The layout / epilogue combinations the library uses:
+//   (X,X) Store   : R = P^T G            ; fp32 also Q^T Z of the refresh
+//   (K,X) Store   : R = G Q              ; fp32 also C Q and Q S of the refresh
+//   (K,X) ApplyW  : W -= P N
+//   (K,K) ApplyW  : W -= N Q^T
+//   (K,K) StoreSym: C = G G^T
+//   (X,X) StoreSym: C = G^T G
+template <class T>
+inline hipError_t launch_gemm_typed(GemmGroup& g, bool ak, bool bk, Epilogue epi, hipStream_t stream) {
+  if (epi == Epilogue::StoreF32) {
+    if (!ak && !bk) return launch_gemm_layout<T, false, false, Epilogue::StoreF32>(g, stream);
+    if (ak && !bk) return launch_gemm_layout<T, true, false, Epilogue::StoreF32>(g, stream);
+  } else if (epi == Epilogue::ApplyW) {
+    if (ak && !bk) return launch_gemm_layout<T, true, false, Epilogue::ApplyW>(g, stream);
+    if (ak && bk) return launch_gemm_layout<T, true, true, Epilogue::ApplyW>(g, stream);
+  } else if (epi == Epilogue::StoreSymF32) {
+    if (ak && bk) return launch_gemm_layout<T, true, true, Epilogue::StoreSymF32>(g, stream);
+    if (!ak && !bk) return launch_gemm_layout<T, false, false, Epilogue::StoreSymF32>(g, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm_bf16(GemmGroup& g, bool ak, bool bk, Epilogue epi, hipStream_t stream);
+hipError_t launch_gemm_f32(GemmGroup& g, bool ak, bool bk, Epilogue epi, hipStream_t stream);
+
+}  // namespace galore

@@ -1,0 +1,26 @@
+// Subspace refresh (Algorithm 2, refresh branch): host interface used by the C ABI.
+#pragma once
+#include "common.hpp"
+#include <vector>
+
+namespace galore {
+
+struct RefreshItem {
+  const void* G;      // gradient, rows x cols, dtype dt, leading dimension ldg
+  int64_t ldg;
+  int64_t rows, cols;
+  DType dt;
+  void* proj;         // output projector (short side x r), dtype dt, leading dimension ldp
+  int64_t ldp;
+  unsigned char* ws;  // refresh_workspace_bytes(short side, r) bytes, 256-byte aligned
+  uint64_t seed;      // seed of the Gaussian start block
+};
+
+// Scratch one tensor's refresh needs (Gram matrix, two iteration blocks, Rayleigh-Ritz
+// matrices, reflector data).
+size_t refresh_workspace_bytes(int64_t kdim, int64_t r);
+
+// Recompute the projectors of up to kMaxGroup tensors with grouped launches on `stream`.
+hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, hipStream_t stream);
+
+}  // namespace galore

@@ -1,0 +1,31 @@
+"""Shared helpers for the parity tests (no method arithmetic)."""
+import numpy as np
+import torch
+
+# Per-step gates on W, M, V (relative Frobenius error against the fp64 oracle).
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def to64(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def relF(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    d = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / (d if d > 0 else 1.0))
+
+
+def dev(a, dtype, device="cuda"):
+    """fp64 numpy (already representable in dtype) -> device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(TDT[dtype] if isinstance(dtype, str) else dtype).to(device).contiguous()
+
+
+def strided(t, pad):
+    """Copy of t living inside a wider buffer, so its leading dimension is cols + pad."""
+    buf = torch.zeros(t.shape[0], t.shape[1] + pad, dtype=t.dtype, device=t.device)
+    view = buf[:, : t.shape[1]]
+    view.copy_(t)
+    return view

@@ -1,0 +1,121 @@
+"""C-ABI checks that need no GPU: the library loads, exports what the header declares, and
+rejects bad arguments on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from conftest import ROOT
+from paper_2403_03507_amd import binding as gb
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "galore.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(galore_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = gb.lib()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(gb.EXPORTS) == names
+
+
+def test_status_strings():
+    L = gb.lib()
+    assert L.galore_status_string(0) == b"ok"
+    assert L.galore_status_string(4) == b"rank out of range"
+
+
+def _hp(**kw):
+    return gb.make_hparams(kw.pop("rank", 4), **kw)
+
+
+def _fake_state(k, r, l, left=True, dtype=gb.GALORE_F32, ptr=4096):
+    mshape = (r, l) if left else (l, r)
+    return gb.galore_state(gb.galore_tensor(ptr, k, r, r, dtype),
+                           gb.galore_tensor(ptr, mshape[0], mshape[1], mshape[1], gb.GALORE_F32),
+                           gb.galore_tensor(ptr, mshape[0], mshape[1], mshape[1], gb.GALORE_F32))
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(gb.GaloreError) as e:
+        fn(*a, **k)
+    return e.value.status
+
+
+def test_workspace_bytes_formula_and_errors():
+    w = [gb.shape_desc(8, 16, torch.float32)]
+    need = gb.galore_workspace_bytes(_hp(rank=4), w)
+    assert need >= 4 * 16 * 4 * 2 and need % 256 == 0
+    assert _status(gb.galore_workspace_bytes, _hp(rank=9), w) == 4          # rank > min(m, n)
+    assert _status(gb.galore_workspace_bytes, _hp(rank=0), w) == 4
+    assert _status(gb.galore_workspace_bytes, _hp(update_gap=0), w) == 1
+    assert _status(gb.galore_workspace_bytes, _hp(beta1=1.0), w) == 1
+    assert _status(gb.galore_workspace_bytes, _hp(refresh_iters=0), w) == 1
+    bad = [gb.galore_tensor(None, 8, 16, 12, 0)]                               # ld < cols
+    assert _status(gb.galore_workspace_bytes, _hp(), bad) == 2
+    bad = [gb.galore_tensor(None, 8, 16, 16, 7)]                               # unknown dtype
+    assert _status(gb.galore_workspace_bytes, _hp(), bad) == 3
+
+
+def test_init_validation_happens_before_any_device_work():
+    hp = _hp(rank=4)
+    w = [gb.shape_desc(8, 16, torch.float32)]
+    ok_state = _fake_state(8, 4, 16)
+    ws = 1 << 20
+    # NULL workspace, misaligned workspace, too-small workspace
+    assert _status(gb.galore_init, hp, w, [ok_state], 0, ws, stream=ctypes.c_void_p(None)) == 1
+    assert _status(gb.galore_init, hp, w, [ok_state], 4096 + 8, ws, stream=ctypes.c_void_p(None)) == 5
+    assert _status(gb.galore_init, hp, w, [ok_state], 4096, 256, stream=ctypes.c_void_p(None)) == 6
+    # projector of the wrong shape / dtype
+    s = _fake_state(8, 4, 16); s.proj.rows = 16
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
+    s = _fake_state(8, 4, 16, dtype=gb.GALORE_BF16)
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 3
+    # moments: wrong orientation, wrong dtype, misaligned, NULL
+    s = _fake_state(8, 4, 16, left=False)
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
+    s = _fake_state(8, 4, 16); s.m.dtype = gb.GALORE_BF16
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 3
+    s = _fake_state(8, 4, 16); s.v.data = 4096 + 4
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 5
+    s = _fake_state(8, 4, 16); s.m.data = None
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 1
+    # tall tensor: projector lives on the column side
+    wt = [gb.shape_desc(16, 8, torch.float32)]
+    s = _fake_state(8, 4, 16, left=True)   # moments given as r x rows: wrong for a RIGHT tensor
+    assert _status(gb.galore_init, hp, wt, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
+    assert "moments" in gb.lib().galore_last_error(None).decode()
+
+
+def test_stateless_calls_validate_shapes():
+    L = gb.lib()
+    T = gb.galore_tensor
+    P = T(4096, 8, 4, 4, 0); G = T(4096, 8, 16, 16, 0); R = T(4096, 4, 16, 16, 0)
+    bad_R = T(4096, 16, 4, 4, 0)
+    assert L.galore_project(ctypes.byref(P), ctypes.byref(G), ctypes.byref(bad_R), None) == 2
+    Gb = T(4096, 8, 16, 16, 1)
+    assert L.galore_project(ctypes.byref(P), ctypes.byref(Gb), ctypes.byref(R), None) == 3
+    assert L.galore_project(None, ctypes.byref(G), ctypes.byref(R), None) == 1
+    P9 = T(4096, 8, 9, 9, 0)
+    assert L.galore_project(ctypes.byref(P9), ctypes.byref(G), ctypes.byref(R), None) == 4
+    M = T(4096, 4, 16, 16, 0)
+    assert L.galore_adam(ctypes.byref(R), ctypes.byref(M), ctypes.byref(M), ctypes.byref(M), 0.9, 0.999, 1e-8, 0, None) == 1
+    Mb = T(4096, 4, 16, 16, 1)
+    assert L.galore_adam(ctypes.byref(R), ctypes.byref(Mb), ctypes.byref(M), ctypes.byref(M), 0.9, 0.999, 1e-8, 1, None) == 3
+    W = T(4096, 8, 16, 16, 0); N = T(4096, 16, 4, 4, 0)
+    assert L.galore_project_back(ctypes.byref(P), ctypes.byref(N), ctypes.byref(W), 1e-3, 0.25, 0.0, None) == 2
+
+
+def test_null_context_calls():
+    L = gb.lib()
+    assert L.galore_step(None, None, None, 0, 0, 0.0) == 1
+    assert L.galore_refresh_subspace(None, None, 0, 0) == 1
+    assert L.galore_set_step(None, 0, 0) == 1
+    L.galore_destroy(None)

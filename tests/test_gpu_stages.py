@@ -1,0 +1,155 @@
+"""GPU parity of the three per-step stages against the fp64 oracle, element by element.
+
+Stages are called through the C ABI (galore_project / galore_adam / galore_project_back), which
+run the same kernels galore_step runs.  Shapes span several 128x128 tiles, ragged tails, odd
+sizes that force the unaligned load path, padded leading dimensions and both orientations.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TDT, TOL, dev, relF, strided, to64
+from oracle import galore_oracle as orc
+from paper_2403_03507_amd import binding as gb
+from paper_2403_03507_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [  # (m, n, r)
+    (512, 1376, 128),   # 60M gate/up
+    (1376, 512, 128),   # 60M down (RIGHT)
+    (512, 512, 128),
+    (256, 300, 96),     # ragged n, not a multiple of 8
+    (130, 257, 33),     # odd everything: unaligned path, partial tiles in every dimension
+    (257, 130, 33),     # same, RIGHT
+    (64, 64, 64),       # r = m = n, single partial tile
+    (1, 5, 1),          # degenerate: one row
+    (300, 1000, 300),   # r = m
+]
+
+
+def _inputs(m, n, r, dtype, seed):
+    k = min(m, n)
+    G = wl.GradientSource(m, n, seed, "lowrank", dtype=dtype, signal_rank=min(8, k), noise=0.05).grad(0)
+    P = wl.random_orthonormal(k, r, seed + 1).to(TDT[dtype])
+    W = wl.make_weight(m, n, seed + 2, dtype)
+    return W, G, P
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_project(shape, dtype):
+    m, n, r = shape
+    _, G, P = _inputs(m, n, r, dtype, 11)
+    R_ref = orc.project(to64(P), to64(G))
+    R = torch.full(R_ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    gb.galore_project(P.cuda(), G.cuda(), R)
+    torch.cuda.synchronize()
+    assert relF(to64(R), R_ref) <= 1e-5
+    scale = np.abs(R_ref).max() + 1e-30
+    assert np.abs(to64(R) - R_ref).max() <= 2e-5 * scale + 1e-6 * np.sqrt(max(m, n))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pad", [8, 3])
+def test_project_with_padded_leading_dimensions(dtype, pad):
+    for (m, n, r) in [(200, 328, 40), (328, 200, 40)]:
+        _, G, P = _inputs(m, n, r, dtype, 12)
+        R_ref = orc.project(to64(P), to64(G))
+        R = torch.empty(R_ref.shape, dtype=torch.float32, device="cuda")
+        gb.galore_project(strided(P.cuda(), pad), strided(G.cuda(), pad), R)
+        torch.cuda.synchronize()
+        assert relF(to64(R), R_ref) <= 1e-5
+
+
+@pytest.mark.parametrize("n_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("count_shape", [(128, 1376), (33, 257), (1, 3), (7, 1), (256, 4096)])
+def test_adam(count_shape, n_dtype):
+    rng = np.random.default_rng(5)
+    shape = count_shape
+    M = np.zeros(shape); V = np.zeros(shape)
+    Md = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    Vd = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    Nd = torch.empty(shape, dtype=TDT[n_dtype], device="cuda")
+    for k in range(1, 5):
+        R32 = (rng.standard_normal(shape) * 10.0 ** rng.integers(-4, 1, shape)).astype(np.float32)
+        N_ref = orc.adam(R32.astype(np.float64), M, V, 0.9, 0.999, 1e-8, k)
+        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
+        torch.cuda.synchronize()
+        assert relF(to64(Md), M) <= 1e-6 and relF(to64(Vd), V) <= 1e-6
+        np.testing.assert_allclose(to64(Md), M, rtol=2e-6, atol=1e-30)
+        np.testing.assert_allclose(to64(Vd), V, rtol=2e-6, atol=1e-30)
+        if n_dtype == "f32":
+            np.testing.assert_allclose(to64(Nd), N_ref, rtol=5e-6, atol=1e-12)
+        else:
+            np.testing.assert_allclose(to64(Nd), N_ref, rtol=2.0 ** -8, atol=1e-12)
+        # oracle state follows fp32 storage, like the device state
+        M[:] = orc.round_storage(M, "f32"); V[:] = orc.round_storage(V, "f32")
+
+
+def test_adam_bias_correction_at_large_k():
+    shape = (16, 64)
+    rng = np.random.default_rng(6)
+    M0 = rng.standard_normal(shape).astype(np.float32); V0 = (rng.standard_normal(shape) ** 2).astype(np.float32)
+    R32 = rng.standard_normal(shape).astype(np.float32)
+    for k in (7, 200, 100000):
+        M = M0.astype(np.float64); V = V0.astype(np.float64)
+        N_ref = orc.adam(R32.astype(np.float64), M, V, 0.9, 0.999, 1e-8, k)
+        Md = torch.from_numpy(M0.copy()).cuda(); Vd = torch.from_numpy(V0.copy()).cuda()
+        Nd = torch.empty(shape, dtype=torch.float32, device="cuda")
+        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
+        np.testing.assert_allclose(to64(Nd), N_ref, rtol=5e-6, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_project_back(shape, dtype):
+    m, n, r = shape
+    W, _, P = _inputs(m, n, r, dtype, 13)
+    rng = np.random.default_rng(14)
+    nshape = (r, n) if m <= n else (m, r)
+    N = torch.from_numpy(rng.uniform(-1, 1, nshape)).to(TDT[dtype])
+    lr, alpha, wd = 1e-2, 0.25, 0.1
+    W_ref = to64(W).copy()
+    orc.apply_update(W_ref, to64(P), to64(N), lr, alpha, wd)
+    Wd = W.cuda().clone()
+    gb.galore_project_back(P.cuda(), N.cuda(), Wd, lr, alpha, wd)
+    torch.cuda.synchronize()
+    assert relF(to64(Wd), W_ref) <= TOL[dtype]
+    if dtype == "f32":
+        np.testing.assert_allclose(to64(Wd), W_ref, rtol=1e-5, atol=1e-7)
+    else:
+        # bf16 storage: every entry within one bf16 ulp of the rounded oracle value
+        W_r = orc.round_storage(W_ref, "bf16")
+        ulp = np.maximum(np.abs(W_r), 2.0 ** -126) * 2.0 ** -7
+        assert np.all(np.abs(to64(Wd) - W_r) <= ulp)
+        assert np.mean(to64(Wd) == W_r) >= 0.98
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_project_back_padded_weight(dtype):
+    for (m, n, r) in [(200, 328, 40), (328, 200, 40)]:
+        W, _, P = _inputs(m, n, r, dtype, 15)
+        rng = np.random.default_rng(16)
+        nshape = (r, n) if m <= n else (m, r)
+        N = torch.from_numpy(rng.uniform(-1, 1, nshape)).to(TDT[dtype])
+        W_ref = to64(W).copy()
+        orc.apply_update(W_ref, to64(P), to64(N), 1e-2, 0.25, 0.0)
+        Wd = strided(W.cuda(), 5)
+        gb.galore_project_back(P.cuda(), N.cuda(), Wd, 1e-2, 0.25, 0.0)
+        torch.cuda.synchronize()
+        assert relF(to64(Wd), W_ref) <= TOL[dtype]
+        assert torch.all(Wd._base[:, n:] == 0)  # padding untouched
+
+
+def test_round_trip_identity_full_rank():
+    # Sec. 3.3: r = min(m, n), identity in place of Adam  =>  P (P^T G) = G.
+    m, n = 96, 200
+    G = wl.GradientSource(m, n, 3, "lowrank", signal_rank=8, noise=0.05).grad(0)
+    P = wl.random_orthonormal(m, m, 4)
+    R = torch.empty(m, n, dtype=torch.float32, device="cuda")
+    gb.galore_project(P.cuda(), G.cuda(), R)
+    W = torch.zeros(m, n, dtype=torch.float32, device="cuda")
+    gb.galore_project_back(P.cuda(), R, W, -1.0, 1.0, 0.0)
+    torch.cuda.synchronize()
+    assert relF(to64(W), to64(G)) <= 1e-5

@@ -1,0 +1,146 @@
+"""GPU parity of whole GaLore steps (galore_init / galore_step) against the fp64 oracle.
+
+The projector is the oracle's (Jacobi SVD, rounded to the storage dtype) and is handed to the
+library by writing state.proj with auto_refresh = 0, so both sides consume identical bits;
+the library's own refresh is checked separately, on the subspace."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TDT, TOL, dev, relF, to64
+from oracle import galore_oracle as orc
+from paper_2403_03507_amd import binding as gb
+from paper_2403_03507_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0, grad_kw=None,
+               chunked=False, workspace_bytes=None):
+    grad_kw = grad_kw or dict(kind="lowrank", signal_rank=32, sigma0=10.0, decay=0.8, noise=0.01)
+    srcs = [wl.GradientSource(m, n, 100 + i, dtype=dtype, **grad_kw) for i, (m, n) in enumerate(shapes)]
+    W0 = [wl.make_weight(m, n, 200 + i, dtype) for i, (m, n) in enumerate(shapes)]
+    oracles = [orc.GaLoreTensor(to64(w), rank, update_gap=update_gap, weight_decay=weight_decay, dtype=dtype)
+               for w in W0]
+    Wd = [w.cuda() for w in W0]
+    opt = gb.GaLore(Wd, rank, update_gap=update_gap, weight_decay=weight_decay, auto_refresh=False,
+                    workspace_bytes=workspace_bytes)
+    worst = dict(W=0.0, M=0.0, V=0.0)
+    for step in range(steps):
+        G = [s.grad(step) for s in srcs]
+        for i, o in enumerate(oracles):
+            if o.t % o.T == 0:
+                o.refresh(to64(G[i]))                      # oracle refresh (Algorithm 2, t mod T == 0)
+                opt.proj[i].copy_(dev(o.proj, dtype))       # same projector bits on the device
+            o.step(to64(G[i]), lr)
+        Gd = [g.cuda() for g in G]
+        if chunked:  # one call per tensor, reverse order (per-layer update during back-propagation)
+            for i in reversed(range(len(shapes))):
+                opt.step([Wd[i]], [Gd[i]], lr, first=i)
+        else:
+            opt.step(Wd, Gd, lr)
+        torch.cuda.synchronize()
+        for i, o in enumerate(oracles):
+            assert opt.get_step(i) == o.t
+            e = dict(W=relF(to64(Wd[i]), o.W), M=relF(to64(opt.M[i]), o.M), V=relF(to64(opt.V[i]), o.V))
+            for k in e:
+                worst[k] = max(worst[k], e[k])
+                assert e[k] <= TOL[dtype], (step, i, k, e[k])
+    opt.close()
+    return worst
+
+
+def test_llama60m_layer_ten_steps_fp32():
+    # configs[0]: one LLaMA-60M layer, fp32, r = 128, T = 5, 10 steps (refresh at t = 0 and 5).
+    c = wl.CONFIGS["llama60m"]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    worst = _run_stack(shapes, "f32", c["rank"], steps=10, update_gap=c["update_gap"])
+    print("worst relF", worst)
+
+
+def test_llama60m_layer_bf16_and_weight_decay():
+    shapes = wl.layer_shapes(512, 1376)[3:]      # o, gate, up, down
+    _run_stack(shapes, "bf16", 128, steps=6, update_gap=3, weight_decay=0.1, lr=1e-2)
+
+
+def test_per_tensor_calls_in_reverse_order_match_one_call():
+    shapes = [(256, 256), (256, 688), (688, 256)]
+    _run_stack(shapes, "f32", 64, steps=4, update_gap=2, chunked=True)
+
+
+def test_small_workspace_forces_several_launch_chunks():
+    shapes = [(256, 256)] * 5 + [(256, 688), (688, 256)]
+    hp = gb.make_hparams(64)
+    one = gb.galore_workspace_bytes(hp, [gb.shape_desc(256, 688, torch.float32)])
+    _run_stack(shapes, "f32", 64, steps=2, update_gap=10, workspace_bytes=one)
+
+
+def test_more_tensors_than_one_group():
+    shapes = [(128, 160)] * 19 + [(160, 128)] * 18   # > 16 per launch group, both orientations
+    _run_stack(shapes, "bf16", 32, steps=2, update_gap=10)
+
+
+def test_ragged_and_odd_shapes():
+    shapes = [(130, 257), (257, 130), (96, 96), (100, 5461 // 8)]
+    _run_stack(shapes, "bf16", 33, steps=3, update_gap=2)
+    _run_stack(shapes, "f32", 33, steps=3, update_gap=2)
+
+
+def test_identity_projector_is_scaled_adam_on_device():
+    # r = m, P = I: the device trajectory must equal plain Adam with step lr*alpha (library Adam, fp64).
+    m, n = 64, 192
+    W0 = wl.make_weight(m, n, 7, "f32")
+    src = wl.GradientSource(m, n, 8, "lowrank", signal_rank=8, noise=0.05)
+    Wd = [W0.cuda()]
+    opt = gb.GaLore(Wd, m, auto_refresh=False)
+    opt.proj[0].copy_(torch.eye(m))
+    p = W0.to(torch.float64).clone().requires_grad_(True)
+    ref = torch.optim.Adam([p], lr=1e-3 * 0.25, betas=(0.9, 0.999), eps=1e-8)
+    for step in range(5):
+        G = src.grad(step)
+        p.grad = G.to(torch.float64); ref.step()
+        opt.step(Wd, [G.cuda()], 1e-3)
+    torch.cuda.synchronize()
+    assert relF(to64(Wd[0]), p.detach().numpy()) <= 1e-5
+
+
+def test_determinism_bitwise():
+    shapes = [(256, 688), (688, 256)]
+    outs = []
+    for _ in range(2):
+        W0 = [wl.make_weight(m, n, 300 + i, "bf16").cuda() for i, (m, n) in enumerate(shapes)]
+        opt = gb.GaLore(W0, 64, auto_refresh=False)
+        for i, (m, n) in enumerate(shapes):
+            opt.proj[i].copy_(wl.random_orthonormal(min(m, n), 64, 400 + i).to(torch.bfloat16))
+        for step in range(3):
+            G = [wl.GradientSource(m, n, 500 + i, "lowrank", dtype="bf16").grad(step).cuda() for i, (m, n) in enumerate(shapes)]
+            opt.step(W0, G, 1e-2)
+        torch.cuda.synchronize()
+        outs.append([w.clone() for w in W0] + [x.clone() for x in opt.M + opt.V])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_checkpoint_resume_is_bit_identical():
+    m, n, r = 256, 688, 64
+    src = wl.GradientSource(m, n, 9, "lowrank", dtype="bf16")
+    P = wl.random_orthonormal(m, r, 10).to(torch.bfloat16)
+
+    def run(split):
+        W = [wl.make_weight(m, n, 11, "bf16").cuda()]
+        opt = gb.GaLore(W, r, auto_refresh=False)
+        opt.proj[0].copy_(P)
+        for step in range(4):
+            if step == split:  # save -> new context -> load
+                saved = (opt.M[0].clone(), opt.V[0].clone(), opt.proj[0].clone(), opt.get_step(0))
+                opt.close()
+                opt = gb.GaLore(W, r, auto_refresh=False)
+                opt.M[0].copy_(saved[0]); opt.V[0].copy_(saved[1]); opt.proj[0].copy_(saved[2])
+                opt.set_step(0, saved[3])
+            opt.step(W, [src.grad(step).cuda()], 1e-2)
+        torch.cuda.synchronize()
+        return W[0].clone(), opt.M[0].clone(), opt.V[0].clone()
+
+    a, b = run(None), run(2)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
