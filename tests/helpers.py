@@ -29,3 +29,8 @@ def strided(t, pad):
     view = buf[:, : t.shape[1]]
     view.copy_(t)
     return view
+
+
+def f32(x):
+    """The value the C ABI receives for a float hyper-parameter; the oracle is given the same number."""
+    return float(np.float32(x))

@@ -8,7 +8,9 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import TDT, TOL, dev, relF, strided, to64
+from helpers import TDT, TOL, dev, f32, relF, strided, to64
+
+B1, B2, EPS = f32(0.9), f32(0.999), f32(1e-8)
 from oracle import galore_oracle as orc
 from paper_2403_03507_amd import binding as gb
 from paper_2403_03507_amd import workloads as wl
@@ -71,18 +73,20 @@ def test_adam(count_shape, n_dtype):
     Md = torch.zeros(shape, dtype=torch.float32, device="cuda")
     Vd = torch.zeros(shape, dtype=torch.float32, device="cuda")
     Nd = torch.empty(shape, dtype=TDT[n_dtype], device="cuda")
+    big = np.zeros(shape)
     for k in range(1, 5):
         R32 = (rng.standard_normal(shape) * 10.0 ** rng.integers(-4, 1, shape)).astype(np.float32)
-        N_ref = orc.adam(R32.astype(np.float64), M, V, 0.9, 0.999, 1e-8, k)
+        big = np.maximum(big, np.abs(R32))  # running size of the terms that entered M
+        N_ref = orc.adam(R32.astype(np.float64), M, V, B1, B2, EPS, k)
         gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
         torch.cuda.synchronize()
         assert relF(to64(Md), M) <= 1e-6 and relF(to64(Vd), V) <= 1e-6
-        np.testing.assert_allclose(to64(Md), M, rtol=2e-6, atol=1e-30)
+        # M is a sum that can cancel: bound the error by the size of the terms, not of the result
+        assert np.all(np.abs(to64(Md) - M) <= 3e-7 * big + 1e-30)
         np.testing.assert_allclose(to64(Vd), V, rtol=2e-6, atol=1e-30)
-        if n_dtype == "f32":
-            np.testing.assert_allclose(to64(Nd), N_ref, rtol=5e-6, atol=1e-12)
-        else:
-            np.testing.assert_allclose(to64(Nd), N_ref, rtol=2.0 ** -8, atol=1e-12)
+        rel = 5e-6 if n_dtype == "f32" else 2.0 ** -8
+        assert relF(to64(Nd), N_ref) <= rel
+        assert np.all(np.abs(to64(Nd) - N_ref) <= rel * np.abs(N_ref) + 1e-5)
         # oracle state follows fp32 storage, like the device state
         M[:] = orc.round_storage(M, "f32"); V[:] = orc.round_storage(V, "f32")
 
@@ -94,7 +98,7 @@ def test_adam_bias_correction_at_large_k():
     R32 = rng.standard_normal(shape).astype(np.float32)
     for k in (7, 200, 100000):
         M = M0.astype(np.float64); V = V0.astype(np.float64)
-        N_ref = orc.adam(R32.astype(np.float64), M, V, 0.9, 0.999, 1e-8, k)
+        N_ref = orc.adam(R32.astype(np.float64), M, V, B1, B2, EPS, k)
         Md = torch.from_numpy(M0.copy()).cuda(); Vd = torch.from_numpy(V0.copy()).cuda()
         Nd = torch.empty(shape, dtype=torch.float32, device="cuda")
         gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
@@ -109,7 +113,7 @@ def test_project_back(shape, dtype):
     rng = np.random.default_rng(14)
     nshape = (r, n) if m <= n else (m, r)
     N = torch.from_numpy(rng.uniform(-1, 1, nshape)).to(TDT[dtype])
-    lr, alpha, wd = 1e-2, 0.25, 0.1
+    lr, alpha, wd = f32(1e-2), 0.25, f32(0.1)
     W_ref = to64(W).copy()
     orc.apply_update(W_ref, to64(P), to64(N), lr, alpha, wd)
     Wd = W.cuda().clone()
@@ -134,7 +138,7 @@ def test_project_back_padded_weight(dtype):
         nshape = (r, n) if m <= n else (m, r)
         N = torch.from_numpy(rng.uniform(-1, 1, nshape)).to(TDT[dtype])
         W_ref = to64(W).copy()
-        orc.apply_update(W_ref, to64(P), to64(N), 1e-2, 0.25, 0.0)
+        orc.apply_update(W_ref, to64(P), to64(N), f32(1e-2), 0.25, 0.0)
         Wd = strided(W.cuda(), 5)
         gb.galore_project_back(P.cuda(), N.cuda(), Wd, 1e-2, 0.25, 0.0)
         torch.cuda.synchronize()

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import TDT, TOL, dev, relF, to64
+from helpers import TDT, TOL, dev, f32, relF, to64
 from oracle import galore_oracle as orc
 from paper_2403_03507_amd import binding as gb
 from paper_2403_03507_amd import workloads as wl
@@ -20,8 +20,10 @@ def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0
     grad_kw = grad_kw or dict(kind="lowrank", signal_rank=32, sigma0=10.0, decay=0.8, noise=0.01)
     srcs = [wl.GradientSource(m, n, 100 + i, dtype=dtype, **grad_kw) for i, (m, n) in enumerate(shapes)]
     W0 = [wl.make_weight(m, n, 200 + i, dtype) for i, (m, n) in enumerate(shapes)]
-    oracles = [orc.GaLoreTensor(to64(w), rank, update_gap=update_gap, weight_decay=weight_decay, dtype=dtype)
+    oracles = [orc.GaLoreTensor(to64(w), rank, update_gap=update_gap, scale=f32(0.25), beta1=f32(0.9),
+                                beta2=f32(0.999), eps=f32(1e-8), weight_decay=f32(weight_decay), dtype=dtype)
                for w in W0]
+    lr = f32(lr)
     Wd = [w.cuda() for w in W0]
     opt = gb.GaLore(Wd, rank, update_gap=update_gap, weight_decay=weight_decay, auto_refresh=False,
                     workspace_bytes=workspace_bytes)
@@ -95,7 +97,7 @@ def test_identity_projector_is_scaled_adam_on_device():
     opt = gb.GaLore(Wd, m, auto_refresh=False)
     opt.proj[0].copy_(torch.eye(m))
     p = W0.to(torch.float64).clone().requires_grad_(True)
-    ref = torch.optim.Adam([p], lr=1e-3 * 0.25, betas=(0.9, 0.999), eps=1e-8)
+    ref = torch.optim.Adam([p], lr=f32(1e-3) * 0.25, betas=(f32(0.9), f32(0.999)), eps=f32(1e-8))
     for step in range(5):
         G = src.grad(step)
         p.grad = G.to(torch.float64); ref.step()
