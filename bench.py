@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the GaLore optimizer step on one MI355X.
+
+A "step" is one pass of the whole hot path (project, low-rank Adam, project back + apply; the
+subspace refresh falls on step 0 and is timed apart) over every GaLore matrix of a synthetic
+LLaMA-7B-shaped stack (32 layers x {4x 4096x4096, 2x 4096x11008, 11008x4096}, bf16 W/G, fp32
+M/V, r = 1024), called one layer at a time in backward order, the way a per-layer weight update
+during back-propagation calls it.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="llama7b")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
+    ap.add_argument("--refresh-iters", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (nothing here uses a "
+              "second GPU)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2403_03507_amd import binding as gb
+    from paper_2403_03507_amd import workloads as wl
+    if not os.path.exists(gb.LIB_PATH):
+        from paper_2403_03507_amd import build as lib_build
+        lib_build.build()
+    gb.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    cfg = dict(wl.CONFIGS[args.config])
+    if args.layers is not None:
+        cfg["layers"] = args.layers
+    L, d, f, r = cfg["layers"], cfg["d"], cfg["f"], cfg["rank"]
+    dtype = cfg["dtype"]
+    tdt = wl.TORCH_DTYPE[dtype]
+    shapes = wl.layer_shapes(d, f)
+    n_per_layer = len(shapes)
+    lr = 1e-3
+
+    # ---- synthetic inputs, resident in HBM before anything is timed ------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    W = []
+    for _ in range(L):
+        for (m, n) in shapes:
+            W.append((torch.randn(m, n, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(tdt))
+    POOL = 4  # gradient layer-sets cycled through, so no step re-reads a cache-warm gradient
+    srcs = wl.make_sources(cfg, seed=7, device=dev, layers=1)
+    Gpool = [[s.grad(slot) for s in srcs] for slot in range(POOL)]
+    del srcs
+    torch.cuda.synchronize()
+
+    opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True)
+    w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
+    g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
+
+    def one_step(step_index):
+        for l in reversed(range(L)):  # backward order, one layer per call
+            gb.galore_step(opt.ctx, w_descs[l], g_descs[(l + step_index) % POOL], n_per_layer * l, n_per_layer, lr)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    # step 0: t mod T == 0 for every tensor, so it carries the subspace refresh
+    gb.galore_profile_start(opt.ctx)
+    first_ms = timed(lambda: one_step(0))
+    prof0 = gb.galore_profile_stop(opt.ctx)
+    refresh_ms = prof0["refresh"][0]
+    for w in range(1, max(args.warmup, 1)):
+        one_step(w)
+    K = args.steps
+    base = max(args.warmup, 1)
+    total_ms = timed(lambda: [one_step(base + i) for i in range(K)])
+    ms_per_step = total_ms / K
+
+    # same K steps again with every kernel group bracketed by HIP events on the library's stream
+    gb.galore_profile_start(opt.ctx)
+    prof_total_ms = timed(lambda: [one_step(base + K + i) for i in range(K)])
+    prof = gb.galore_profile_stop(opt.ctx)
+
+    # ---- roofline of the dominant kernel -----------------------------------------------------------
+    left = [(m, n) for (m, n) in shapes if m <= n]
+    right = [(m, n) for (m, n) in shapes if m > n]
+    flops = {"project_left": sum(2.0 * m * n * r for m, n in left), "project_right": sum(2.0 * m * n * r for m, n in right)}
+    flops["back_left"], flops["back_right"] = flops["project_left"], flops["project_right"]
+    sN = 2 if dtype == "bf16" else 4
+    adam_bytes = sum(r * max(m, n) * (4 * 5 + sN) for m, n in shapes)  # read R, M, V; write M, V, N
+    stage_ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}        # average duration of one launch
+    gemm_stages = ["project_left", "project_right", "back_left", "back_right"]
+    dominant = max(gemm_stages + ["adam"], key=lambda k: prof[k][0])
+    if dominant == "adam":
+        achieved = adam_bytes / (stage_ms["adam"] * 1e-3) / 1e9
+        roofline = {"kernel": "adam_group_kernel", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    else:
+        peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
+        achieved = flops[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
+        roofline = {"kernel": "gemm_group_kernel/" + dominant, "bound": "mfma", "achieved": achieved, "peak": peak,
+                    "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
+    roofline["launch_ms"] = stage_ms[dominant]
+    per_stage = {}
+    for k in gemm_stages:
+        if prof[k][1]:
+            per_stage[k] = {"ms_per_launch": stage_ms[k], "tflops": flops[k] / (stage_ms[k] * 1e-3) / 1e12}
+    per_stage["adam"] = {"ms_per_launch": stage_ms["adam"], "gbs": adam_bytes / (stage_ms["adam"] * 1e-3) / 1e9}
+
+    # ---- CPU baseline: the fp64 oracle on a bounded sample --------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import galore_oracle as orc
+        m, n = shapes[0]
+        rng = np.random.default_rng(0)
+        Gs = Gpool[0][0].to("cpu").to(torch.float64).numpy()
+        Ps = opt.proj[0].to("cpu").to(torch.float64).numpy()
+        o = orc.GaLoreTensor(W[0].to("cpu").to(torch.float64).numpy(), r, dtype=dtype, auto_refresh=False)
+        o.set_projector(Ps)
+        t0 = time.time()
+        o.step(Gs, lr)
+        dt = time.time() - t0
+        layer_flops = sum(4.0 * a * b * r for a, b in shapes)
+        scale = layer_flops / (4.0 * m * n * r)
+        cpu = {"value": dt * 1e3 * scale, "unit": "ms per layer set", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": "one oracle step (project, Adam, apply; projector given) on one %dx%d tensor, r=%d: %.2f s, "
+                         "scaled by the layer set's flop ratio %.2f" % (m, n, r, dt, scale)}
+
+    out = {
+        "metric": "GaLore step ms per LLaMA-7B layer set @r=1024",
+        "value": ms_per_step / L,
+        "unit": "ms per layer set (7 matrices)",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, fp32 M/V, r=%d, per-layer calls in "
+                               "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype, r, POOL),
+                   "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "stages": per_stage,
+        "ms_per_step_with_events": prof_total_ms / K,
+        "refresh": {"ms_total_step0": refresh_ms, "ms_per_layer_set": refresh_ms / L, "step0_ms": first_ms},
+        "step_flops": 4.0 * sum(m * n for m, n in shapes) * r * L,
+        "step_tflops": 4.0 * sum(m * n for m, n in shapes) * r * L / (ms_per_step * 1e-3) / 1e12,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

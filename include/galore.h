@@ -166,6 +166,25 @@ galore_status galore_project_back(const galore_tensor* proj, const galore_tensor
                                   const galore_tensor* W, float lr, float scale,
                                   float weight_decay, void* hip_stream);
 
+/* ---- Instrumentation (measurement only, no part of the method) ----
+ * Between galore_profile_start and galore_profile_stop every kernel group that galore_step or
+ * galore_refresh_subspace enqueues is bracketed by a pair of HIP events on the context's
+ * stream.  galore_profile_stop waits for the recorded work, then returns per stage the summed
+ * device time in milliseconds and the number of bracketed launches (arrays of
+ * GALORE_STAGE_COUNT entries, host memory).  A refresh counts as one launch per tensor group. */
+typedef enum {
+  GALORE_STAGE_PROJECT_LEFT = 0,   /* R = P^T G  (grouped MFMA GEMM) */
+  GALORE_STAGE_PROJECT_RIGHT = 1,  /* R = G Q */
+  GALORE_STAGE_ADAM = 2,           /* fused low-rank Adam */
+  GALORE_STAGE_BACK_LEFT = 3,      /* W -= lr*alpha*P N  (GEMM + weight epilogue) */
+  GALORE_STAGE_BACK_RIGHT = 4,     /* W -= lr*alpha*N Q^T */
+  GALORE_STAGE_REFRESH = 5,        /* whole subspace refresh of a tensor group */
+  GALORE_STAGE_COUNT = 6
+} galore_stage;
+
+galore_status galore_profile_start(galore_ctx* ctx);
+galore_status galore_profile_stop(galore_ctx* ctx, double* ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

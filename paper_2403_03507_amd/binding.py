@@ -43,7 +43,9 @@ class GaloreError(RuntimeError):
 
 EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
-           "galore_destroy", "galore_project", "galore_adam", "galore_project_back"]
+           "galore_destroy", "galore_project", "galore_adam", "galore_project_back",
+           "galore_profile_start", "galore_profile_stop"]
+STAGES = ["project_left", "project_right", "adam", "back_left", "back_right", "refresh"]
 
 _lib = None
 
@@ -72,6 +74,8 @@ def lib():
         L.galore_project.argtypes = [tp, tp, tp, vp]
         L.galore_adam.argtypes = [tp, tp, tp, tp, f32, f32, f32, i64, vp]
         L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
+        L.galore_profile_start.argtypes = [vp]
+        L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
     return _lib
 
@@ -159,6 +163,19 @@ def galore_adam(R, M, V, N, beta1, beta2, eps, k):
 def galore_project_back(proj, N, W, lr, scale, weight_decay=0.0):
     _check(lib().galore_project_back(ctypes.byref(desc(proj)), ctypes.byref(desc(N)), ctypes.byref(desc(W)), lr, scale,
                                      weight_decay, _stream()))
+
+
+def galore_profile_start(ctx):
+    _check(lib().galore_profile_start(ctx), ctx)
+
+
+def galore_profile_stop(ctx):
+    """-> {stage name: (milliseconds, launches)}"""
+    n = len(STAGES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(lib().galore_profile_stop(ctx, ms, cnt), ctx)
+    return {STAGES[i]: (ms[i], cnt[i]) for i in range(n)}
 
 
 class GaLore:

@@ -32,6 +32,11 @@ struct TensorInfo {
 
 }  // namespace
 
+struct ProfRecord {
+  hipEvent_t begin, end;
+  int stage;
+};
+
 struct galore_ctx {
   galore_hparams hp;
   std::vector<TensorInfo> tensors;
@@ -39,6 +44,9 @@ struct galore_ctx {
   size_t ws_bytes;
   hipStream_t stream;
   std::string err;
+  bool profiling = false;
+  std::vector<ProfRecord> records;
+  std::vector<hipEvent_t> event_pool;
 };
 
 namespace {
@@ -104,6 +112,28 @@ galore_status hip_fail(galore_ctx* ctx, hipError_t e, const char* where) {
   return fail(ctx, GALORE_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
 }
 
+// Event bracket around one kernel group while profiling is on.
+struct ProfScope {
+  galore_ctx* ctx;
+  ProfRecord rec{};
+  bool live = false;
+  ProfScope(galore_ctx* c, int stage, bool nonempty) : ctx(c) {
+    if (!c->profiling || !nonempty) return;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!c->event_pool.empty()) { ev[i] = c->event_pool.back(); c->event_pool.pop_back(); }
+      else if (hipEventCreate(&ev[i]) != hipSuccess) { if (i == 1) c->event_pool.push_back(ev[0]); return; }
+    }
+    rec.begin = ev[0]; rec.end = ev[1]; rec.stage = stage;
+    live = hipEventRecord(rec.begin, c->stream) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(rec.end, ctx->stream);
+    ctx->records.push_back(rec);
+  }
+};
+
 // ---- one chunk of the step: tensors idx[0..n) with their W, G -------------------------------
 struct StepItem {
   int tensor;
@@ -147,6 +177,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
           p.C = it.R; p.ldc = r;
         }
       }
+      ProfScope prof(ctx, left ? GALORE_STAGE_PROJECT_LEFT : GALORE_STAGE_PROJECT_RIGHT, g.count > 0);
       hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/!left, /*b_kcontig=*/false, Epilogue::StoreF32, ctx->stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
     }
@@ -167,6 +198,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
         p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
         p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
       }
+      ProfScope prof(ctx, GALORE_STAGE_ADAM, g.count > 0);
       hipError_t e = launch_adam_group(g, dt, ctx->stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "Adam launch");
     }
@@ -189,6 +221,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
         p.s0 = 1.f - lr * hp.weight_decay;
         p.s1 = lr * hp.scale;
       }
+      ProfScope prof(ctx, left ? GALORE_STAGE_BACK_LEFT : GALORE_STAGE_BACK_RIGHT, g.count > 0);
       hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::ApplyW, ctx->stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "back-projection GEMM launch");
     }
@@ -227,6 +260,7 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
       used += need;
       ++pos;
     }
+    ProfScope prof(ctx, GALORE_STAGE_REFRESH, true);
     hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
   }
@@ -423,7 +457,38 @@ galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t) {
 
 const char* galore_last_error(const galore_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }
 
-void galore_destroy(galore_ctx* ctx) { delete ctx; }
+void galore_destroy(galore_ctx* ctx) {
+  if (!ctx) return;
+  for (ProfRecord& r : ctx->records) { (void)hipEventDestroy(r.begin); (void)hipEventDestroy(r.end); }
+  for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+galore_status galore_profile_start(galore_ctx* ctx) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  for (ProfRecord& r : ctx->records) { ctx->event_pool.push_back(r.begin); ctx->event_pool.push_back(r.end); }
+  ctx->records.clear();
+  ctx->profiling = true;
+  return GALORE_OK;
+}
+
+galore_status galore_profile_stop(galore_ctx* ctx, double* ms, int64_t* launches) {
+  if (!ctx || !ms || !launches) return fail(ctx, GALORE_ERR_INVALID_ARG, "NULL argument");
+  ctx->profiling = false;
+  for (int i = 0; i < GALORE_STAGE_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  galore_status st = GALORE_OK;
+  for (ProfRecord& r : ctx->records) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(r.end);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.begin, r.end);
+    if (e != hipSuccess) st = hip_fail(ctx, e, "reading profile events");
+    else { ms[r.stage] += t; launches[r.stage] += 1; }
+    ctx->event_pool.push_back(r.begin);
+    ctx->event_pool.push_back(r.end);
+  }
+  ctx->records.clear();
+  return st;
+}
 
 // ---- stateless stage calls ---------------------------------------------------------------------
 
