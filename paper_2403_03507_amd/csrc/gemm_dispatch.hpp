@@ -1,13 +1,47 @@
 // Layout / epilogue dispatch shared by the per-dtype GEMM translation units.
 #pragma once
+#include <type_traits>
+
 #include "gemm_mfma.hpp"
+#include "gemm_mfma_dl.hpp"
+
+// Build-time choice of the large-tile configuration (tuning knob; 0 disables the kernel).
+#ifndef GALORE_DL_VARIANT
+#define GALORE_DL_VARIANT 2
+#endif
 
 namespace galore {
 
 using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
+#if GALORE_DL_VARIANT == 1
+using CfgDl = DlCfg<256, 256, 2, 2, 2>;
+#elif GALORE_DL_VARIANT == 2
+using CfgDl = DlCfg<256, 256, 2, 4, 2>;
+#elif GALORE_DL_VARIANT == 3
+using CfgDl = DlCfg<256, 128, 2, 2, 2>;
+#elif GALORE_DL_VARIANT == 4
+using CfgDl = DlCfg<256, 128, 2, 2, 3>;
+#elif GALORE_DL_VARIANT == 5
+using CfgDl = DlCfg<128, 128, 2, 2, 2>;
+#elif GALORE_DL_VARIANT == 6
+using CfgDl = DlCfg<128, 128, 2, 2, 4>;
+#elif GALORE_DL_VARIANT == 7
+using CfgDl = DlCfg<128, 256, 2, 2, 2>;
+#elif GALORE_DL_VARIANT == 8
+using CfgDl = DlCfg<256, 128, 4, 2, 2>;
+#endif
 
 template <class T, bool AK, bool BKC, Epilogue EPI>
 inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
+#if GALORE_DL_VARIANT > 0
+  if constexpr (std::is_same<T, __bf16>::value) {
+    if (group_fits_dl(g, AK, BKC, EPI)) {
+      plan_tiles<CfgDl>(g);
+      if (g.total_tiles == 0) return hipSuccess;
+      return launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(g, stream);
+    }
+  }
+#endif
   plan_tiles<CfgDefault>(g);
   if (g.total_tiles == 0) return hipSuccess;
   if (group_is_aligned<T>(g, AK, BKC))
