@@ -100,20 +100,26 @@ def main():
     total_ms = timed(lambda: [one_step(base + i) for i in range(K)])
     ms_per_step = total_ms / K
 
-    # same K steps again with every kernel group bracketed by HIP events on the library's stream
+    # Same K steps again, serial (one chain) and with every kernel group bracketed by HIP events on
+    # the library's stream: concurrent chains share the CUs, so per-kernel durations are only
+    # meaningful without overlap.
+    gb.galore_set_concurrency(opt.ctx, 1)
+    serial_ms = timed(lambda: [one_step(base + K + i) for i in range(K)]) / K
     gb.galore_profile_start(opt.ctx)
-    prof_total_ms = timed(lambda: [one_step(base + K + i) for i in range(K)])
+    prof_total_ms = timed(lambda: [one_step(base + 2 * K + i) for i in range(K)])
     prof = gb.galore_profile_stop(opt.ctx)
+    gb.galore_set_concurrency(opt.ctx, 3)
 
     # ---- roofline of the dominant kernel -----------------------------------------------------------
     left = [(m, n) for (m, n) in shapes if m <= n]
     right = [(m, n) for (m, n) in shapes if m > n]
     flops = {"project_left": sum(2.0 * m * n * r for m, n in left), "project_right": sum(2.0 * m * n * r for m, n in right)}
-    flops["back_left"], flops["back_right"] = flops["project_left"], flops["project_right"]
+    flops["back"] = flops["project_left"] + flops["project_right"]
     sN = 2 if dtype == "bf16" else 4
     adam_bytes = sum(r * max(m, n) * (4 * 5 + sN) for m, n in shapes)  # read R, M, V; write M, V, N
     stage_ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}        # average duration of one launch
-    gemm_stages = ["project_left", "project_right", "back_left", "back_right"]
+    stage_ms["adam"] = prof["adam"][0] / max(K * L, 1)                  # Adam: two launches (one per orientation) per layer
+    gemm_stages = ["project_left", "project_right", "back"]
     dominant = max(gemm_stages + ["adam"], key=lambda k: prof[k][0])
     if dominant == "adam":
         achieved = adam_bytes / (stage_ms["adam"] * 1e-3) / 1e9
@@ -164,7 +170,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "stages": per_stage,
-        "ms_per_step_with_events": prof_total_ms / K,
+        "ms_per_step_serial": serial_ms,
+        "ms_per_step_serial_with_events": prof_total_ms / K,
         "refresh": {"ms_total_step0": refresh_ms, "ms_per_layer_set": refresh_ms / L, "step0_ms": first_ms},
         "step_flops": 4.0 * sum(m * n for m, n in shapes) * r * L,
         "step_tflops": 4.0 * sum(m * n for m, n in shapes) * r * L / (ms_per_step * 1e-3) / 1e12,

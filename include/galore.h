@@ -63,15 +63,21 @@ typedef struct {
   int32_t dtype; /* galore_dtype */
 } galore_tensor;
 
-/* Optimizer state of one weight.  BORROWED, caller-allocated, survives across steps
- * (this is what a checkpoint saves, together with the step counter).
- *   proj : P (rows x r) for LEFT, Q (cols x r) for RIGHT; dtype = dtype of W.
- *   m, v : fp32, r x cols (LEFT) or rows x r (RIGHT), ld == cols, 16-byte aligned.
- * Element count is min(rows,cols)*r + 2*max(rows,cols)*r, the paper's mr + 2nr (Sec. 4.2). */
+/* Optimizer state of one weight.  BORROWED, caller-allocated, survives across steps.
+ *   proj   : P (rows x r) for LEFT, Q (cols x r) for RIGHT; dtype = dtype of W.
+ *   m, v   : fp32, r x cols (LEFT) or rows x r (RIGHT), ld == cols, 16-byte aligned.
+ *   proj_t : r x min(rows, cols), dtype of W: the projector transposed.  Derived data that
+ *            the library maintains (rewritten after every refresh, and from proj at every
+ *            step when auto_refresh == 0), kept so that both GEMMs of the step read the
+ *            projector with its contraction index contiguous.  Its initial contents do not
+ *            matter and a checkpoint need not save it.
+ * proj, m, v hold min(rows,cols)*r + 2*max(rows,cols)*r elements, the paper's mr + 2nr
+ * (Sec. 4.2); proj_t adds another min(rows,cols)*r. */
 typedef struct {
   galore_tensor proj;
   galore_tensor m;
   galore_tensor v;
+  galore_tensor proj_t;
 } galore_state;
 
 /* Hyper-parameters (Algorithm 2 inputs; Sec. 4.4).  Paper defaults: update_gap 200,
@@ -132,6 +138,14 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
 galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, int32_t first,
                                       int32_t count);
 
+/* Number of independent chains (1..3, default 3) into which one galore_step call splits its
+ * tensors.  Chains run project -> Adam -> project back for disjoint tensors on the context's
+ * stream and on up to two library-owned streams of default priority, forked from and joined
+ * back into the context's stream with events inside the call, so tail waves of one GEMM and the
+ * bandwidth-bound Adam pass overlap with another chain's MFMA work.  1 = strictly serial on the
+ * context's stream.  Results do not depend on the setting. */
+galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
+
 /* Step counter t of one tensor (number of steps taken); set is for checkpoint resume. */
 galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t);
 galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t);
@@ -147,21 +161,27 @@ void galore_destroy(galore_ctx* ctx);
  * They run the same kernels galore_step runs and exist so each stage can be checked and
  * timed alone. */
 
-/* R = P^T G (LEFT) or G Q (RIGHT) (Algorithm 2, projection line).  R is fp32, r x cols or
- * rows x r, ld == its cols.  proj dtype == G dtype. */
-galore_status galore_project(const galore_tensor* proj, const galore_tensor* G,
+/* dst (cols x rows) = src^T, same dtype.  galore_step uses it to derive state.proj_t. */
+galore_status galore_transpose(const galore_tensor* src, const galore_tensor* dst, void* hip_stream);
+
+/* R = P^T G (LEFT) or G Q (RIGHT) (Algorithm 2, projection line).  proj_t is the TRANSPOSED
+ * projector, r x min(rows, cols), dtype of G.  R is fp32, r x cols or rows x r, ld == its cols. */
+galore_status galore_project(const galore_tensor* proj_t, const galore_tensor* G,
                              const galore_tensor* R, void* hip_stream);
 
-/* Adam on the projected gradient (Algorithm 2, update block): updates fp32 M, V in place
- * and writes N (fp32 or bf16), all with R's shape and ld == cols.  k >= 1 is the 1-based
- * step used by the bias correction. */
+/* Adam on the projected gradient (Algorithm 2, update block): updates fp32 M, V (R's shape,
+ * dense) in place and writes N (fp32 or bf16, dense).  With transpose_n == 0, N has R's shape;
+ * with transpose_n != 0, N is stored transposed (R.cols x R.rows), which is what
+ * galore_project_back expects for a LEFT tensor.  k >= 1 is the 1-based step used by the
+ * bias correction. */
 galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V,
-                          const galore_tensor* N, float beta1, float beta2, float eps, int64_t k,
-                          void* hip_stream);
+                          const galore_tensor* N, int32_t transpose_n, float beta1, float beta2,
+                          float eps, int64_t k, void* hip_stream);
 
 /* W <- (1 - lr*weight_decay) W - lr*scale * (P N  or  N Q^T) (Algorithm 2, last lines),
- * applied inside the GEMM epilogue; the full-size update is never stored.  N dtype ==
- * proj dtype == W dtype. */
+ * applied inside the GEMM epilogue; the full-size update is never stored.  N is
+ * max(rows, cols) x r for both orientations (i.e. transposed for a LEFT tensor), dense.
+ * N dtype == proj dtype == W dtype. */
 galore_status galore_project_back(const galore_tensor* proj, const galore_tensor* N,
                                   const galore_tensor* W, float lr, float scale,
                                   float weight_decay, void* hip_stream);
@@ -175,9 +195,9 @@ galore_status galore_project_back(const galore_tensor* proj, const galore_tensor
 typedef enum {
   GALORE_STAGE_PROJECT_LEFT = 0,   /* R = P^T G  (grouped MFMA GEMM) */
   GALORE_STAGE_PROJECT_RIGHT = 1,  /* R = G Q */
-  GALORE_STAGE_ADAM = 2,           /* fused low-rank Adam */
-  GALORE_STAGE_BACK_LEFT = 3,      /* W -= lr*alpha*P N  (GEMM + weight epilogue) */
-  GALORE_STAGE_BACK_RIGHT = 4,     /* W -= lr*alpha*N Q^T */
+  GALORE_STAGE_ADAM = 2,           /* fused low-rank Adam (one launch per orientation) */
+  GALORE_STAGE_BACK = 3,           /* W -= lr*alpha*(P N | N Q^T)  (GEMM + weight epilogue) */
+  GALORE_STAGE_TRANSPOSE = 4,      /* proj -> proj_t */
   GALORE_STAGE_REFRESH = 5,        /* whole subspace refresh of a tensor group */
   GALORE_STAGE_COUNT = 6
 } galore_stage;

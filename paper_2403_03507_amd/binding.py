@@ -25,7 +25,7 @@ class galore_tensor(ctypes.Structure):
 
 
 class galore_state(ctypes.Structure):
-    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("v", galore_tensor)]
+    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("v", galore_tensor), ("proj_t", galore_tensor)]
 
 
 class galore_hparams(ctypes.Structure):
@@ -43,9 +43,9 @@ class GaloreError(RuntimeError):
 
 EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
-           "galore_destroy", "galore_project", "galore_adam", "galore_project_back",
-           "galore_profile_start", "galore_profile_stop"]
-STAGES = ["project_left", "project_right", "adam", "back_left", "back_right", "refresh"]
+           "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_project_back",
+           "galore_profile_start", "galore_profile_stop", "galore_set_concurrency"]
+STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
 _lib = None
 
@@ -71,9 +71,11 @@ def lib():
         L.galore_last_error.restype = ctypes.c_char_p
         L.galore_destroy.argtypes = [vp]
         L.galore_destroy.restype = None
+        L.galore_transpose.argtypes = [tp, tp, vp]
         L.galore_project.argtypes = [tp, tp, tp, vp]
-        L.galore_adam.argtypes = [tp, tp, tp, tp, f32, f32, f32, i64, vp]
+        L.galore_adam.argtypes = [tp, tp, tp, tp, i32, f32, f32, f32, i64, vp]
         L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
+        L.galore_set_concurrency.argtypes = [vp, i32]
         L.galore_profile_start.argtypes = [vp]
         L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
@@ -151,18 +153,26 @@ def galore_destroy(ctx):
     lib().galore_destroy(ctx)
 
 
-def galore_project(proj, G, R):
-    _check(lib().galore_project(ctypes.byref(desc(proj)), ctypes.byref(desc(G)), ctypes.byref(desc(R)), _stream()))
+def galore_transpose(src, dst):
+    _check(lib().galore_transpose(ctypes.byref(desc(src)), ctypes.byref(desc(dst)), _stream()))
 
 
-def galore_adam(R, M, V, N, beta1, beta2, eps, k):
+def galore_project(proj_t, G, R):
+    _check(lib().galore_project(ctypes.byref(desc(proj_t)), ctypes.byref(desc(G)), ctypes.byref(desc(R)), _stream()))
+
+
+def galore_adam(R, M, V, N, transpose_n, beta1, beta2, eps, k):
     _check(lib().galore_adam(ctypes.byref(desc(R)), ctypes.byref(desc(M)), ctypes.byref(desc(V)), ctypes.byref(desc(N)),
-                             beta1, beta2, eps, k, _stream()))
+                             1 if transpose_n else 0, beta1, beta2, eps, k, _stream()))
 
 
 def galore_project_back(proj, N, W, lr, scale, weight_decay=0.0):
     _check(lib().galore_project_back(ctypes.byref(desc(proj)), ctypes.byref(desc(N)), ctypes.byref(desc(W)), lr, scale,
                                      weight_decay, _stream()))
+
+
+def galore_set_concurrency(ctx, lanes):
+    _check(lib().galore_set_concurrency(ctx, lanes), ctx)
 
 
 def galore_profile_start(ctx):
@@ -186,10 +196,11 @@ class GaLore:
         self.hp = make_hparams(rank, **hparams)
         self.shapes = [(w.shape[0], w.shape[1]) for w in weights]
         self.dtypes = [w.dtype for w in weights]
-        self.proj, self.M, self.V = [], [], []
+        self.proj, self.M, self.V, self.proj_t = [], [], [], []
         for (m, n), dt in zip(self.shapes, self.dtypes):
             k, l = (m, n) if m <= n else (n, m)
             self.proj.append(torch.zeros(k, rank, dtype=dt, device=device))
+            self.proj_t.append(torch.empty(rank, k, dtype=dt, device=device))
             shape = (rank, l) if m <= n else (l, rank)
             self.M.append(torch.empty(shape, dtype=torch.float32, device=device))
             self.V.append(torch.empty(shape, dtype=torch.float32, device=device))
@@ -197,7 +208,8 @@ class GaLore:
         if workspace_bytes is None:
             workspace_bytes = galore_workspace_bytes(self.hp, w_descs)
         self.workspace = torch.empty(max(workspace_bytes, 256), dtype=torch.uint8, device=device)
-        states = [galore_state(desc(p), desc(m), desc(v)) for p, m, v in zip(self.proj, self.M, self.V)]
+        states = [galore_state(desc(p), desc(m), desc(v), desc(pt))
+                  for p, m, v, pt in zip(self.proj, self.M, self.V, self.proj_t)]
         self.ctx = galore_init(self.hp, w_descs, states, self.workspace.data_ptr(), workspace_bytes)
 
     def step(self, weights, grads, lr, first=0):

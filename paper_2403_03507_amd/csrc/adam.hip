@@ -62,9 +62,85 @@ __global__ __launch_bounds__(256) void adam_group_kernel(const AdamGroup grp) {
   }
 }
 
+// Same update, but N is written transposed (cols x rows): the back-projection GEMM then finds
+// its contraction index contiguous in memory.  One block per 64 x 64 tile: R, M, V are read and
+// M, V written row-wise with 16-byte vectors, N goes through a padded LDS tile and leaves
+// column-wise, again as 16-byte vectors.  Ragged or unaligned tiles take an element-wise path.
+template <class TN>
+__global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGroup grp) {
+  constexpr int TS = 64;
+  constexpr int VEC = 16 / sizeof(TN);          // N elements per 16 bytes
+  __shared__ __align__(16) TN tile[TS][TS + VEC];  // tile[j][i] = N[i][j]
+  const AdamProblem& pr = grp.p[blockIdx.y];
+  const int rows = pr.rows, cols = pr.cols;
+  const int tiles_c = (cols + TS - 1) / TS;
+  const int ntiles = tiles_c * ((rows + TS - 1) / TS);
+  const float beta1 = grp.beta1, beta2 = grp.beta2, eps = grp.eps;
+  const float ic1 = pr.inv_c1, ic2 = pr.inv_c2;
+  const float* __restrict__ R = pr.R;
+  float* __restrict__ M = pr.M;
+  float* __restrict__ V = pr.V;
+  TN* __restrict__ N = static_cast<TN*>(pr.N);
+  const bool aligned = (cols % 4 == 0) && (rows % VEC == 0);
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int i0 = (t / tiles_c) * TS, j0 = (t % tiles_c) * TS;
+    const bool full = aligned && i0 + TS <= rows && j0 + TS <= cols;
+    if (full) {
+#pragma unroll
+      for (int ps = 0; ps < 4; ++ps) {
+        const int i = ps * 16 + (threadIdx.x >> 4), j = (threadIdx.x & 15) * 4;
+        const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
+        const f32x4 g = *reinterpret_cast<const f32x4*>(R + idx);
+        f32x4 m = *reinterpret_cast<const f32x4*>(M + idx);
+        f32x4 v = *reinterpret_cast<const f32x4*>(V + idx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float me = m[e], ve = v[e];
+          tile[j + e][i] = (TN)adam_entry(g[e], me, ve, beta1, beta2, eps, ic1, ic2);
+          m[e] = me; v[e] = ve;
+        }
+        *reinterpret_cast<f32x4*>(M + idx) = m;
+        *reinterpret_cast<f32x4*>(V + idx) = v;
+      }
+      __syncthreads();
+      constexpr int LPR = TS / VEC;        // lanes per output row
+      constexpr int RPP = 256 / LPR;       // output rows per pass
+#pragma unroll
+      for (int ps = 0; ps < TS / RPP; ++ps) {
+        const int j = ps * RPP + threadIdx.x / LPR, i = (threadIdx.x % LPR) * VEC;
+        *reinterpret_cast<uint4*>(N + (size_t)(j0 + j) * rows + i0 + i) = *reinterpret_cast<const uint4*>(&tile[j][i]);
+      }
+      __syncthreads();
+    } else {
+      for (int e = threadIdx.x; e < TS * TS; e += 256) {
+        const int i = e / TS, j = e % TS;
+        if (i0 + i < rows && j0 + j < cols) {
+          const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
+          float me = M[idx], ve = V[idx];
+          const float n = adam_entry(R[idx], me, ve, beta1, beta2, eps, ic1, ic2);
+          M[idx] = me; V[idx] = ve;
+          N[(size_t)(j0 + j) * rows + i0 + i] = (TN)n;
+        }
+      }
+    }
+  }
+}
+
 hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream) {
   if (g.count <= 0) return hipSuccess;
   if (g.count > kMaxGroup) return hipErrorInvalidValue;
+  if (g.p[0].transpose_n) {
+    int64_t maxtiles = 0;
+    for (int i = 0; i < g.count; ++i) {
+      const int64_t t = (int64_t)((g.p[i].rows + 63) / 64) * ((g.p[i].cols + 63) / 64);
+      maxtiles = t > maxtiles ? t : maxtiles;
+    }
+    if (maxtiles == 0) return hipSuccess;
+    const dim3 grid((unsigned)(maxtiles > 4096 ? 4096 : maxtiles), (unsigned)g.count);
+    if (n_dtype == DType::BF16) hipLaunchKernelGGL(adam_transpose_group_kernel<__bf16>, grid, dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL(adam_transpose_group_kernel<float>, grid, dim3(256), 0, stream, g);
+    return hipGetLastError();
+  }
   int64_t maxcount = 0;
   for (int i = 0; i < g.count; ++i) maxcount = g.p[i].count > maxcount ? g.p[i].count : maxcount;
   if (maxcount == 0) return hipSuccess;
@@ -97,6 +173,46 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                      static_cast<unsigned char*>(ptr), bytes);
+  return hipGetLastError();
+}
+
+// dst (cols x rows) = src^T through a padded 64 x 64 LDS tile; element-wise, any shape / stride.
+template <class T>
+__global__ __launch_bounds__(256) void transpose_group_kernel(const TransposeGroup grp) {
+  constexpr int TS = 64;
+  __shared__ T tile[TS][TS + 2];
+  const TransposeProblem& pr = grp.p[blockIdx.y];
+  const T* __restrict__ src = static_cast<const T*>(pr.src);
+  T* __restrict__ dst = static_cast<T*>(pr.dst);
+  const int tiles_c = (pr.cols + TS - 1) / TS;
+  const int ntiles = tiles_c * ((pr.rows + TS - 1) / TS);
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int i0 = (t / tiles_c) * TS, j0 = (t % tiles_c) * TS;
+    for (int e = threadIdx.x; e < TS * TS; e += 256) {
+      const int i = e / TS, j = e % TS;
+      if (i0 + i < pr.rows && j0 + j < pr.cols) tile[i][j] = src[(size_t)(i0 + i) * pr.lds + j0 + j];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < TS * TS; e += 256) {
+      const int j = e / TS, i = e % TS;
+      if (i0 + i < pr.rows && j0 + j < pr.cols) dst[(size_t)(j0 + j) * pr.ldd + i0 + i] = tile[i][j];
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_transpose_group(const TransposeGroup& g, DType dt, hipStream_t stream) {
+  if (g.count <= 0) return hipSuccess;
+  if (g.count > kMaxGroup) return hipErrorInvalidValue;
+  int64_t maxtiles = 0;
+  for (int i = 0; i < g.count; ++i) {
+    const int64_t t = (int64_t)((g.p[i].rows + 63) / 64) * ((g.p[i].cols + 63) / 64);
+    maxtiles = t > maxtiles ? t : maxtiles;
+  }
+  if (maxtiles == 0) return hipSuccess;
+  const dim3 grid((unsigned)(maxtiles > 2048 ? 2048 : maxtiles), (unsigned)g.count);
+  if (dt == DType::BF16) hipLaunchKernelGGL(transpose_group_kernel<__bf16>, grid, dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL(transpose_group_kernel<float>, grid, dim3(256), 0, stream, g);
   return hipGetLastError();
 }
 

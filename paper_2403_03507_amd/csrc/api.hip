@@ -28,6 +28,7 @@ struct TensorInfo {
   int64_t ldim;    // long side
   galore_state st;
   int64_t t;
+  bool proj_t_valid;  // state.proj_t mirrors state.proj (only trusted when the library owns the projector)
 };
 
 }  // namespace
@@ -47,6 +48,13 @@ struct galore_ctx {
   bool profiling = false;
   std::vector<ProfRecord> records;
   std::vector<hipEvent_t> event_pool;
+  // Concurrency inside one galore_step call: the tensors of a call are split into up to
+  // `lanes` independent chains (project -> Adam -> project back) that run on the caller's
+  // stream and on library-owned streams (default priority), forked and joined with events.
+  int lanes = 3;
+  hipStream_t aux[2] = {nullptr, nullptr};
+  hipEvent_t fork_ev = nullptr;
+  hipEvent_t join_ev[2] = {nullptr, nullptr};
 };
 
 namespace {
@@ -115,9 +123,10 @@ galore_status hip_fail(galore_ctx* ctx, hipError_t e, const char* where) {
 // Event bracket around one kernel group while profiling is on.
 struct ProfScope {
   galore_ctx* ctx;
+  hipStream_t stream;
   ProfRecord rec{};
   bool live = false;
-  ProfScope(galore_ctx* c, int stage, bool nonempty) : ctx(c) {
+  ProfScope(galore_ctx* c, int stage, bool nonempty, hipStream_t st = nullptr) : ctx(c), stream(st ? st : c->stream) {
     if (!c->profiling || !nonempty) return;
     hipEvent_t ev[2];
     for (int i = 0; i < 2; ++i) {
@@ -125,11 +134,11 @@ struct ProfScope {
       else if (hipEventCreate(&ev[i]) != hipSuccess) { if (i == 1) c->event_pool.push_back(ev[0]); return; }
     }
     rec.begin = ev[0]; rec.end = ev[1]; rec.stage = stage;
-    live = hipEventRecord(rec.begin, c->stream) == hipSuccess;
+    live = hipEventRecord(rec.begin, stream) == hipSuccess;
   }
   ~ProfScope() {
     if (!live) return;
-    (void)hipEventRecord(rec.end, ctx->stream);
+    (void)hipEventRecord(rec.end, stream);
     ctx->records.push_back(rec);
   }
 };
@@ -143,76 +152,88 @@ struct StepItem {
   void* N;
 };
 
-galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, float lr) {
+galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, float lr, hipStream_t stream) {
   const galore_hparams& hp = ctx->hp;
   const int r = hp.rank;
-  // workspace carve-up
-  size_t off = 0;
-  for (StepItem& it : items) {
-    const TensorInfo& ti = ctx->tensors[it.tensor];
-    it.R = reinterpret_cast<float*>(ctx->ws + off);
-    off += align_up((size_t)r * ti.ldim * 4);
-    it.N = ctx->ws + off;
-    off += align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
-  }
-  // The list may mix dtypes; launches are split by (dtype, orientation).
+  // The list may mix dtypes; launches are split by dtype (and by orientation where layouts differ).
   for (int dti = 0; dti < 2; ++dti) {
     const DType dt = dti == 0 ? DType::F32 : DType::BF16;
-    // K1: project
+    // proj_t <- proj^T where the library cannot vouch for the copy it has
+    {
+      TransposeGroup g{};
+      for (const StepItem& it : items) {
+        TensorInfo& ti = ctx->tensors[it.tensor];
+        if (ti.dt != dt || (hp.auto_refresh && ti.proj_t_valid)) continue;
+        TransposeProblem& p = g.p[g.count++];
+        p.src = ti.st.proj.data; p.lds = (int)ti.st.proj.ld;
+        p.dst = ti.st.proj_t.data; p.ldd = (int)ti.st.proj_t.ld;
+        p.rows = (int)ti.kdim; p.cols = r;
+        ti.proj_t_valid = true;
+      }
+      ProfScope prof(ctx, GALORE_STAGE_TRANSPOSE, g.count > 0, stream);
+      hipError_t e = launch_transpose_group(g, dt, stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "projector transpose launch");
+    }
+    // K1: project.  Both operands are read from layouts in which as much as possible is
+    // contiguous along the contraction index; only G of a LEFT tensor is not.
     for (int left = 1; left >= 0; --left) {
       GemmGroup g{};
       for (const StepItem& it : items) {
         const TensorInfo& ti = ctx->tensors[it.tensor];
         if (ti.dt != dt || (int)ti.left != left) continue;
         GemmProblem& p = g.p[g.count++];
-        if (left) {  // R (r x n) = P^T G : A = P as [K=m][M=r], B = G as [K=m][N=n]
-          p.A = ti.st.proj.data; p.lda = (int)ti.st.proj.ld;
+        if (left) {  // R (r x n) = P^T G : A = proj_t as [M=r][K=m], B = G as [K=m][N=n]
+          p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
           p.B = it.G->data; p.ldb = (int)it.G->ld;
           p.M = r; p.N = (int)ti.cols; p.K = (int)ti.rows;
           p.C = it.R; p.ldc = (int)ti.cols;
-        } else {     // R (m x r) = G Q : A = G as [M=m][K=n], B = Q as [K=n][N=r]
+        } else {     // R (m x r) = G Q : A = G as [M=m][K=n], B = proj_t as [N=r][K=n]
           p.A = it.G->data; p.lda = (int)it.G->ld;
-          p.B = ti.st.proj.data; p.ldb = (int)ti.st.proj.ld;
+          p.B = ti.st.proj_t.data; p.ldb = (int)ti.st.proj_t.ld;
           p.M = (int)ti.rows; p.N = r; p.K = (int)ti.cols;
           p.C = it.R; p.ldc = r;
         }
       }
-      ProfScope prof(ctx, left ? GALORE_STAGE_PROJECT_LEFT : GALORE_STAGE_PROJECT_RIGHT, g.count > 0);
-      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/!left, /*b_kcontig=*/false, Epilogue::StoreF32, ctx->stream);
+      ProfScope prof(ctx, left ? GALORE_STAGE_PROJECT_LEFT : GALORE_STAGE_PROJECT_RIGHT, g.count > 0, stream);
+      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::StoreF32, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
     }
-    // K2: Adam on R
-    {
+    // K2: Adam on R.  N always leaves as (long side) x r: transposed for LEFT tensors.
+    for (int left = 1; left >= 0; --left) {
       AdamGroup g{};
       g.beta1 = hp.beta1; g.beta2 = hp.beta2; g.eps = hp.eps;
       for (const StepItem& it : items) {
         const TensorInfo& ti = ctx->tensors[it.tensor];
-        if (ti.dt != dt) continue;
+        if (ti.dt != dt || (int)ti.left != left) continue;
         AdamProblem& p = g.p[g.count++];
         const double k = (double)(ti.t + 1);
         p.R = it.R;
         p.M = static_cast<float*>(ti.st.m.data);
         p.V = static_cast<float*>(ti.st.v.data);
         p.N = it.N;
+        p.rows = left ? r : (int)ti.rows;
+        p.cols = left ? (int)ti.cols : r;
         p.count = (int64_t)r * ti.ldim;
+        p.transpose_n = left;
         p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
         p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
       }
-      ProfScope prof(ctx, GALORE_STAGE_ADAM, g.count > 0);
-      hipError_t e = launch_adam_group(g, dt, ctx->stream);
+      ProfScope prof(ctx, GALORE_STAGE_ADAM, g.count > 0, stream);
+      hipError_t e = launch_adam_group(g, dt, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "Adam launch");
     }
-    // K3: project back + apply
-    for (int left = 1; left >= 0; --left) {
+    // K3: project back + apply; with N as (long side) x r both orientations share one layout
+    // (A and B contiguous along r), hence one launch.
+    {
       GemmGroup g{};
       for (const StepItem& it : items) {
         const TensorInfo& ti = ctx->tensors[it.tensor];
-        if (ti.dt != dt || (int)ti.left != left) continue;
+        if (ti.dt != dt) continue;
         GemmProblem& p = g.p[g.count++];
-        if (left) {  // W (m x n) -= P N : A = P as [M=m][K=r], B = N as [K=r][N=n]
+        if (ti.left) {  // W (m x n) -= P N : A = P as [M=m][K=r], B = N^T as [N=n][K=r]
           p.A = ti.st.proj.data; p.lda = (int)ti.st.proj.ld;
-          p.B = it.N; p.ldb = (int)ti.cols;
-        } else {     // W (m x n) -= N Q^T : A = N as [M=m][K=r], B = Q as [N=n][K=r]
+          p.B = it.N; p.ldb = r;
+        } else {        // W (m x n) -= N Q^T : A = N as [M=m][K=r], B = Q as [N=n][K=r]
           p.A = it.N; p.lda = r;
           p.B = ti.st.proj.data; p.ldb = (int)ti.st.proj.ld;
         }
@@ -221,12 +242,61 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
         p.s0 = 1.f - lr * hp.weight_decay;
         p.s1 = lr * hp.scale;
       }
-      ProfScope prof(ctx, left ? GALORE_STAGE_BACK_LEFT : GALORE_STAGE_BACK_RIGHT, g.count > 0);
-      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::ApplyW, ctx->stream);
+      ProfScope prof(ctx, GALORE_STAGE_BACK, g.count > 0, stream);
+      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/true, Epilogue::ApplyW, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "back-projection GEMM launch");
     }
   }
   return GALORE_OK;
+}
+
+// One chunk of the step: carve the workspace, split the tensors into chains of similar cost and
+// run the chains concurrently.  Chains touch disjoint tensors and disjoint workspace regions.
+galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, float lr) {
+  const int r = ctx->hp.rank;
+  size_t off = 0;
+  for (StepItem& it : items) {
+    const TensorInfo& ti = ctx->tensors[it.tensor];
+    it.R = reinterpret_cast<float*>(ctx->ws + off);
+    off += align_up((size_t)r * ti.ldim * 4);
+    it.N = ctx->ws + off;
+    off += align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+  }
+  int lanes = ctx->lanes;
+  if (lanes > 1 && (!ctx->aux[0] || !ctx->aux[1] || !ctx->fork_ev)) lanes = 1;
+  if ((int)items.size() < 2) lanes = 1;
+  if (lanes <= 1) return run_chain(ctx, items, lr, ctx->stream);
+
+  // Greedy balance by cost (m n, as r is shared): heaviest tensor first, always into the lightest chain.
+  std::vector<int> order(items.size());
+  for (size_t i = 0; i < items.size(); ++i) order[i] = (int)i;
+  auto cost = [&](int i) { const TensorInfo& ti = ctx->tensors[items[i].tensor]; return (double)ti.rows * (double)ti.cols; };
+  for (size_t a = 1; a < order.size(); ++a)  // insertion sort, descending cost, stable
+    for (size_t b = a; b > 0 && cost(order[b]) > cost(order[b - 1]); --b) { const int x = order[b]; order[b] = order[b - 1]; order[b - 1] = x; }
+  std::vector<StepItem> chain[3];
+  double load[3] = {0, 0, 0};
+  for (int i : order) {
+    int best = 0;
+    for (int c = 1; c < lanes; ++c)
+      if (load[c] < load[best]) best = c;
+    chain[best].push_back(items[i]);
+    load[best] += cost(i);
+  }
+  hipError_t e = hipEventRecord(ctx->fork_ev, ctx->stream);
+  for (int c = 1; c < lanes && e == hipSuccess; ++c)
+    if (!chain[c].empty()) e = hipStreamWaitEvent(ctx->aux[c - 1], ctx->fork_ev, 0);
+  if (e != hipSuccess) return hip_fail(ctx, e, "forking streams");
+  galore_status st = GALORE_OK;
+  for (int c = 0; c < lanes && st == GALORE_OK; ++c)
+    if (!chain[c].empty()) st = run_chain(ctx, chain[c], lr, c == 0 ? ctx->stream : ctx->aux[c - 1]);
+  // always join, also after a failed launch, so the caller's stream stays ordered after our streams
+  for (int c = 1; c < lanes; ++c) {
+    if (chain[c].empty()) continue;
+    e = hipEventRecord(ctx->join_ev[c - 1], ctx->aux[c - 1]);
+    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_ev[c - 1], 0);
+    if (e != hipSuccess && st == GALORE_OK) st = hip_fail(ctx, e, "joining streams");
+  }
+  return st;
 }
 
 galore_status check_step_tensor(galore_ctx* ctx, const TensorInfo& ti, const galore_tensor& x, const char* what, int i) {
@@ -244,6 +314,7 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
   size_t pos = 0;
   while (pos < local.size()) {
     std::vector<RefreshItem> chunk;
+    std::vector<int> chunk_tensors;
     size_t used = 0;
     while (pos < local.size() && (int)chunk.size() < kMaxGroup) {
       const int i = local[pos];
@@ -257,12 +328,27 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
       it.ws = ctx->ws + used;
       it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
       chunk.push_back(it);
+      chunk_tensors.push_back(first + i);
       used += need;
       ++pos;
     }
     ProfScope prof(ctx, GALORE_STAGE_REFRESH, true);
     hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
+    for (int dti = 0; dti < 2 && e == hipSuccess; ++dti) {  // keep proj_t in step with the new projector
+      TransposeGroup g{};
+      for (int idx : chunk_tensors) {
+        TensorInfo& ti = ctx->tensors[idx];
+        if ((int)ti.dt != dti) continue;
+        TransposeProblem& p = g.p[g.count++];
+        p.src = ti.st.proj.data; p.lds = (int)ti.st.proj.ld;
+        p.dst = ti.st.proj_t.data; p.ldd = (int)ti.st.proj_t.ld;
+        p.rows = (int)ti.kdim; p.cols = ctx->hp.rank;
+        ti.proj_t_valid = true;
+      }
+      e = launch_transpose_group(g, (DType)dti, ctx->stream);
+    }
+    if (e != hipSuccess) return hip_fail(ctx, e, "projector transpose launch");
   }
   return GALORE_OK;
 }
@@ -338,6 +424,13 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
     if (p.rows != ti.kdim || p.cols != r)
       return fail(nullptr, GALORE_ERR_SHAPE, "S[%d].proj must be %lld x %lld", i, (long long)ti.kdim, (long long)r);
     if ((DType)p.dtype != ti.dt) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d].proj dtype must equal the weight dtype", i);
+    const galore_tensor& pt = S[i].proj_t;
+    s = check_matrix(nullptr, pt, "S.proj_t", i, true);
+    if (s) return s;
+    if (pt.rows != r || pt.cols != ti.kdim)
+      return fail(nullptr, GALORE_ERR_SHAPE, "S[%d].proj_t must be %lld x %lld", i, (long long)r, (long long)ti.kdim);
+    if ((DType)pt.dtype != ti.dt) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d].proj_t dtype must equal the weight dtype", i);
+    ti.proj_t_valid = false;
     const int64_t mr = ti.left ? r : ti.rows, mc = ti.left ? ti.cols : r;
     const galore_tensor* mv[2] = {&S[i].m, &S[i].v};
     for (int q = 0; q < 2; ++q) {
@@ -362,6 +455,19 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
   ctx->ws = static_cast<unsigned char*>(workspace);
   ctx->ws_bytes = workspace_bytes;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
+  {
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipStreamCreateWithFlags(&ctx->aux[i], hipStreamNonBlocking);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->join_ev[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      galore_status st = hip_fail(nullptr, e, "creating streams");
+      galore_destroy(ctx);
+      return st;
+    }
+  }
   // M_0 = V_0 = 0 (Algorithm 2, initialisation)
   for (const TensorInfo& ti : ctx->tensors) {
     const size_t bytes = (size_t)r * ti.ldim * 4;
@@ -452,6 +558,7 @@ galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t) {
     return fail(ctx, GALORE_ERR_INVALID_ARG, "tensor index %d out of range", tensor);
   if (t < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "step counter must be >= 0");
   ctx->tensors[tensor].t = t;
+  ctx->tensors[tensor].proj_t_valid = false;  // a resumed projector was written by the caller
   return GALORE_OK;
 }
 
@@ -461,7 +568,19 @@ void galore_destroy(galore_ctx* ctx) {
   if (!ctx) return;
   for (ProfRecord& r : ctx->records) { (void)hipEventDestroy(r.begin); (void)hipEventDestroy(r.end); }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->aux[i]) { (void)hipStreamSynchronize(ctx->aux[i]); (void)hipStreamDestroy(ctx->aux[i]); }
+    if (ctx->join_ev[i]) (void)hipEventDestroy(ctx->join_ev[i]);
+  }
+  if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
   delete ctx;
+}
+
+galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  if (lanes < 1 || lanes > 3) return fail(ctx, GALORE_ERR_INVALID_ARG, "lanes must be 1, 2 or 3");
+  ctx->lanes = lanes;
+  return GALORE_OK;
 }
 
 galore_status galore_profile_start(galore_ctx* ctx) {
@@ -492,45 +611,60 @@ galore_status galore_profile_stop(galore_ctx* ctx, double* ms, int64_t* launches
 
 // ---- stateless stage calls ---------------------------------------------------------------------
 
-galore_status galore_project(const galore_tensor* proj, const galore_tensor* G, const galore_tensor* R, void* hip_stream) {
-  if (!proj || !G || !R) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+galore_status galore_transpose(const galore_tensor* src, const galore_tensor* dst, void* hip_stream) {
+  if (!src || !dst) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
   galore_status s;
-  if ((s = check_matrix(nullptr, *proj, "proj", 0, true)) || (s = check_matrix(nullptr, *G, "G", 0, true)) ||
+  if ((s = check_matrix(nullptr, *src, "src", 0, true)) || (s = check_matrix(nullptr, *dst, "dst", 0, true))) return s;
+  if (src->dtype != dst->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "src and dst dtypes differ");
+  if (dst->rows != src->cols || dst->cols != src->rows) return fail(nullptr, GALORE_ERR_SHAPE, "dst must be cols x rows of src");
+  TransposeGroup g{};
+  g.count = 1;
+  g.p[0].src = src->data; g.p[0].lds = (int)src->ld; g.p[0].dst = dst->data; g.p[0].ldd = (int)dst->ld;
+  g.p[0].rows = (int)src->rows; g.p[0].cols = (int)src->cols;
+  hipError_t e = launch_transpose_group(g, (DType)src->dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "transpose launch");
+}
+
+galore_status galore_project(const galore_tensor* proj_t, const galore_tensor* G, const galore_tensor* R, void* hip_stream) {
+  if (!proj_t || !G || !R) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+  galore_status s;
+  if ((s = check_matrix(nullptr, *proj_t, "proj_t", 0, true)) || (s = check_matrix(nullptr, *G, "G", 0, true)) ||
       (s = check_matrix(nullptr, *R, "R", 0, true)))
     return s;
-  if (proj->dtype != G->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj and G dtypes differ");
+  if (proj_t->dtype != G->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj_t and G dtypes differ");
   if (R->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "R must be fp32");
   const bool left = G->rows <= G->cols;
-  const int64_t r = proj->cols;
+  const int64_t r = proj_t->rows;
   if (r > (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
-  if (proj->rows != (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj rows must equal the short side of G");
+  if (proj_t->cols != (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj_t cols must equal the short side of G");
   if (R->rows != (left ? r : G->rows) || R->cols != (left ? G->cols : r))
     return fail(nullptr, GALORE_ERR_SHAPE, "R has the wrong shape");
   GemmGroup g{};
   g.count = 1;
   GemmProblem& p = g.p[0];
   if (left) {
-    p.A = proj->data; p.lda = (int)proj->ld; p.B = G->data; p.ldb = (int)G->ld;
+    p.A = proj_t->data; p.lda = (int)proj_t->ld; p.B = G->data; p.ldb = (int)G->ld;
     p.M = (int)r; p.N = (int)G->cols; p.K = (int)G->rows;
   } else {
-    p.A = G->data; p.lda = (int)G->ld; p.B = proj->data; p.ldb = (int)proj->ld;
+    p.A = G->data; p.lda = (int)G->ld; p.B = proj_t->data; p.ldb = (int)proj_t->ld;
     p.M = (int)G->rows; p.N = (int)r; p.K = (int)G->cols;
   }
   p.C = R->data; p.ldc = (int)R->ld;
-  hipError_t e = launch_gemm_group(g, (DType)G->dtype, !left, false, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
+  hipError_t e = launch_gemm_group(g, (DType)G->dtype, true, !left, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "projection GEMM launch");
 }
 
 galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V, const galore_tensor* N,
-                          float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
+                          int32_t transpose_n, float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
   if (!R || !M || !V || !N) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
   const galore_tensor* all[4] = {R, M, V, N};
   const char* names[4] = {"R", "M", "V", "N"};
   for (int i = 0; i < 4; ++i) {
     galore_status s = check_matrix(nullptr, *all[i], names[i], 0, true);
     if (s) return s;
-    if (all[i]->rows != R->rows || all[i]->cols != R->cols || all[i]->ld != all[i]->cols)
-      return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense with R's shape", names[i]);
+    const bool tr = i == 3 && transpose_n;
+    if (all[i]->rows != (tr ? R->cols : R->rows) || all[i]->cols != (tr ? R->rows : R->cols) || all[i]->ld != all[i]->cols)
+      return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense with R's shape%s", names[i], tr ? " transposed" : "");
     if (i < 3 && all[i]->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "%s must be fp32", names[i]);
     if (reinterpret_cast<uintptr_t>(all[i]->data) & 15) return fail(nullptr, GALORE_ERR_ALIGN, "%s must be 16-byte aligned", names[i]);
   }
@@ -542,6 +676,7 @@ galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const 
   AdamProblem& p = g.p[0];
   p.R = static_cast<const float*>(R->data); p.M = static_cast<float*>(M->data); p.V = static_cast<float*>(V->data);
   p.N = N->data; p.count = R->rows * R->cols;
+  p.rows = (int)R->rows; p.cols = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
   p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
   p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
   hipError_t e = launch_adam_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
@@ -560,8 +695,8 @@ galore_status galore_project_back(const galore_tensor* proj, const galore_tensor
   const int64_t r = proj->cols;
   if (r > (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
   if (proj->rows != (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj rows must equal the short side of W");
-  if (N->rows != (left ? r : W->rows) || N->cols != (left ? W->cols : r))
-    return fail(nullptr, GALORE_ERR_SHAPE, "N has the wrong shape");
+  if (N->rows != (left ? W->cols : W->rows) || N->cols != r)
+    return fail(nullptr, GALORE_ERR_SHAPE, "N must be max(rows, cols) x r");
   GemmGroup g{};
   g.count = 1;
   GemmProblem& p = g.p[0];
@@ -574,7 +709,7 @@ galore_status galore_project_back(const galore_tensor* proj, const galore_tensor
   p.C = W->data; p.ldc = (int)W->ld;
   p.s0 = 1.f - lr * weight_decay;
   p.s1 = lr * scale;
-  hipError_t e = launch_gemm_group(g, (DType)W->dtype, true, !left, Epilogue::ApplyW, static_cast<hipStream_t>(hip_stream));
+  hipError_t e = launch_gemm_group(g, (DType)W->dtype, true, true, Epilogue::ApplyW, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "back-projection GEMM launch");
 }
 

@@ -52,7 +52,10 @@ struct AdamProblem {
   float* M;
   float* V;
   void* N;        // fp32 or bf16
-  int64_t count;
+  int64_t count;  // rows * cols
+  int32_t rows;   // shape of R, M, V (dense, row-major)
+  int32_t cols;
+  int32_t transpose_n;  // 0: N has R's layout; 1: N is stored transposed (cols x rows)
   float inv_c1;   // 1 / (1 - beta1^k)
   float inv_c2;   // 1 / (1 - beta2^k)
 };
@@ -63,7 +66,20 @@ struct AdamGroup {
   AdamProblem p[kMaxGroup];
 };
 
+// All problems of a group share n_dtype and transpose_n.
 hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream);
+
+// ---- grouped matrix transpose (projector k x r -> r x k) ------------------------------------
+struct TransposeProblem {
+  const void* src;  // rows x cols, leading dimension lds
+  void* dst;        // cols x rows, leading dimension ldd
+  int32_t rows, cols, lds, ldd;
+};
+struct TransposeGroup {
+  int32_t count;
+  TransposeProblem p[kMaxGroup];
+};
+hipError_t launch_transpose_group(const TransposeGroup& g, DType dt, hipStream_t stream);
 
 // ---- small utilities -----------------------------------------------------------------------
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);

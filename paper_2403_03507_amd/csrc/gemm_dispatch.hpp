@@ -14,28 +14,30 @@ namespace galore {
 
 using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
 #if GALORE_DL_VARIANT == 1
-using CfgDl = DlCfg<256, 256, 2, 2, 2>;
+using CfgDl = DlCfg<256, 256, 64, 2, 2, 2>;
 #elif GALORE_DL_VARIANT == 2
-using CfgDl = DlCfg<256, 256, 2, 4, 2>;
+using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;
 #elif GALORE_DL_VARIANT == 3
-using CfgDl = DlCfg<256, 128, 2, 2, 2>;
+using CfgDl = DlCfg<256, 128, 32, 2, 2, 3>;
 #elif GALORE_DL_VARIANT == 4
-using CfgDl = DlCfg<256, 128, 2, 2, 3>;
+using CfgDl = DlCfg<256, 128, 32, 2, 2, 2>;
 #elif GALORE_DL_VARIANT == 5
-using CfgDl = DlCfg<128, 128, 2, 2, 2>;
+using CfgDl = DlCfg<128, 128, 64, 2, 2, 2>;
 #elif GALORE_DL_VARIANT == 6
-using CfgDl = DlCfg<128, 128, 2, 2, 4>;
+using CfgDl = DlCfg<128, 256, 32, 2, 2, 3>;
 #elif GALORE_DL_VARIANT == 7
-using CfgDl = DlCfg<128, 256, 2, 2, 2>;
+using CfgDl = DlCfg<256, 256, 32, 2, 4, 3>;
 #elif GALORE_DL_VARIANT == 8
-using CfgDl = DlCfg<256, 128, 4, 2, 2>;
+using CfgDl = DlCfg<256, 128, 64, 4, 2, 2>;
+#elif GALORE_DL_VARIANT == 9
+using CfgDl = DlCfg<256, 256, 32, 2, 2, 4>;
 #endif
 
 template <class T, bool AK, bool BKC, Epilogue EPI>
 inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
 #if GALORE_DL_VARIANT > 0
   if constexpr (std::is_same<T, __bf16>::value) {
-    if (group_fits_dl(g, AK, BKC, EPI)) {
+    if (group_fits_dl(g, AK, BKC, EPI, CfgDl::BK)) {
       plan_tiles<CfgDl>(g);
       if (g.total_tiles == 0) return hipSuccess;
       return launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(g, stream);
@@ -50,10 +52,11 @@ inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
 }
 
 // The layout / epilogue combinations the library uses:
-//   (X,X) Store   : R = P^T G            ; fp32 also Q^T Z of the refresh
-//   (K,X) Store   : R = G Q              ; fp32 also C Q and Q S of the refresh
-//   (K,X) ApplyW  : W -= P N
-//   (K,K) ApplyW  : W -= N Q^T
+//   (K,X) Store   : R = P^T G with A = the transposed projector copy ; fp32 also C Q and Q S of the refresh
+//   (K,K) Store   : R = G Q   with B = the transposed projector copy
+//   (K,K) ApplyW  : W -= P N^T^T (N stored transposed) and W -= N Q^T
+//   (X,X) Store   : fp32 Q^T Z of the refresh
+//   (K,X) ApplyW  : fp32 trailing updates
 //   (K,K) StoreSym: C = G G^T
 //   (X,X) StoreSym: C = G^T G
 template <class T>
@@ -61,6 +64,7 @@ inline hipError_t launch_gemm_typed(GemmGroup& g, bool ak, bool bk, Epilogue epi
   if (epi == Epilogue::StoreF32) {
     if (!ak && !bk) return launch_gemm_layout<T, false, false, Epilogue::StoreF32>(g, stream);
     if (ak && !bk) return launch_gemm_layout<T, true, false, Epilogue::StoreF32>(g, stream);
+    if (ak && bk) return launch_gemm_layout<T, true, true, Epilogue::StoreF32>(g, stream);
   } else if (epi == Epilogue::ApplyW) {
     if (ak && !bk) return launch_gemm_layout<T, true, false, Epilogue::ApplyW>(g, stream);
     if (ak && bk) return launch_gemm_layout<T, true, true, Epilogue::ApplyW>(g, stream);

@@ -1,5 +1,5 @@
 // Large-tile bf16 MFMA GEMM with direct global -> LDS loads (gfx950), used when every
-// operand is 16-byte aligned and K is a multiple of 64.
+// operand is 16-byte aligned and K is a multiple of the K step.
 //
 // Differences from the generic kernel in gemm_mfma.hpp:
 //   * tiles go from global memory straight into LDS with global_load_lds_dwordx4 (each wave
@@ -7,19 +7,21 @@
 //     VGPRs are spent on staging and a tile can be in flight while the previous one is consumed;
 //   * LDS rows are unpadded; bank conflicts are avoided by an XOR swizzle that is applied by
 //     choosing WHICH 16-byte piece of global memory each lane fetches:
-//       - K-contiguous tile (rows of 64 k = 8 pieces): piece p of row x sits at p ^ ((x >> 1) & 7);
+//       - K-contiguous tile (rows of 64 k = 8 pieces): piece p of row x sits at p ^ ((x >> 1) & 7)
+//         (rows of 32 k = 4 pieces: p ^ ((x >> 2) & 3));
 //       - tile contiguous along its M/N index (rows are k): column c of row k sits at c ^ (32 (k & 3));
 //     both make the ds_read_b128 / ds_read_b64_tr_b16 fragment reads conflict-free;
 //   * rows past the matrix edge are fetched from the clamped (last valid) row / column and
 //     never stored, so no masking is needed in the main loop;
-//   * a STAGES-deep ring of tiles with one workgroup barrier per 64-wide K step.
+//   * a STAGES-deep ring of tiles with one workgroup barrier per K step of 32 or 64.
 #pragma once
 #include "gemm_mfma.hpp"
 
 namespace galore {
 
-template <int BM_, int BN_, int WGM_, int WGN_, int STAGES_> struct DlCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = 64, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_> struct DlCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
+  static_assert(BK == 32 || BK == 64, "K step is 32 or 64");
   static constexpr int NW = WGM * WGN;
   static constexpr int NT = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -36,8 +38,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(imm);
 }
 
-template <bool KCONTIG, int BX, int NW> struct DlOperand {
-  static constexpr int BK = 64;
+template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
   static constexpr int TILE_BYTES = BX * BK * 2;
   static constexpr int CHUNKS = TILE_BYTES / 1024;  // one wave instruction fills 1 KB
   static constexpr int PER_WAVE = CHUNKS / NW;
@@ -53,8 +54,9 @@ template <bool KCONTIG, int BX, int NW> struct DlOperand {
     for (int it = 0; it < PER_WAVE; ++it) {
       const int c = wave + it * NW;
       if (KCONTIG) {
-        const int row = 8 * c + (lane >> 3);
-        const int p = (lane & 7) ^ ((row >> 1) & 7);
+        // BK = 64: rows of 8 pieces, 8 rows per chunk; BK = 32: rows of 4 pieces, 16 rows per chunk
+        const int row = BK == 64 ? 8 * c + (lane >> 3) : 16 * c + (lane >> 2);
+        const int p = BK == 64 ? (lane & 7) ^ ((row >> 1) & 7) : (lane & 3) ^ ((row >> 2) & 3);
         int xr = x0 + row;
         xr = xr < X ? xr : X - 1;
         voff[it] = ((unsigned)xr * (unsigned)ld + p * 8) * 2u;
@@ -88,7 +90,7 @@ template <bool KCONTIG, int BX, int NW> struct DlOperand {
   static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds_tile, int x, int kk, int lane) {
     if (KCONTIG) {
       const int i = lane & 31;
-      const int pc = (2 * (kk >> 4) + (lane >> 5)) ^ ((i >> 1) & 7);
+      const int pc = (2 * (kk >> 4) + (lane >> 5)) ^ (BK == 64 ? (i >> 1) & 7 : (i >> 2) & 3);
       return *reinterpret_cast<const bf16x8*>(lds_tile + (x + i) * ROW_BYTES + pc * 16);
     } else {
       const int s = lane & 15, g = lane >> 4;
@@ -108,8 +110,8 @@ template <bool AK, bool BKC, Epilogue EPI, class Cfg>
 __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, S = Cfg::STAGES;
   constexpr int TM = Cfg::TM, TN = Cfg::TN;
-  using AOp = DlOperand<AK, BM, NW>;
-  using BOp = DlOperand<BKC, BN, NW>;
+  using AOp = DlOperand<AK, BM, BK, NW>;
+  using BOp = DlOperand<BKC, BN, BK, NW>;
   constexpr int STAGE_BYTES = AOp::TILE_BYTES + BOp::TILE_BYTES;
   constexpr int LOADS = AOp::PER_WAVE + BOp::PER_WAVE;  // vector-memory ops per wave per tile
   static_assert((S - 2) * LOADS <= 63, "too many loads in flight for the wait counter");
@@ -167,10 +169,13 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     if (kt + S - 2 < KT) wait_vmcnt<(S - 2) * LOADS>();
     else wait_vmcnt<0>();
     __syncthreads();  // everyone's pieces of tile kt are visible; everyone is done with tile kt - 1
+#ifndef GALORE_EXPERIMENT_NO_LOAD
     if (kt + S - 1 < KT) issue_tile(kt + S - 1);  // refills the stage consumed at kt - 1
+#endif
 
     const unsigned char* as = smem_dl + (kt % S) * STAGE_BYTES;
     const unsigned char* bs = as + AOp::TILE_BYTES;
+#ifndef GALORE_EXPERIMENT_NO_MFMA
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[TM], fb[TN];
@@ -184,6 +189,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+#endif
   }
 
   // ---- epilogue: accumulators -> wave-private LDS strip -> row-contiguous 16/32-byte accesses ----
@@ -262,8 +268,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
 
 template <bool AK, bool BKC, Epilogue EPI, class Cfg>
 inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream) {
-  using AOp = DlOperand<AK, Cfg::BM, Cfg::NW>;
-  using BOp = DlOperand<BKC, Cfg::BN, Cfg::NW>;
+  using AOp = DlOperand<AK, Cfg::BM, Cfg::BK, Cfg::NW>;
+  using BOp = DlOperand<BKC, Cfg::BN, Cfg::BK, Cfg::NW>;
   constexpr size_t smem = (size_t)Cfg::STAGES * (AOp::TILE_BYTES + BOp::TILE_BYTES);
   static_assert(smem <= 160 * 1024, "tile ring does not fit the 160 KB LDS");
   auto kern = gemm_dl_kernel<AK, BKC, EPI, Cfg>;
@@ -281,12 +287,12 @@ inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream
 // The direct-load kernel needs 16-byte alignment of both operands and of the output (its
 // epilogue moves 8 consecutive columns per lane), K a multiple of 64, N a multiple of 8, and at
 // least 8 valid elements along each M/N index (for the edge clamp).
-inline bool group_fits_dl(const GemmGroup& g, bool ak, bool bk, Epilogue epi) {
+inline bool group_fits_dl(const GemmGroup& g, bool ak, bool bk, Epilogue epi, int bk_step = 64) {
   if (!group_is_aligned<__bf16>(g, ak, bk)) return false;
   const int c_vec = epi == Epilogue::ApplyW ? 8 : 4;  // elements per 16 bytes of the output
   for (int i = 0; i < g.count; ++i) {
     const GemmProblem& p = g.p[i];
-    if (p.K % 64 != 0 || p.K < 64) return false;
+    if (p.K % bk_step != 0 || p.K < bk_step) return false;
     if (p.M < 8 || p.N < 8 || p.N % 8 != 0) return false;
     if ((reinterpret_cast<uintptr_t>(p.C) & 15) || p.ldc % c_vec != 0) return false;
   }

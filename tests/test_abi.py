@@ -40,7 +40,8 @@ def _fake_state(k, r, l, left=True, dtype=gb.GALORE_F32, ptr=4096):
     mshape = (r, l) if left else (l, r)
     return gb.galore_state(gb.galore_tensor(ptr, k, r, r, dtype),
                            gb.galore_tensor(ptr, mshape[0], mshape[1], mshape[1], gb.GALORE_F32),
-                           gb.galore_tensor(ptr, mshape[0], mshape[1], mshape[1], gb.GALORE_F32))
+                           gb.galore_tensor(ptr, mshape[0], mshape[1], mshape[1], gb.GALORE_F32),
+                           gb.galore_tensor(ptr, r, k, k, dtype))
 
 
 def _status(fn, *a, **k):
@@ -78,6 +79,11 @@ def test_init_validation_happens_before_any_device_work():
     assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
     s = _fake_state(8, 4, 16, dtype=gb.GALORE_BF16)
     assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 3
+    # transposed projector copy: wrong shape / missing
+    s = _fake_state(8, 4, 16); s.proj_t.rows, s.proj_t.cols, s.proj_t.ld = 8, 4, 4
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
+    s = _fake_state(8, 4, 16); s.proj_t.data = None
+    assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 1
     # moments: wrong orientation, wrong dtype, misaligned, NULL
     s = _fake_state(8, 4, 16, left=False)
     assert _status(gb.galore_init, hp, w, [s], 4096, ws, stream=ctypes.c_void_p(None)) == 2
@@ -97,20 +103,23 @@ def test_init_validation_happens_before_any_device_work():
 def test_stateless_calls_validate_shapes():
     L = gb.lib()
     T = gb.galore_tensor
-    P = T(4096, 8, 4, 4, 0); G = T(4096, 8, 16, 16, 0); R = T(4096, 4, 16, 16, 0)
+    P = T(4096, 8, 4, 4, 0); Pt = T(4096, 4, 8, 8, 0); G = T(4096, 8, 16, 16, 0); R = T(4096, 4, 16, 16, 0)
     bad_R = T(4096, 16, 4, 4, 0)
-    assert L.galore_project(ctypes.byref(P), ctypes.byref(G), ctypes.byref(bad_R), None) == 2
+    assert L.galore_project(ctypes.byref(Pt), ctypes.byref(G), ctypes.byref(bad_R), None) == 2
+    assert L.galore_project(ctypes.byref(P), ctypes.byref(G), ctypes.byref(R), None) in (2, 4)   # untransposed projector
     Gb = T(4096, 8, 16, 16, 1)
-    assert L.galore_project(ctypes.byref(P), ctypes.byref(Gb), ctypes.byref(R), None) == 3
+    assert L.galore_project(ctypes.byref(Pt), ctypes.byref(Gb), ctypes.byref(R), None) == 3
     assert L.galore_project(None, ctypes.byref(G), ctypes.byref(R), None) == 1
-    P9 = T(4096, 8, 9, 9, 0)
+    P9 = T(4096, 9, 8, 8, 0)
     assert L.galore_project(ctypes.byref(P9), ctypes.byref(G), ctypes.byref(R), None) == 4
     M = T(4096, 4, 16, 16, 0)
-    assert L.galore_adam(ctypes.byref(R), ctypes.byref(M), ctypes.byref(M), ctypes.byref(M), 0.9, 0.999, 1e-8, 0, None) == 1
+    assert L.galore_adam(ctypes.byref(R), ctypes.byref(M), ctypes.byref(M), ctypes.byref(M), 0, 0.9, 0.999, 1e-8, 0, None) == 1
     Mb = T(4096, 4, 16, 16, 1)
-    assert L.galore_adam(ctypes.byref(R), ctypes.byref(Mb), ctypes.byref(M), ctypes.byref(M), 0.9, 0.999, 1e-8, 1, None) == 3
-    W = T(4096, 8, 16, 16, 0); N = T(4096, 16, 4, 4, 0)
-    assert L.galore_project_back(ctypes.byref(P), ctypes.byref(N), ctypes.byref(W), 1e-3, 0.25, 0.0, None) == 2
+    assert L.galore_adam(ctypes.byref(R), ctypes.byref(Mb), ctypes.byref(M), ctypes.byref(M), 0, 0.9, 0.999, 1e-8, 1, None) == 3
+    assert L.galore_adam(ctypes.byref(R), ctypes.byref(M), ctypes.byref(M), ctypes.byref(M), 1, 0.9, 0.999, 1e-8, 1, None) == 2  # N not transposed
+    W = T(4096, 8, 16, 16, 0); N = T(4096, 4, 16, 16, 0)
+    assert L.galore_project_back(ctypes.byref(P), ctypes.byref(N), ctypes.byref(W), 1e-3, 0.25, 0.0, None) == 2  # N must be 16 x 4
+    assert L.galore_transpose(ctypes.byref(P), ctypes.byref(P), None) == 2
 
 
 def test_null_context_calls():

@@ -1,6 +1,7 @@
 """GPU parity of the three per-step stages against the fp64 oracle, element by element.
 
-Stages are called through the C ABI (galore_project / galore_adam / galore_project_back), which
+Stages are called through the C ABI (galore_transpose / galore_project / galore_adam /
+galore_project_back), which
 run the same kernels galore_step runs.  Shapes span several 128x128 tiles, ragged tails, odd
 sizes that force the unaligned load path, padded leading dimensions and both orientations.
 """
@@ -30,6 +31,18 @@ SHAPES = [  # (m, n, r)
 ]
 
 
+def _transposed(P):
+    """The projector's transposed copy, made by the library's own transpose stage."""
+    Pt = torch.empty(P.shape[1], P.shape[0], dtype=P.dtype, device=P.device)
+    gb.galore_transpose(P, Pt)
+    return Pt
+
+
+def _long_by_r(N, m, n):
+    """Device copy of N in the layout the back-projection reads: (long side) x r."""
+    return (N.t().contiguous() if m <= n else N).cuda()
+
+
 def _inputs(m, n, r, dtype, seed):
     k = min(m, n)
     G = wl.GradientSource(m, n, seed, "lowrank", dtype=dtype, signal_rank=min(8, k), noise=0.05).grad(0)
@@ -45,7 +58,7 @@ def test_project(shape, dtype):
     _, G, P = _inputs(m, n, r, dtype, 11)
     R_ref = orc.project(to64(P), to64(G))
     R = torch.full(R_ref.shape, float("nan"), dtype=torch.float32, device="cuda")
-    gb.galore_project(P.cuda(), G.cuda(), R)
+    gb.galore_project(_transposed(P.cuda()), G.cuda(), R)
     torch.cuda.synchronize()
     assert relF(to64(R), R_ref) <= 1e-5
     scale = np.abs(R_ref).max() + 1e-30
@@ -59,34 +72,36 @@ def test_project_with_padded_leading_dimensions(dtype, pad):
         _, G, P = _inputs(m, n, r, dtype, 12)
         R_ref = orc.project(to64(P), to64(G))
         R = torch.empty(R_ref.shape, dtype=torch.float32, device="cuda")
-        gb.galore_project(strided(P.cuda(), pad), strided(G.cuda(), pad), R)
+        gb.galore_project(strided(_transposed(P.cuda()), pad), strided(G.cuda(), pad), R)
         torch.cuda.synchronize()
         assert relF(to64(R), R_ref) <= 1e-5
 
 
+@pytest.mark.parametrize("transpose_n", [False, True])
 @pytest.mark.parametrize("n_dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("count_shape", [(128, 1376), (33, 257), (1, 3), (7, 1), (256, 4096)])
-def test_adam(count_shape, n_dtype):
+@pytest.mark.parametrize("count_shape", [(128, 1376), (33, 257), (1, 3), (7, 1), (256, 4096), (64, 200), (72, 136)])
+def test_adam(count_shape, n_dtype, transpose_n):
     rng = np.random.default_rng(5)
     shape = count_shape
     M = np.zeros(shape); V = np.zeros(shape)
     Md = torch.zeros(shape, dtype=torch.float32, device="cuda")
     Vd = torch.zeros(shape, dtype=torch.float32, device="cuda")
-    Nd = torch.empty(shape, dtype=TDT[n_dtype], device="cuda")
+    Nd = torch.empty(shape[::-1] if transpose_n else shape, dtype=TDT[n_dtype], device="cuda")
     big = np.zeros(shape)
     for k in range(1, 5):
         R32 = (rng.standard_normal(shape) * 10.0 ** rng.integers(-4, 1, shape)).astype(np.float32)
         big = np.maximum(big, np.abs(R32))  # running size of the terms that entered M
         N_ref = orc.adam(R32.astype(np.float64), M, V, B1, B2, EPS, k)
-        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
+        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, transpose_n, 0.9, 0.999, 1e-8, k)
         torch.cuda.synchronize()
+        N_dev = to64(Nd).T if transpose_n else to64(Nd)
         assert relF(to64(Md), M) <= 1e-6 and relF(to64(Vd), V) <= 1e-6
         # M is a sum that can cancel: bound the error by the size of the terms, not of the result
         assert np.all(np.abs(to64(Md) - M) <= 3e-7 * big + 1e-30)
         np.testing.assert_allclose(to64(Vd), V, rtol=2e-6, atol=1e-30)
         rel = 5e-6 if n_dtype == "f32" else 2.0 ** -8
-        assert relF(to64(Nd), N_ref) <= rel
-        assert np.all(np.abs(to64(Nd) - N_ref) <= rel * np.abs(N_ref) + 1e-5)
+        assert relF(N_dev, N_ref) <= rel
+        assert np.all(np.abs(N_dev - N_ref) <= rel * np.abs(N_ref) + 1e-5)
         # oracle state follows fp32 storage, like the device state
         M[:] = orc.round_storage(M, "f32"); V[:] = orc.round_storage(V, "f32")
 
@@ -101,7 +116,7 @@ def test_adam_bias_correction_at_large_k():
         N_ref = orc.adam(R32.astype(np.float64), M, V, B1, B2, EPS, k)
         Md = torch.from_numpy(M0.copy()).cuda(); Vd = torch.from_numpy(V0.copy()).cuda()
         Nd = torch.empty(shape, dtype=torch.float32, device="cuda")
-        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, 0.9, 0.999, 1e-8, k)
+        gb.galore_adam(torch.from_numpy(R32).cuda(), Md, Vd, Nd, False, 0.9, 0.999, 1e-8, k)
         np.testing.assert_allclose(to64(Nd), N_ref, rtol=5e-6, atol=1e-12)
 
 
@@ -117,7 +132,7 @@ def test_project_back(shape, dtype):
     W_ref = to64(W).copy()
     orc.apply_update(W_ref, to64(P), to64(N), lr, alpha, wd)
     Wd = W.cuda().clone()
-    gb.galore_project_back(P.cuda(), N.cuda(), Wd, lr, alpha, wd)
+    gb.galore_project_back(P.cuda(), _long_by_r(N, m, n), Wd, lr, alpha, wd)
     torch.cuda.synchronize()
     assert relF(to64(Wd), W_ref) <= TOL[dtype]
     if dtype == "f32":
@@ -140,7 +155,7 @@ def test_project_back_padded_weight(dtype):
         W_ref = to64(W).copy()
         orc.apply_update(W_ref, to64(P), to64(N), f32(1e-2), 0.25, 0.0)
         Wd = strided(W.cuda(), 5)
-        gb.galore_project_back(P.cuda(), N.cuda(), Wd, 1e-2, 0.25, 0.0)
+        gb.galore_project_back(P.cuda(), _long_by_r(N, m, n), Wd, 1e-2, 0.25, 0.0)
         torch.cuda.synchronize()
         assert relF(to64(Wd), W_ref) <= TOL[dtype]
         assert torch.all(Wd._base[:, n:] == 0)  # padding untouched
@@ -152,8 +167,8 @@ def test_round_trip_identity_full_rank():
     G = wl.GradientSource(m, n, 3, "lowrank", signal_rank=8, noise=0.05).grad(0)
     P = wl.random_orthonormal(m, m, 4)
     R = torch.empty(m, n, dtype=torch.float32, device="cuda")
-    gb.galore_project(P.cuda(), G.cuda(), R)
+    gb.galore_project(_transposed(P.cuda()), G.cuda(), R)
     W = torch.zeros(m, n, dtype=torch.float32, device="cuda")
-    gb.galore_project_back(P.cuda(), R, W, -1.0, 1.0, 0.0)
+    gb.galore_project_back(P.cuda(), R.t().contiguous(), W, -1.0, 1.0, 0.0)
     torch.cuda.synchronize()
     assert relF(to64(W), to64(G)) <= 1e-5

@@ -123,6 +123,27 @@ def test_determinism_bitwise():
         assert torch.equal(a, b)
 
 
+def test_concurrent_chains_match_serial_bitwise():
+    # galore_set_concurrency only changes which stream each tensor's chain runs on.
+    shapes = [(256, 688), (688, 256), (256, 256), (256, 256), (256, 688)]
+    outs = []
+    for lanes in (1, 2, 3):
+        W0 = [wl.make_weight(m, n, 300 + i, "bf16").cuda() for i, (m, n) in enumerate(shapes)]
+        opt = gb.GaLore(W0, 64, auto_refresh=False)
+        gb.galore_set_concurrency(opt.ctx, lanes)
+        for i, (m, n) in enumerate(shapes):
+            opt.proj[i].copy_(wl.random_orthonormal(min(m, n), 64, 400 + i).to(torch.bfloat16))
+        for step in range(3):
+            G = [wl.GradientSource(m, n, 500 + i, "lowrank", dtype="bf16").grad(step).cuda() for i, (m, n) in enumerate(shapes)]
+            opt.step(W0, G, 1e-2)
+        torch.cuda.synchronize()
+        outs.append([w.clone() for w in W0] + [x.clone() for x in opt.M + opt.V])
+        opt.close()
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
+
+
 def test_checkpoint_resume_is_bit_identical():
     m, n, r = 256, 688, 64
     src = wl.GradientSource(m, n, 9, "lowrank", dtype="bf16")
