@@ -325,6 +325,7 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
       it.G = G[i].data; it.ldg = G[i].ld; it.rows = ti.rows; it.cols = ti.cols;
       it.dt = ti.dt;
       it.proj = ti.st.proj.data; it.ldp = ti.st.proj.ld;
+      it.proj_t = ti.st.proj_t.data; it.ldpt = ti.st.proj_t.ld;
       it.ws = ctx->ws + used;
       it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
       chunk.push_back(it);
@@ -335,20 +336,7 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
     ProfScope prof(ctx, GALORE_STAGE_REFRESH, true);
     hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
-    for (int dti = 0; dti < 2 && e == hipSuccess; ++dti) {  // keep proj_t in step with the new projector
-      TransposeGroup g{};
-      for (int idx : chunk_tensors) {
-        TensorInfo& ti = ctx->tensors[idx];
-        if ((int)ti.dt != dti) continue;
-        TransposeProblem& p = g.p[g.count++];
-        p.src = ti.st.proj.data; p.lds = (int)ti.st.proj.ld;
-        p.dst = ti.st.proj_t.data; p.ldd = (int)ti.st.proj_t.ld;
-        p.rows = (int)ti.kdim; p.cols = ctx->hp.rank;
-        ti.proj_t_valid = true;
-      }
-      e = launch_transpose_group(g, (DType)dti, ctx->stream);
-    }
-    if (e != hipSuccess) return hip_fail(ctx, e, "projector transpose launch");
+    for (int idx : chunk_tensors) ctx->tensors[idx].proj_t_valid = true;  // the refresh writes proj and proj_t
   }
   return GALORE_OK;
 }

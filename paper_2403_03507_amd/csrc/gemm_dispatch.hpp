@@ -55,14 +55,12 @@ inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
 //   (K,X) Store   : R = P^T G with A = the transposed projector copy ; fp32 also C Q and Q S of the refresh
 //   (K,K) Store   : R = G Q   with B = the transposed projector copy
 //   (K,K) ApplyW  : W -= P N^T^T (N stored transposed) and W -= N Q^T
-//   (X,X) Store   : fp32 Q^T Z of the refresh
-//   (K,X) ApplyW  : fp32 trailing updates
+//   (K,X) ApplyW  : kept for callers that hold N untransposed
 //   (K,K) StoreSym: C = G G^T
 //   (X,X) StoreSym: C = G^T G
 template <class T>
 inline hipError_t launch_gemm_typed(GemmGroup& g, bool ak, bool bk, Epilogue epi, hipStream_t stream) {
   if (epi == Epilogue::StoreF32) {
-    if (!ak && !bk) return launch_gemm_layout<T, false, false, Epilogue::StoreF32>(g, stream);
     if (ak && !bk) return launch_gemm_layout<T, true, false, Epilogue::StoreF32>(g, stream);
     if (ak && bk) return launch_gemm_layout<T, true, true, Epilogue::StoreF32>(g, stream);
   } else if (epi == Epilogue::ApplyW) {

@@ -7,11 +7,16 @@
 // followed by a Rayleigh-Ritz step B = Q^T C Q = S L S^T, P = Q S, columns ordered by
 // decreasing L, each column signed so that its largest-magnitude entry is positive.
 //   * Gram and the tall GEMMs run on the grouped MFMA GEMM.
-//   * QR is Householder, one reflector per launch: every block rebuilds the reflector of
-//     column j with a wavefront (DPP shuffle) + LDS reduction and applies it to its own strip
-//     of 32 trailing columns; Q is then formed by applying the reflectors to [I; 0] backwards.
+//   * QR is Householder in panels of 8 reflectors: one block per tensor factors a panel held in
+//     registers (wavefront shuffle + LDS reductions for the norms and inner products), then
+//     blocks of 8 trailing columns apply the 8 reflectors to register-resident data, so each
+//     panel costs one read and one write of the trailing matrix; Q is formed by applying the
+//     panels to [I; 0] backwards.  Short sides beyond 4096 fall back to one launch per reflector.
 //   * The r x r eigenproblem is solved by one-sided (Hestenes) Jacobi on the rows of B with
 //     round-robin pair ordering, one launch per round of r/2 disjoint pairs.
+// The iteration blocks are kept TRANSPOSED in memory (Qt, Zt: r x k row-major), so that a
+// column of Z - the thing a Householder reflector works on - is a contiguous row and every
+// access below is coalesced; C is symmetric, so Zt = Qt C needs no transposed GEMM either.
 // All tensors of a group advance in lock-step (blockIdx.y = tensor), nothing syncs the host,
 // iteration counts are fixed, and no atomics are used, so results are reproducible bit for bit.
 #include "refresh.hpp"
@@ -23,23 +28,27 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-constexpr int kJacobiSweeps = 10;
-constexpr float kJacobiTol = 1e-7f;
+constexpr int kJacobiSweeps = 10;   // upper bound; sweeps after convergence return at once
+constexpr float kJacobiTol = 4e-6f;  // |b_p.b_q| <= tol |b_p||b_q|: the rounding floor of an fp32 dot of length r
+constexpr int kNB = 8;               // reflectors per Householder panel
+constexpr int kRPT = 4;              // rows per thread in the panel kernels (1024 threads): k - j0 <= 4096
+constexpr int kSW = 8;               // columns per block in the blocked reflector application
 
 struct RefreshTensor {
   float* C;      // k x k Gram matrix
-  float* Q;      // k x r iteration block
-  float* Z;      // k x r product block / factored reflectors / fp32 projector
+  float* Q;      // Qt: r x k, the iteration block transposed
+  float* Z;      // Zt: r x k, product block / factored reflectors / fp32 projector, transposed
   float* Bw;     // r x r Rayleigh-Ritz matrix, rotated in place
   float* Jt;     // r x r accumulated rotations (rows = eigenvectors)
-  float* S;      // r x r eigenvectors as columns, ordered
+  float* S;      // St: r x r, rows = eigenvectors, ordered by decreasing Ritz value, unit length
   float* tau;    // r
   float* vscale; // r
   float* lambda; // r
   int32_t* order;// r : order[i] = output column of eigenvector i
-  void* proj;    // output, k x r, ld ldp
+  int32_t* sweep_flag;  // kJacobiSweeps + 1 : sweep s rotated something
+  void* proj_t;  // output, r x k, ld ldpt (the projector itself is its transpose)
   int32_t k;
-  int32_t ldp;
+  int32_t ldpt;
   uint64_t seed;
 };
 
@@ -50,7 +59,7 @@ struct RefreshGroup {
 };
 
 struct Layout {
-  size_t C, Q, Z, Bw, Jt, S, tau, vscale, lambda, order, total;
+  size_t C, Q, Z, Bw, Jt, S, tau, vscale, lambda, order, sweep_flag, total;
 };
 
 Layout layout_for(int64_t k, int64_t r) {
@@ -67,6 +76,7 @@ Layout layout_for(int64_t k, int64_t r) {
   L.vscale = take((size_t)r * 4);
   L.lambda = take((size_t)r * 4);
   L.order = take((size_t)r * 4);
+  L.sweep_flag = take((size_t)(kJacobiSweeps + 1) * 4);
   L.total = off;
   return L;
 }
@@ -110,34 +120,31 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-// ---- Householder reflector j applied to a strip of 32 columns --------------------------------
-// V holds the (unscaled) reflector of column j in rows >= j of its column j: v_j = 1,
-// v_row = V[row][j] * vscale_j.  H_j = I - tau_j v v^T is applied to columns
-// col_begin + 32 blockIdx.x + (0..31) of the target matrix, rows >= j.
-// COMPUTE: derive tau_j and vscale_j from column j first (QR factorisation; target == V and
-// col_begin = j + 1) and let block 0 publish them; otherwise read them (forming Q).
+// ---- Householder reflector j applied to 32 columns (fallback for short sides beyond 4096) -------
+// Element (row, col) of Z lives at Zt[col * k + row].  Column j (rows > j) holds the unscaled
+// reflector, v_j = 1, v_row = Z[row][j] * vscale_j.  H_j = I - tau_j v v^T is applied to columns
+// col_begin + 32 blockIdx.x + (0..31) of the target, rows >= j.  Each column is handled by one
+// 32-lane half-wave striding over the rows, so the inner product is a plain shuffle reduction.
+// COMPUTE: derive tau_j and vscale_j from column j first (factoring; target == Z, col_begin = j + 1)
+// and let block 0 publish them; otherwise read them (forming Q).
 template <bool COMPUTE>
 __global__ __launch_bounds__(1024) void householder_strip_kernel(const RefreshGroup grp, int j, int col_begin,
                                                                  int target_is_q) {
-  __shared__ float red[32][33];
   __shared__ float red1[16];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r, k = t.k;
-  const float* __restrict__ V = t.Z;
-  float* __restrict__ X = target_is_q ? t.Q : t.Z;
-  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int col = col_begin + 32 * blockIdx.x + c;
+  const float* __restrict__ vcol = t.Z + (size_t)j * k;  // column j of Z
+  const int cg = threadIdx.x >> 5, l32 = threadIdx.x & 31;
+  const int col = col_begin + 32 * blockIdx.x + cg;
   const bool active = col < r;
+  float* __restrict__ xcol = (target_is_q ? t.Q : t.Z) + (size_t)(active ? col : 0) * k;
 
   float tau, vs;
   if (COMPUTE) {
     float part = 0.f;
-    for (int row = j + 1 + threadIdx.x; row < k; row += 1024) {
-      const float x = V[(size_t)row * r + j];
-      part += x * x;
-    }
+    for (int row = j + 1 + threadIdx.x; row < k; row += 1024) part += vcol[row] * vcol[row];
     const float sigma = block_sum(part, red1);
-    const float x0 = V[(size_t)j * r + j];
+    const float x0 = vcol[j];
     if (sigma == 0.f) {
       tau = 0.f; vs = 0.f;
     } else {
@@ -149,47 +156,199 @@ __global__ __launch_bounds__(1024) void householder_strip_kernel(const RefreshGr
   } else {
     tau = t.tau[j]; vs = t.vscale[j];
   }
-  if (tau == 0.f) return;  // H_j = I (uniform over the block)
+  if (tau == 0.f || !active) return;  // H_j = I, or a column past the matrix (whole half-wave)
 
-  // w_c = X[j][col] + vs * sum_{row > j} V[row][j] X[row][col]
   float part = 0.f;
-  if (active)
-    for (int row = j + 1 + rg; row < k; row += 32) part += V[(size_t)row * r + j] * X[(size_t)row * r + col];
-  red[rg][c] = part;
-  __syncthreads();
-  if (rg == 0) {
-    float s = 0.f;
+  for (int row = j + 1 + l32; row < k; row += 32) part += vcol[row] * xcol[row];
 #pragma unroll
-    for (int g = 0; g < 32; ++g) s += red[g][c];
-    red[0][c] = active ? X[(size_t)j * r + col] + vs * s : 0.f;
-  }
-  __syncthreads();
-  const float w = red[0][c];
-  if (!active) return;
-  const float tw = tau * w;
-  if (rg == 0) X[(size_t)j * r + col] -= tw;
+  for (int o = 16; o > 0; o >>= 1) part += __shfl_xor(part, o, 32);
+  const float tw = tau * (xcol[j] + vs * part);
   const float tws = tw * vs;
-  for (int row = j + 1 + rg; row < k; row += 32) X[(size_t)row * r + col] -= V[(size_t)row * r + j] * tws;
+  for (int row = j + 1 + l32; row < k; row += 32) xcol[row] -= vcol[row] * tws;
+  if (l32 == 0) xcol[j] -= tw;
 }
 
-// Q <- [I_r ; 0]
-__global__ __launch_bounds__(256) void identity_fill_kernel(const RefreshGroup grp, int which /*0: Q, 1: Jt*/) {
+// ---- blocked Householder (panels of kNB reflectors), for k <= 1024 * kRPT -----------------------
+// Thread t of the 1024-thread block owns rows j0 + t + 1024 s (s < kRPT) and keeps them in
+// registers, so a panel is read and written once however many reflectors touch it.
+
+// Sum NV values over the block of 16 waves; every thread gets all sums.  red: [17][NV] floats.
+template <int NV>
+__device__ __forceinline__ void block_sum_vec(float (&v)[NV], float* red) {
+#pragma unroll
+  for (int c = 0; c < NV; ++c) v[c] = wave_sum(v[c]);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();  // earlier readers of `red` are done
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int c = 0; c < NV; ++c) red[wave * NV + c] = v[c];
+  }
+  __syncthreads();
+  if (threadIdx.x < NV) {  // one thread per value adds the 16 wave sums, in a fixed order
+    float s = 0.f;
+    for (int w = 0; w < 16; ++w) s += red[w * NV + threadIdx.x];
+    red[16 * NV + threadIdx.x] = s;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < NV; ++c) v[c] = red[16 * NV + c];
+}
+
+// Factor columns [j0, j0 + nb) of Z below row j0: LAPACK-style reflectors, column j keeps the
+// unscaled vector below its diagonal, tau_j and the scale 1 / (x0 - beta) go to side arrays.
+__global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGroup grp, int j0, int nb) {
+  __shared__ float red[17 * kNB];
+  __shared__ float bc[kNB + 1];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int k = t.k;
+  float* __restrict__ Z = t.Z;  // element (row, col) at Z[col * k + row]
+  const int tid = threadIdx.x;
+  float x[kRPT][kNB];
+#pragma unroll
+  for (int s = 0; s < kRPT; ++s) {
+    const int row = j0 + tid + 1024 * s;
+#pragma unroll
+    for (int c = 0; c < kNB; ++c) x[s][c] = (row < k && c < nb) ? Z[(size_t)(j0 + c) * k + row] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < kNB; ++i) {
+    if (i >= nb) break;
+    const int j = j0 + i;
+    // dot products of column i (rows > j) with itself and with the later panel columns
+    float d[kNB];
+#pragma unroll
+    for (int c = 0; c < kNB; ++c) {
+      float a = 0.f;
+      if (c >= i) {
+#pragma unroll
+        for (int s = 0; s < kRPT; ++s)
+          if (j0 + tid + 1024 * s > j) a += x[s][i] * x[s][c];
+      }
+      d[c] = a;
+    }
+    if (tid == i) {  // owner of row j publishes that row of the panel
+#pragma unroll
+      for (int c = 0; c < kNB; ++c) bc[c] = x[0][c];
+    }
+    block_sum_vec<kNB>(d, red);  // its barriers also publish bc
+    const float x0 = bc[i];
+    const float sigma = d[i];
+    float tau = 0.f, vs = 0.f;
+    if (sigma != 0.f) {
+      const float beta = -copysignf(sqrtf(x0 * x0 + sigma), x0);
+      tau = (beta - x0) / beta;
+      vs = 1.0f / (x0 - beta);
+    }
+    if (tid == 0) { t.tau[j] = tau; t.vscale[j] = vs; }
+    if (tau != 0.f) {
+#pragma unroll
+      for (int c = 0; c < kNB; ++c) {
+        if (c <= i) continue;
+        const float tw = tau * (bc[c] + vs * d[c]);
+#pragma unroll
+        for (int s = 0; s < kRPT; ++s) {
+          const int row = j0 + tid + 1024 * s;
+          if (row == j) x[s][c] -= tw;
+          else if (row > j) x[s][c] -= tw * vs * x[s][i];
+        }
+      }
+    }
+    __syncthreads();  // bc is rewritten in the next round
+  }
+#pragma unroll
+  for (int s = 0; s < kRPT; ++s) {
+    const int row = j0 + tid + 1024 * s;
+    if (row < k) {
+#pragma unroll
+      for (int c = 0; c < kNB; ++c)
+        if (c < nb) Z[(size_t)(j0 + c) * k + row] = x[s][c];
+    }
+  }
+}
+
+// Apply the nb reflectors of panel j0 (stored in Z) to columns col_begin + kSW blockIdx.x + (0..kSW-1)
+// of the target (Z itself while factoring, Q while forming the orthogonal factor), rows >= j0,
+// in forward order (H_nb-1 ... H_0 X: factoring) or reverse order (H_0 ... H_nb-1 X: forming Q).
+__global__ __launch_bounds__(1024) void householder_block_apply_kernel(const RefreshGroup grp, int j0, int nb, int col_begin,
+                                                                       int target_is_q, int reverse) {
+  __shared__ float red[17 * kSW];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int r = grp.r, k = t.k;
+  const float* __restrict__ Zv = t.Z;
+  float* __restrict__ X = target_is_q ? t.Q : t.Z;
+  const int tid = threadIdx.x;
+  const int c0 = col_begin + kSW * blockIdx.x;
+  // v[s][ii]: entry of the ii-th reflector IN APPLICATION ORDER (unit diagonal, zeros above it)
+  float v[kRPT][kNB], x[kRPT][kSW];
+#pragma unroll
+  for (int s = 0; s < kRPT; ++s) {
+    const int row = j0 + tid + 1024 * s;
+#pragma unroll
+    for (int ii = 0; ii < kNB; ++ii) {
+      float e = 0.f;
+      if (row < k && ii < nb) {
+        const int j = j0 + (reverse ? nb - 1 - ii : ii);
+        if (row > j) e = Zv[(size_t)j * k + row] * t.vscale[j];
+        else if (row == j) e = 1.f;
+      }
+      v[s][ii] = e;
+    }
+#pragma unroll
+    for (int c = 0; c < kSW; ++c) x[s][c] = (row < k && c0 + c < r) ? X[(size_t)(c0 + c) * k + row] : 0.f;
+  }
+#pragma unroll
+  for (int ii = 0; ii < kNB; ++ii) {
+    if (ii >= nb) break;
+    const float tau = t.tau[j0 + (reverse ? nb - 1 - ii : ii)];
+    if (tau == 0.f) continue;  // uniform over the block
+    float w[kSW];
+#pragma unroll
+    for (int c = 0; c < kSW; ++c) {
+      float a = 0.f;
+#pragma unroll
+      for (int s = 0; s < kRPT; ++s) a += v[s][ii] * x[s][c];
+      w[c] = a;
+    }
+    block_sum_vec<kSW>(w, red);
+#pragma unroll
+    for (int s = 0; s < kRPT; ++s) {
+      const float tv = tau * v[s][ii];
+#pragma unroll
+      for (int c = 0; c < kSW; ++c) x[s][c] -= tv * w[c];
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < kRPT; ++s) {
+    const int row = j0 + tid + 1024 * s;
+    if (row < k) {
+#pragma unroll
+      for (int c = 0; c < kSW; ++c)
+        if (c0 + c < r) X[(size_t)(c0 + c) * k + row] = x[s][c];
+    }
+  }
+}
+
+// which 0: Qt <- [I_r 0] (r x k);  which 1: Jt <- I_r and the sweep flags <- 0
+__global__ __launch_bounds__(256) void identity_fill_kernel(const RefreshGroup grp, int which) {
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
+  if (which == 1 && blockIdx.x == 0 && threadIdx.x <= kJacobiSweeps) t.sweep_flag[threadIdx.x] = 0;
   float* X = which == 0 ? t.Q : t.Jt;
-  const int64_t count = (int64_t)(which == 0 ? t.k : r) * r;
+  const int64_t width = which == 0 ? t.k : r;
+  const int64_t count = width * r;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
-    X[i] = (i / r == i % r) ? 1.f : 0.f;
+    X[i] = (i / width == i % width) ? 1.f : 0.f;
 }
 
 // ---- one-sided Jacobi on the rows of Bw ----------------------------------------------------------
 // Round `round` of a round-robin tournament over n = r (+1 if odd) players: pair s = 0 is
 // (n-1, round); pair s > 0 is ((round + s) mod (n-1), (round - s) mod (n-1)).
-__global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup grp, int round, int n) {
+__global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup grp, int round, int n, int sweep) {
   __shared__ float red[3][4];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
+  if (sweep > 0 && t.sweep_flag[sweep - 1] == 0) return;  // the previous sweep rotated nothing: converged
   const int s = blockIdx.x;
   int p, q;
   if (s == 0) { p = n - 1; q = round; }
@@ -216,6 +375,7 @@ __global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup gr
   const float tt = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
   const float cs = 1.f / sqrtf(1.f + tt * tt);
   const float sn = cs * tt;
+  if (threadIdx.x == 0) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
   float* jp = t.Jt + (size_t)p * r;
   float* jq = t.Jt + (size_t)q * r;
   for (int i = threadIdx.x; i < r; i += 256) {
@@ -264,7 +424,7 @@ __global__ __launch_bounds__(256) void ritz_order_kernel(const RefreshGroup grp)
   }
 }
 
-// S[kk][order[i]] = Jt[i][kk] / |Jt[i]|
+// St[order[i]][:] = Jt[i][:] / |Jt[i]|
 __global__ __launch_bounds__(256) void ritz_vectors_kernel(const RefreshGroup grp) {
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
@@ -272,43 +432,37 @@ __global__ __launch_bounds__(256) void ritz_vectors_kernel(const RefreshGroup gr
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
     const int i = (int)(e / r), kk = (int)(e % r);
-    t.S[(size_t)kk * r + t.order[i]] = t.Jt[e] * t.tau[i];
+    t.S[(size_t)t.order[i] * r + kk] = t.Jt[e] * t.tau[i];
   }
 }
 
-// proj[:, col] = sign * Z[:, col] with sign chosen so the entry of largest magnitude (lowest row
-// on ties) is positive; stored in the projector's dtype (round to nearest even for bf16).
+// proj_t[c][:] = sign * Zt[c][:] with the sign chosen so the entry of largest magnitude (lowest
+// index on ties) is positive; stored in the projector's dtype (round to nearest even for bf16).
+// One block per projector column (= row of Zt).
 template <class T>
-__global__ __launch_bounds__(1024) void finalize_projector_kernel(const RefreshGroup grp) {
-  __shared__ float bestv[32][33];
-  __shared__ int bestr[32][33];
+__global__ __launch_bounds__(256) void finalize_projector_kernel(const RefreshGroup grp) {
+  __shared__ float bestv[256];
+  __shared__ int besti[256];
   const RefreshTensor& t = grp.t[blockIdx.y];
-  const int r = grp.r, k = t.k;
-  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int col = 32 * blockIdx.x + c;
-  const bool active = col < r;
-  float bv = -1.f; int br = 0x7fffffff;
-  if (active)
-    for (int row = rg; row < k; row += 32) {
-      const float x = fabsf(t.Z[(size_t)row * r + col]);
-      if (x > bv) { bv = x; br = row; }   // rows ascend per thread: first maximum kept
-    }
-  bestv[rg][c] = bv; bestr[rg][c] = br;
-  __syncthreads();
-  if (rg == 0) {
-    float v = bestv[0][c]; int rw = bestr[0][c];
-    for (int g = 1; g < 32; ++g) {
-      const float x = bestv[g][c]; const int y = bestr[g][c];
-      if (x > v || (x == v && y < rw)) { v = x; rw = y; }
-    }
-    bestr[0][c] = rw;
+  const int k = t.k, c = blockIdx.x;
+  const float* __restrict__ z = t.Z + (size_t)c * k;
+  float bv = -1.f; int bi = 0x7fffffff;
+  for (int row = threadIdx.x; row < k; row += 256) {
+    const float x = fabsf(z[row]);
+    if (x > bv) { bv = x; bi = row; }  // rows ascend per thread: first maximum kept
   }
+  bestv[threadIdx.x] = bv; besti[threadIdx.x] = bi;
   __syncthreads();
-  if (!active) return;
-  const int arg = bestr[0][c];
-  const float sgn = t.Z[(size_t)arg * r + col] < 0.f ? -1.f : 1.f;
-  T* P = static_cast<T*>(t.proj);
-  for (int row = rg; row < k; row += 32) P[(size_t)row * t.ldp + col] = (T)(sgn * t.Z[(size_t)row * r + col]);
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) {
+      const float x = bestv[threadIdx.x + o]; const int y = besti[threadIdx.x + o];
+      if (x > bestv[threadIdx.x] || (x == bestv[threadIdx.x] && y < besti[threadIdx.x])) { bestv[threadIdx.x] = x; besti[threadIdx.x] = y; }
+    }
+    __syncthreads();
+  }
+  const float sgn = z[besti[0]] < 0.f ? -1.f : 1.f;
+  T* P = static_cast<T*>(t.proj_t) + (size_t)c * t.ldpt;
+  for (int row = threadIdx.x; row < k; row += 256) P[row] = (T)(sgn * z[row]);
 }
 
 inline unsigned blocks_for(int64_t count, int per_block, unsigned cap) {
@@ -352,9 +506,10 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     t.vscale = reinterpret_cast<float*>(it.ws + L.vscale);
     t.lambda = reinterpret_cast<float*>(it.ws + L.lambda);
     t.order = reinterpret_cast<int32_t*>(it.ws + L.order);
-    t.proj = it.proj;
+    t.sweep_flag = reinterpret_cast<int32_t*>(it.ws + L.sweep_flag);
+    t.proj_t = it.proj_t;
     t.k = (int32_t)k;
-    t.ldp = (int32_t)it.ldp;
+    t.ldpt = (int32_t)it.ldpt;
     t.seed = it.seed;
     kmax = k > kmax ? k : kmax;
   }
@@ -387,32 +542,54 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     for (int i = 0; i < n; ++i) {
       const RefreshTensor& t = grp.t[i];
       GemmProblem& p = g.p[i];
-      if (which == 0) {         // Z (k x r) = C Q
-        p.A = t.C; p.lda = t.k; p.B = t.Q; p.ldb = r; p.M = t.k; p.N = r; p.K = t.k; p.C = t.Z; p.ldc = r;
-      } else if (which == 1) {  // Bw (r x r) = Q^T Z
-        p.A = t.Q; p.lda = r; p.B = t.Z; p.ldb = r; p.M = r; p.N = r; p.K = t.k; p.C = t.Bw; p.ldc = r;
-      } else {                  // Z (k x r) = Q S
-        p.A = t.Q; p.lda = r; p.B = t.S; p.ldb = r; p.M = t.k; p.N = r; p.K = r; p.C = t.Z; p.ldc = r;
+      if (which == 0) {         // Zt (r x k) = Qt C     (C symmetric)
+        p.A = t.Q; p.lda = t.k; p.B = t.C; p.ldb = t.k; p.M = r; p.N = t.k; p.K = t.k; p.C = t.Z; p.ldc = t.k;
+      } else if (which == 1) {  // Bw (r x r) = Qt Zt^T = Q^T C Q
+        p.A = t.Q; p.lda = t.k; p.B = t.Z; p.ldb = t.k; p.M = r; p.N = r; p.K = t.k; p.C = t.Bw; p.ldc = r;
+      } else {                  // Zt (r x k) = St Qt = (Q S)^T
+        p.A = t.S; p.lda = r; p.B = t.Q; p.ldb = t.k; p.M = r; p.N = t.k; p.K = r; p.C = t.Z; p.ldc = t.k;
       }
     }
-    return launch_gemm_group(g, DType::F32, which != 1, false, Epilogue::StoreF32, stream);
+    return launch_gemm_group(g, DType::F32, true, which == 1, Epilogue::StoreF32, stream);
   };
 
   for (int it = 0; it < iters; ++it) {
     GALORE_RETURN_IF(gemm_f32(0));
-    // Householder QR of Z, reflector by reflector
-    for (int j = 0; j < r; ++j) {
-      const int ncols = r - (j + 1);
-      const dim3 grid(ncols > 0 ? (ncols + 31) / 32 : 1, n);
-      hipLaunchKernelGGL(householder_strip_kernel<true>, grid, dim3(1024), 0, stream, grp, j, j + 1, 0);
+    // Householder QR of Z
+    if (kmax <= 1024 * kRPT) {
+      // blocked: factor a panel of kNB columns, apply its reflectors to the trailing columns
+      for (int j0 = 0; j0 < r; j0 += kNB) {
+        const int nb = r - j0 < kNB ? r - j0 : kNB;
+        hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
+        const int ncols = r - (j0 + nb);
+        if (ncols > 0)
+          hipLaunchKernelGGL(householder_block_apply_kernel, dim3((ncols + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+                             j0, nb, j0 + nb, 0, 0);
+      }
+      GALORE_RETURN_IF(hipGetLastError());
+      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+      const int last = (r - 1) / kNB * kNB;
+      for (int j0 = last; j0 >= 0; j0 -= kNB) {
+        const int nb = r - j0 < kNB ? r - j0 : kNB;
+        hipLaunchKernelGGL(householder_block_apply_kernel, dim3((r - j0 + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+                           j0, nb, j0, 1, 1);
+      }
+      GALORE_RETURN_IF(hipGetLastError());
+    } else {
+      // tall fallback (short side beyond the register-resident panel): reflector by reflector
+      for (int j = 0; j < r; ++j) {
+        const int ncols = r - (j + 1);
+        const dim3 grid(ncols > 0 ? (ncols + 31) / 32 : 1, n);
+        hipLaunchKernelGGL(householder_strip_kernel<true>, grid, dim3(1024), 0, stream, grp, j, j + 1, 0);
+      }
+      GALORE_RETURN_IF(hipGetLastError());
+      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+      for (int j = r - 1; j >= 0; --j) {
+        const dim3 grid((r - j + 31) / 32, n);
+        hipLaunchKernelGGL(householder_strip_kernel<false>, grid, dim3(1024), 0, stream, grp, j, j, 1);
+      }
+      GALORE_RETURN_IF(hipGetLastError());
     }
-    GALORE_RETURN_IF(hipGetLastError());
-    hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
-    for (int j = r - 1; j >= 0; --j) {
-      const dim3 grid((r - j + 31) / 32, n);
-      hipLaunchKernelGGL(householder_strip_kernel<false>, grid, dim3(1024), 0, stream, grp, j, j, 1);
-    }
-    GALORE_RETURN_IF(hipGetLastError());
   }
 
   // Rayleigh-Ritz
@@ -423,7 +600,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
   if (r > 1)
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
-        hipLaunchKernelGGL(jacobi_round_kernel, dim3(players / 2, n), dim3(256), 0, stream, grp, round, players);
+        hipLaunchKernelGGL(jacobi_round_kernel, dim3(players / 2, n), dim3(256), 0, stream, grp, round, players, sweep);
   GALORE_RETURN_IF(hipGetLastError());
   hipLaunchKernelGGL(ritz_values_kernel, dim3(r, n), dim3(256), 0, stream, grp);
   hipLaunchKernelGGL(ritz_order_kernel, dim3((r + 255) / 256, n), dim3(256), 0, stream, grp);
@@ -439,10 +616,20 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     for (int i = 0; i < n; ++i)
       if (items[i].dt == dt) sub.t[sub.count++] = grp.t[i];
     if (sub.count == 0) continue;
-    const dim3 grid((r + 31) / 32, sub.count);
-    if (dt == DType::F32) hipLaunchKernelGGL(finalize_projector_kernel<float>, grid, dim3(1024), 0, stream, sub);
-    else hipLaunchKernelGGL(finalize_projector_kernel<__bf16>, grid, dim3(1024), 0, stream, sub);
+    const dim3 grid(r, sub.count);
+    if (dt == DType::F32) hipLaunchKernelGGL(finalize_projector_kernel<float>, grid, dim3(256), 0, stream, sub);
+    else hipLaunchKernelGGL(finalize_projector_kernel<__bf16>, grid, dim3(256), 0, stream, sub);
     GALORE_RETURN_IF(hipGetLastError());
+    // the projector proper (k x r) is the transpose of what was just written
+    TransposeGroup tg{};
+    for (int i = 0; i < n; ++i) {
+      if (items[i].dt != dt) continue;
+      TransposeProblem& p = tg.p[tg.count++];
+      p.src = items[i].proj_t; p.lds = (int)items[i].ldpt;
+      p.dst = items[i].proj; p.ldd = (int)items[i].ldp;
+      p.rows = r; p.cols = grp.t[i].k;
+    }
+    GALORE_RETURN_IF(launch_transpose_group(tg, dt, stream));
   }
   return hipSuccess;
 }

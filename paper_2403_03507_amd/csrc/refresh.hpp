@@ -12,6 +12,8 @@ struct RefreshItem {
   DType dt;
   void* proj;         // output projector (short side x r), dtype dt, leading dimension ldp
   int64_t ldp;
+  void* proj_t;       // output, the projector transposed (r x short side), leading dimension ldpt
+  int64_t ldpt;
   unsigned char* ws;  // refresh_workspace_bytes(short side, r) bytes, 256-byte aligned
   uint64_t seed;      // seed of the Gaussian start block
 };

@@ -43,6 +43,7 @@ def test_gapped_spectrum_subspace_fp32(shape):
     assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
     # columns are the singular vectors themselves, ordered by decreasing singular value, signed
     assert np.all(np.abs(np.sum(P * P0, axis=0)) >= 1 - 1e-4)
+    np.testing.assert_array_equal(to64(opt.proj_t[0]), P.T)   # the transposed copy is kept in step
     for c in range(r):
         assert P[np.argmax(np.abs(P[:, c])), c] > 0
     np.testing.assert_allclose(np.sum(P * P0, axis=0), 1.0, atol=1e-4)
@@ -126,6 +127,26 @@ def test_edge_ranks(shape, r):
         assert _proj_dist(P, P0) <= 1e-3
     else:  # full rank: P P^T = I, and projecting loses nothing
         assert np.abs(P @ P.T - np.eye(k)).max() <= 1e-5
+    opt.close()
+
+
+def test_short_side_beyond_4096_takes_the_per_reflector_path():
+    # The panel QR keeps 4096 rows in registers; a taller short side falls back to one launch per
+    # reflector.  Too large for the oracle's Jacobi SVD, so properties that hold at any size are
+    # checked against the generator's own construction: G = U diag(s) V^T + noise with known U.
+    m, n, r = 4100, 4160, 8
+    src = wl.GradientSource(m, n, 44, "gapped", gap_rank=r)
+    G = src.grad(0)
+    opt = _refresh([G], r, iters=6)
+    P = to64(opt.proj[0])
+    assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
+    U = to64(src.U)                      # signal directions; noise tilts the true subspace by ~noise/gap
+    assert np.linalg.norm(P @ P.T - U @ U.T) <= 0.5   # an unrelated subspace would give sqrt(2r) = 4
+    G64 = to64(G)
+    captured = np.sum((P.T @ G64) ** 2)
+    signal = np.sum(to64(src.sigma) ** 2)
+    assert captured >= 0.999 * signal
+    np.testing.assert_array_equal(to64(opt.proj_t[0]), P.T)
     opt.close()
 
 
