@@ -31,6 +31,10 @@ using CfgDl = DlCfg<256, 256, 32, 2, 4, 3>;
 using CfgDl = DlCfg<256, 128, 64, 4, 2, 2>;
 #elif GALORE_DL_VARIANT == 9
 using CfgDl = DlCfg<256, 256, 32, 2, 2, 4>;
+#elif GALORE_DL_VARIANT == 10
+using CfgDl = DlCfg<256, 256, 32, 2, 4, 4>;
+#elif GALORE_DL_VARIANT == 11
+using CfgDl = DlCfg<256, 256, 32, 2, 4, 5>;
 #endif
 
 template <class T, bool AK, bool BKC, Epilogue EPI>

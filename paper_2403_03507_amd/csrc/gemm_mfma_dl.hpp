@@ -159,6 +159,21 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     opb.issue(reinterpret_cast<const unsigned char*>(B) + kt * b_step, st + AOp::TILE_BYTES, wave);
   };
 
+  // Epilogue geometry (see below): after a trip through LDS each lane owns 8 consecutive
+  // columns of row (32 i + ps RPP + rr) of its wave's tile.
+  constexpr int WN = Cfg::WN;
+  constexpr int PITCH = WN + 8;
+  constexpr int LPR = WN / 8;        // lanes per row
+  constexpr int RPP = 64 / LPR;      // rows per pass
+  constexpr int PASSES = 32 / RPP;
+  const int ldc = pr.ldc;
+  const int rr = lane / LPR, cc = (lane % LPR) * 8;
+  const int col = n0 + wn0 + cc;
+  // The weight update reads W; those loads are issued during the last K step so their latency
+  // hides behind its MFMAs instead of sitting in front of the epilogue.
+  bf16x8 wpre[TM][PASSES];
+  bool wok[TM][PASSES];
+
   // prologue: S - 1 tiles in flight (empty groups keep the wait counts uniform)
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
@@ -168,10 +183,23 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     // tile kt has landed once at most the loads of the younger tiles are outstanding
     if (kt + S - 2 < KT) wait_vmcnt<(S - 2) * LOADS>();
     else wait_vmcnt<0>();
+#ifndef GALORE_EXPERIMENT_NO_BARRIER
     __syncthreads();  // everyone's pieces of tile kt are visible; everyone is done with tile kt - 1
+#endif
 #ifndef GALORE_EXPERIMENT_NO_LOAD
     if (kt + S - 1 < KT) issue_tile(kt + S - 1);  // refills the stage consumed at kt - 1
 #endif
+    if (EPI == Epilogue::ApplyW && kt == KT - 1) {
+      const __bf16* W = static_cast<const __bf16*>(pr.C);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+          const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
+          wok[i][ps] = row < M && col < N;
+          if (wok[i][ps]) wpre[i][ps] = *reinterpret_cast<const bf16x8*>(W + (size_t)row * ldc + col);
+        }
+    }
 
     const unsigned char* as = smem_dl + (kt % S) * STAGE_BYTES;
     const unsigned char* bs = as + AOp::TILE_BYTES;
@@ -179,10 +207,17 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[TM], fb[TN];
+#ifdef GALORE_EXPERIMENT_NO_LDSREAD
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(smem_dl, wm0 + 32 * i, 0, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(smem_dl, wn0 + 32 * j, 0, lane);
+#else
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(as, wm0 + 32 * i, kk, lane);
 #pragma unroll
       for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(bs, wn0 + 32 * j, kk, lane);
+#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -197,17 +232,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   // global access 2 or 4 bytes wide.  Each wave therefore parks a 32-row strip of its tile in LDS
   // (fp32, row pitch WN + 8 so both the column-wise writes and the row-wise reads spread over
   // the banks) and re-reads it with 8 consecutive columns per lane.
-  constexpr int WN = Cfg::WN;
-  constexpr int PITCH = WN + 8;
-  constexpr int LPR = WN / 8;        // lanes per row
-  constexpr int RPP = 64 / LPR;      // rows per pass
-  constexpr int PASSES = 32 / RPP;
   static_assert(NW * 32 * PITCH * 4 <= S * STAGE_BYTES, "epilogue strips must fit the tile ring");
   __syncthreads();  // every wave has finished reading the last tile
   float* strip = reinterpret_cast<float*>(smem_dl) + wave * (32 * PITCH);
-  const int ldc = pr.ldc;
-  const int rr = lane / LPR, cc = (lane % LPR) * 8;
-  const int col = n0 + wn0 + cc;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -224,23 +251,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     }
     if (EPI == Epilogue::ApplyW) {
       __bf16* W = static_cast<__bf16*>(pr.C);
-      bf16x8 w[PASSES];
-      bool ok[PASSES];
 #pragma unroll
       for (int ps = 0; ps < PASSES; ++ps) {
-        const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
-        ok[ps] = row < M && col < N;
-        if (ok[ps]) w[ps] = *reinterpret_cast<const bf16x8*>(W + (size_t)row * ldc + col);
-      }
-#pragma unroll
-      for (int ps = 0; ps < PASSES; ++ps) {
-        if (!ok[ps]) continue;
+        if (!wok[i][ps]) continue;
         const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
         bf16x8 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          o[e] = (__bf16)(pr.s0 * (float)w[ps][e] - pr.s1 * lo[ps][e]);
-          o[e + 4] = (__bf16)(pr.s0 * (float)w[ps][e + 4] - pr.s1 * hi[ps][e]);
+          o[e] = (__bf16)(pr.s0 * (float)wpre[i][ps][e] - pr.s1 * lo[ps][e]);
+          o[e + 4] = (__bf16)(pr.s0 * (float)wpre[i][ps][e + 4] - pr.s1 * hi[ps][e]);
         }
         *reinterpret_cast<bf16x8*>(W + (size_t)row * ldc + col) = o;
       }
