@@ -30,6 +30,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--refresh-iters", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (nothing here uses a "

@@ -25,7 +25,8 @@ struct GemmProblem {
   int32_t M, N, K;
   int32_t lda, ldb, ldc;
   int32_t tile_begin;  // first block of this problem in the launch
-  int32_t tiles_m;     // tiles along M (tile id within problem: tm fastest)
+  int32_t tiles_m;     // tiles along M and N; tile ids are decoded by tile_coords()
+  int32_t tiles_n;
   float s0, s1, s2, s3;  // epilogue scalars
 };
 

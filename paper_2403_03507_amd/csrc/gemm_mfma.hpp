@@ -145,6 +145,21 @@ __device__ __forceinline__ int xcd_contiguous_block_id(int bid, int nblocks) {
   return xcd * base + (xcd < rem ? xcd : rem) + q;
 }
 
+// Tile id -> (tm, tn).  Tiles are numbered in bands of 4 tile-rows, and inside a band down the
+// rows first, so any 32 consecutive ids (what the CUs of one XCD work on at a time) form a
+// 4 x 8 patch of the output: they share 4 A panels and 8 B panels instead of streaming 32 + 32
+// panels through the XCD's L2.
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kBand = 4;
+  const int per_band = kBand * tiles_n;
+  const int band = t / per_band;
+  const int first = band * kBand;
+  const int height = tiles_m - first < kBand ? tiles_m - first : kBand;
+  const int in_band = t - band * per_band;
+  tm = first + in_band % height;
+  tn = in_band / height;
+}
+
 template <class T> __device__ __forceinline__ float to_f32(T x) { return (float)x; }
 
 // ---- the kernel --------------------------------------------------------------------------------
@@ -176,8 +191,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_group_kernel(const GemmGroup grp
   for (int i = 1; i < grp.count; ++i)
     if (bid >= grp.p[i].tile_begin) pi = i;
   const GemmProblem& pr = grp.p[pi];
-  const int t = bid - pr.tile_begin;
-  const int tm = t % pr.tiles_m, tn = t / pr.tiles_m;
+  int tm, tn;
+  tile_coords(bid - pr.tile_begin, pr.tiles_m, pr.tiles_n, tm, tn);
   if (EPI == Epilogue::StoreSymF32 && tm > tn) return;
   const int m0 = tm * BM, n0 = tn * BN;
   const int M = pr.M, N = pr.N, K = pr.K;
@@ -287,7 +302,8 @@ template <class Cfg> inline void plan_tiles(GemmGroup& g) {
     GemmProblem& p = g.p[i];
     p.tile_begin = total;
     p.tiles_m = (p.M + Cfg::BM - 1) / Cfg::BM;
-    total += p.tiles_m * ((p.N + Cfg::BN - 1) / Cfg::BN);
+    p.tiles_n = (p.N + Cfg::BN - 1) / Cfg::BN;
+    total += p.tiles_m * p.tiles_n;
   }
   g.total_tiles = total;
 }

@@ -129,8 +129,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   for (int i = 1; i < grp.count; ++i)
     if (bid >= grp.p[i].tile_begin) pi = i;
   const GemmProblem& pr = grp.p[pi];
-  const int t = bid - pr.tile_begin;
-  const int tm = t % pr.tiles_m, tn = t / pr.tiles_m;
+  int tm, tn;
+  tile_coords(bid - pr.tile_begin, pr.tiles_m, pr.tiles_n, tm, tn);
   if (EPI == Epilogue::StoreSymF32 && tm > tn) return;
   const int m0 = tm * BM, n0 = tn * BN;
   const int M = pr.M, N = pr.N;
