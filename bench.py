@@ -20,6 +20,16 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch (one LLaMA-7B layer set, r = 1024) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# runs of paper_2403_03507_amd/traffic_probe.py, calibrated with a 1 GiB copy (see
+# profiles/step_llama7b_hbm_traffic.md).  Reported as roofline.traffic; null for other shapes.
+MEASURED_TRAFFIC_BYTES_7B = {
+    "project_left": 581.1e6 + 158.7e6,
+    "project_right": 205.6e6 + 45.2e6,
+    "back": 1093.8e6 + 404.8e6,
+    "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
+}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -30,6 +40,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--refresh-iters", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
 
     args = ap.parse_args()
     if args.gpus != 1:
@@ -73,6 +84,7 @@ def main():
     torch.cuda.synchronize()
 
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True)
+    gb.galore_set_concurrency(opt.ctx, args.lanes)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
 
@@ -109,7 +121,7 @@ def main():
     gb.galore_profile_start(opt.ctx)
     prof_total_ms = timed(lambda: [one_step(base + 2 * K + i) for i in range(K)])
     prof = gb.galore_profile_stop(opt.ctx)
-    gb.galore_set_concurrency(opt.ctx, 3)
+    gb.galore_set_concurrency(opt.ctx, args.lanes)
 
     # ---- roofline of the dominant kernel -----------------------------------------------------------
     left = [(m, n) for (m, n) in shapes if m <= n]
@@ -132,6 +144,9 @@ def main():
         roofline = {"kernel": "gemm_group_kernel/" + dominant, "bound": "mfma", "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
+    if args.config == "llama7b":
+        roofline["traffic"] = MEASURED_TRAFFIC_BYTES_7B[dominant]
+        roofline["traffic_unit"] = "bytes per launch (L2 fetch + write-back counters; cache hits in the 256 MB MALL are included)"
     per_stage = {}
     for k in gemm_stages:
         if prof[k][1]:
@@ -167,7 +182,8 @@ def main():
         "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, fp32 M/V, r=%d, per-layer calls in "
                                "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype, r, POOL),
-                   "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters},
+                   "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
+                   "concurrent_chains": args.lanes},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "stages": per_stage,
