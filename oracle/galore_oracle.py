@@ -113,6 +113,44 @@ def project(proj, G):
     return R
 
 
+def project_left(P, G):
+    """R (r x n) = P^T G whatever the shape of G (used on column subsets of a LEFT tensor)."""
+    G, P = _c(G), _c(P)
+    (m, n), r = G.shape, P.shape[1]
+    assert P.shape[0] == m
+    R = np.empty((r, n))
+    lib().oracle_project_left(_p(P), _p(G), _p(R), m, n, r)
+    return R
+
+
+def project_right(Q, G):
+    """R (m x r) = G Q whatever the shape of G (used on row subsets of a RIGHT tensor)."""
+    G, Q = _c(G), _c(Q)
+    (m, n), r = G.shape, Q.shape[1]
+    assert Q.shape[0] == n
+    R = np.empty((m, r))
+    lib().oracle_project_right(_p(G), _p(Q), _p(R), m, n, r)
+    return R
+
+
+def apply_left(W, P, N, lr, alpha, weight_decay=0.0):
+    """In place W <- (1 - lr*wd) W - lr*alpha * P N, whatever the shape of W."""
+    P, N = _c(P), _c(N)
+    (m, n), r = W.shape, P.shape[1]
+    assert P.shape[0] == m and N.shape == (r, n)
+    lib().oracle_apply_left(_p(W), _p(P), _p(N), m, n, r, lr, alpha, weight_decay)
+    return W
+
+
+def apply_right(W, Q, N, lr, alpha, weight_decay=0.0):
+    """In place W <- (1 - lr*wd) W - lr*alpha * N Q^T, whatever the shape of W."""
+    Q, N = _c(Q), _c(N)
+    (m, n), r = W.shape, Q.shape[1]
+    assert Q.shape[0] == n and N.shape == (m, r)
+    lib().oracle_apply_right(_p(W), _p(N), _p(Q), m, n, r, lr, alpha, weight_decay)
+    return W
+
+
 def adam(R, M, V, beta1, beta2, eps, k):
     """In-place moment update; returns N.  k is the 1-based step number."""
     R = _c(R)

@@ -1,0 +1,81 @@
+"""Parity at the benchmark's full size and launch configuration: one LLaMA-7B-shaped layer set
+(4x 4096x4096, 2x 4096x11008, 11008x4096; bf16; r = 1024) stepped by one galore_step call with the
+default three concurrent chains, exactly as bench.py calls it.
+
+The oracle cannot afford the whole thing, but the step is separable: for a LEFT tensor column j of
+W, M, V depends only on column j of G (R[:, j] = P^T G[:, j], Adam is entry-wise, dW[:, j] = P N[:, j]);
+for a RIGHT tensor the same holds row-wise.  So the oracle runs the complete step on a sample of
+columns (rows) and every entry of those is compared."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, f32, relF, to64
+from oracle import galore_oracle as orc
+from paper_2403_03507_amd import binding as gb
+from paper_2403_03507_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_llama7b_layer_set_sampled_columns():
+    c = wl.CONFIGS["llama7b"]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    r, dtype, lr = c["rank"], "bf16", f32(1e-3)
+    dev = "cuda"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    srcs = wl.make_sources(c, seed=3, device=dev, layers=1)
+    W = [(torch.randn(m, n, generator=gen, device=dev) * 0.02).to(torch.bfloat16) for (m, n) in shapes]
+    W0 = [w.clone() for w in W]
+    opt = gb.GaLore(W, r, auto_refresh=False)            # default: three concurrent chains
+    for i, p in enumerate(opt.proj):
+        p.copy_(wl.random_orthonormal(p.shape[0], r, 50 + i, device=dev).to(torch.bfloat16))
+    steps = 2
+    Gs = [[s.grad(t) for s in srcs] for t in range(steps)]
+    for t in range(steps):
+        opt.step(W, Gs[t], lr)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(5)
+    for i, (m, n) in enumerate(shapes):
+        left = m <= n
+        long_side = n if left else m
+        # sample: the first and last index, tile-boundary neighbours and a few random ones
+        idx = np.unique(np.concatenate([[0, 1, 255, 256, 257, long_side - 257, long_side - 1],
+                                        rng.integers(0, long_side, 9)])).astype(np.int64)
+        sel = torch.from_numpy(idx).to(dev)
+        P = to64(opt.proj[i])
+        take = (lambda x: x[:, sel]) if left else (lambda x: x[sel, :])
+        Wo = orc.round_storage(to64(take(W0[i])), dtype)
+        Mo = np.zeros((r, len(idx)) if left else (len(idx), r))
+        Vo = np.zeros_like(Mo)
+        b1, b2, eps, alpha = f32(0.9), f32(0.999), f32(1e-8), f32(0.25)
+        for t in range(steps):                      # Algorithm 2 on the sampled columns (rows), storage rounding as on the device
+            G = to64(take(Gs[t][i]))
+            R = orc.project_left(P, G) if left else orc.project_right(P, G)
+            N = orc.adam(R, Mo, Vo, b1, b2, eps, t + 1)
+            (orc.apply_left if left else orc.apply_right)(Wo, P, N, lr, alpha, 0.0)
+            Wo = orc.round_storage(Wo, dtype)
+            Mo = orc.round_storage(Mo, "f32"); Vo = orc.round_storage(Vo, "f32")
+
+        class o:  # the names the checks below use
+            W, M, V = Wo, Mo, Vo
+        Wd = to64(W[i][:, sel] if left else W[i][sel, :])
+        Md = to64(opt.M[i][:, sel] if left else opt.M[i][sel, :])
+        Vd = to64(opt.V[i][:, sel] if left else opt.V[i][sel, :])
+        assert relF(Wd, o.W) <= TOL[dtype], (i, relF(Wd, o.W))
+        assert relF(Md, o.M) <= 1e-5, (i, relF(Md, o.M))
+        assert relF(Vd, o.V) <= 1e-5, (i, relF(Vd, o.V))
+        # bf16 storage: nearly every sampled weight equals the rounded oracle value; a rounding that
+        # falls the other way costs one ulp per step (ulp of the larger of old and new weight), and an
+        # entry of R within rounding distance of zero may flip the sign of its N at step 1, which moves a
+        # weight by at most 2 lr alpha |P_ik| (a small fraction of lr alpha)
+        before = to64(take(W0[i]))
+        ulp = np.maximum(np.maximum(np.abs(o.W), np.abs(before)), 2.0 ** -126) * 2.0 ** -7
+        assert np.all(np.abs(Wd - o.W) <= steps * ulp + 0.1 * lr * alpha)
+        print('tensor', i, (m, n), 'identical', np.mean(Wd == o.W), 'relF W/M/V', relF(Wd, o.W), relF(Md, o.M), relF(Vd, o.V))
+        assert np.mean(Wd == o.W) >= 0.98
+        # the step really moved the weights (so the comparison is not vacuous)
+        assert np.mean(Wd != before) > 0.2
+    opt.close()
