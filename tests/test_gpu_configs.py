@@ -1,0 +1,44 @@
+"""Step parity on one layer of each smaller BASELINE stack (130M, 350M, 1B shapes and gradient
+recipes), bf16 W/G, fp32 M/V.  The projector is a seeded orthonormal block rounded to bf16 (the
+oracle's own SVD at these sizes takes minutes; the refresh is gated separately), both sides get the
+same bits.  The 1B shapes include n = 5461: odd, so rows are not even 4-byte aligned and the GEMMs
+take their element-wise load path."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, f32, relF, to64
+from oracle import galore_oracle as orc
+from paper_2403_03507_amd import binding as gb
+from paper_2403_03507_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cfg", ["llama130m", "llama350m", "llama1b"])
+def test_one_layer_two_steps(cfg):
+    c = wl.CONFIGS[cfg]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    r, dtype, lr = c["rank"], c["dtype"], f32(1e-3)
+    srcs = wl.make_sources(cfg, seed=11, device="cpu", layers=1)
+    W0 = [wl.make_weight(m, n, 70 + i, dtype) for i, (m, n) in enumerate(shapes)]
+    Wd = [w.cuda() for w in W0]
+    opt = gb.GaLore(Wd, r, update_gap=c["update_gap"], auto_refresh=False)
+    oracles = []
+    for i, (m, n) in enumerate(shapes):
+        P = wl.random_orthonormal(min(m, n), r, 90 + i).to(torch.bfloat16)
+        opt.proj[i].copy_(P)
+        o = orc.GaLoreTensor(to64(W0[i]), r, update_gap=c["update_gap"], scale=f32(0.25), beta1=f32(0.9), beta2=f32(0.999),
+                             eps=f32(1e-8), dtype=dtype, auto_refresh=False)
+        o.set_projector(to64(P))
+        oracles.append(o)
+    for step in range(2):
+        G = [s.grad(step) for s in srcs]
+        opt.step(Wd, [g.cuda() for g in G], lr)
+        torch.cuda.synchronize()
+        for i, o in enumerate(oracles):
+            o.step(to64(G[i]), lr)
+            assert relF(to64(Wd[i]), o.W) <= TOL[dtype], (cfg, step, i)
+            assert relF(to64(opt.M[i]), o.M) <= 1e-5, (cfg, step, i)
+            assert relF(to64(opt.V[i]), o.V) <= 1e-5, (cfg, step, i)
+    opt.close()
