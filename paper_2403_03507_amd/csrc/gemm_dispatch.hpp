@@ -13,6 +13,9 @@
 namespace galore {
 
 using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
+// Measured on the 7B shapes (projection / back-projection TFLOP/s of a single 4096x11008 tensor):
+//   1: 256x256x64, 4 waves (128x128 each)  746 / 650     2: 256x256x64, 8 waves (128x64 each)  876 / 894
+//   3: 256x128x32, 4 waves, 3 stages       828 / 699     4: 128x128x64, 4 waves                878 / 711
 #if GALORE_DL_VARIANT == 1
 using CfgDl = DlCfg<256, 256, 64, 2, 2, 2>;
 #elif GALORE_DL_VARIANT == 2
@@ -20,21 +23,15 @@ using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;
 #elif GALORE_DL_VARIANT == 3
 using CfgDl = DlCfg<256, 128, 32, 2, 2, 3>;
 #elif GALORE_DL_VARIANT == 4
-using CfgDl = DlCfg<256, 128, 32, 2, 2, 2>;
-#elif GALORE_DL_VARIANT == 5
 using CfgDl = DlCfg<128, 128, 64, 2, 2, 2>;
+#elif GALORE_DL_VARIANT == 5
+using CfgDl = DlCfg<256, 128, 64, 2, 2, 3>;
 #elif GALORE_DL_VARIANT == 6
-using CfgDl = DlCfg<128, 256, 32, 2, 2, 3>;
+using CfgDl = DlCfg<256, 128, 64, 4, 2, 3>;
 #elif GALORE_DL_VARIANT == 7
-using CfgDl = DlCfg<256, 256, 32, 2, 4, 3>;
+using CfgDl = DlCfg<128, 256, 64, 2, 4, 3>;
 #elif GALORE_DL_VARIANT == 8
-using CfgDl = DlCfg<256, 128, 64, 4, 2, 2>;
-#elif GALORE_DL_VARIANT == 9
-using CfgDl = DlCfg<256, 256, 32, 2, 2, 4>;
-#elif GALORE_DL_VARIANT == 10
-using CfgDl = DlCfg<256, 256, 32, 2, 4, 4>;
-#elif GALORE_DL_VARIANT == 11
-using CfgDl = DlCfg<256, 256, 32, 2, 4, 5>;
+using CfgDl = DlCfg<128, 256, 64, 1, 4, 3>;
 #endif
 
 template <class T, bool AK, bool BKC, Epilogue EPI>

@@ -100,7 +100,6 @@ template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
       typedef s16x4 __attribute__((address_space(3))) * lds_v4;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * ROW_BYTES));
-      typedef short s16x8 __attribute__((ext_vector_type(8)));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
   }
@@ -183,12 +182,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     // tile kt has landed once at most the loads of the younger tiles are outstanding
     if (kt + S - 2 < KT) wait_vmcnt<(S - 2) * LOADS>();
     else wait_vmcnt<0>();
-#ifndef GALORE_EXPERIMENT_NO_BARRIER
     __syncthreads();  // everyone's pieces of tile kt are visible; everyone is done with tile kt - 1
-#endif
-#ifndef GALORE_EXPERIMENT_NO_LOAD
     if (kt + S - 1 < KT) issue_tile(kt + S - 1);  // refills the stage consumed at kt - 1
-#endif
     if (EPI == Epilogue::ApplyW && kt == KT - 1) {
       const __bf16* W = static_cast<const __bf16*>(pr.C);
 #pragma unroll
@@ -203,28 +198,19 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
 
     const unsigned char* as = smem_dl + (kt % S) * STAGE_BYTES;
     const unsigned char* bs = as + AOp::TILE_BYTES;
-#ifndef GALORE_EXPERIMENT_NO_MFMA
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[TM], fb[TN];
-#ifdef GALORE_EXPERIMENT_NO_LDSREAD
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(smem_dl, wm0 + 32 * i, 0, lane);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(smem_dl, wn0 + 32 * j, 0, lane);
-#else
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(as, wm0 + 32 * i, kk, lane);
 #pragma unroll
       for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(bs, wn0 + 32 * j, kk, lane);
-#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-#endif
   }
 
   // ---- epilogue: accumulators -> wave-private LDS strip -> row-contiguous 16/32-byte accesses ----
