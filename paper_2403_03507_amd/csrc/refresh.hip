@@ -12,14 +12,19 @@
 //     blocks of 8 trailing columns apply the 8 reflectors to register-resident data, so each
 //     panel costs one read and one write of the trailing matrix; Q is formed by applying the
 //     panels to [I; 0] backwards.  Short sides beyond 4096 fall back to one launch per reflector.
-//   * The r x r eigenproblem is solved by one-sided (Hestenes) Jacobi on the rows of B with
-//     round-robin pair ordering, one launch per round of r/2 disjoint pairs.
+//   * The r x r eigenproblem is solved by one-sided (Hestenes) Jacobi on the rows of B, blocked:
+//     a workgroup holds two blocks of 16 whole rows in LDS, orthogonalises them against each
+//     other and applies the accumulated 32 x 32 rotation to the eigenvector rows; block pairs
+//     follow a round-robin schedule, one launch per round of disjoint pairs.  (Rows longer than
+//     LDS allows fall back to one launch per round of row pairs.)
 // The iteration blocks are kept TRANSPOSED in memory (Qt, Zt: r x k row-major), so that a
 // column of Z - the thing a Householder reflector works on - is a contiguous row and every
 // access below is coalesced; C is symmetric, so Zt = Qt C needs no transposed GEMM either.
 // All tensors of a group advance in lock-step (blockIdx.y = tensor), nothing syncs the host,
 // iteration counts are fixed, and no atomics are used, so results are reproducible bit for bit.
 #include "refresh.hpp"
+
+#include <type_traits>
 
 namespace galore {
 
@@ -102,10 +107,23 @@ __global__ __launch_bounds__(256) void gaussian_fill_kernel(const RefreshGroup g
 }
 
 // ---- block reductions (wavefront shuffles, then LDS across the waves) ------------------------
+// Sum over the 64 lanes of a wavefront; every lane gets the result.  Data-parallel-primitive
+// moves inside the VALU (quad permutes, row mirrors, row broadcasts) instead of LDS-crossbar
+// shuffles: six dependent adds of a few cycles each where six ds_bpermute round trips took
+// well over a hundred cycles apiece.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  auto dpp = [](float x, auto ctrl, auto row_mask) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                 decltype(row_mask)::value, 0xF, false));
+  };
+  using std::integral_constant;
+  v += dpp(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});   // quad_perm [1,0,3,2]
+  v += dpp(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});   // quad_perm [2,3,0,1]
+  v += dpp(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});  // row_half_mirror
+  v += dpp(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});  // row_mirror: each row of 16 holds its sum
+  v += dpp(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast15 into rows 1 and 3
+  v += dpp(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // Sum over all threads of the block; every thread gets the result.  `red` holds >= 16 floats.
@@ -388,6 +406,128 @@ __global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup gr
   }
 }
 
+// ---- block one-sided Jacobi ------------------------------------------------------------------
+// The rows of Bw are cut into blocks of `b` rows.  One workgroup takes a pair of blocks (2b rows,
+// whole rows, in LDS), orthogonalises those rows against each other with `kInnerSweeps` sweeps of
+// the same Hestenes rotations (round-robin over the 2b rows, one row pair per wave and round),
+// accumulates the 2b x 2b product of the rotations, writes the rows back and applies the product
+// to the matching rows of Jt.  Block pairs of one launch are disjoint (round-robin over the
+// blocks), so a sweep over all pairs of rows costs (blocks - 1) launches that each read and write
+// Bw and Jt once, instead of (r - 1) launches.
+constexpr int kInnerSweeps = 1;
+constexpr int kJacobiMaxR = 1280;  // longest row the register-resident inner loop is unrolled for (5 float4 per lane and row)
+
+typedef float jf4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshGroup grp, int round, int nplayers, int b,
+                                                                  int sweep) {
+  extern __shared__ __align__(16) float jsm[];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int r = grp.r;
+  if (sweep > 0 && t.sweep_flag[sweep - 1] == 0) return;  // converged
+  const int nblocks = (r + b - 1) / b;
+  const int s = blockIdx.x;
+  int bi, bj;
+  if (s == 0) { bi = nplayers - 1; bj = round; }
+  else { bi = (round + s) % (nplayers - 1); bj = (round - s + (nplayers - 1)) % (nplayers - 1); }
+  if (bi > bj) { const int x = bi; bi = bj; bj = x; }
+  if (bi >= nblocks) return;                // both absent
+  const int rows2 = 2 * b;
+  const int rp = (r + 3) & ~3;               // LDS row pitch: rows padded with zeros to a multiple of 4
+  float* X = jsm;                            // [2b][rp]
+  float* RotT = jsm + (size_t)rows2 * rp;    // [2b][2b], RotT[j][i] = Rot[i][j]
+  __shared__ int rotated;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  auto grow = [&](int ls) { return ls < b ? bi * b + ls : bj * b + (ls - b); };  // local row -> row of Bw
+  auto present = [&](int ls) { return (ls < b || bj < nblocks) && grow(ls) < r; };
+
+  for (int e = tid; e < rows2 * rp; e += 1024) {
+    const int ls = e / rp, c = e - ls * rp;
+    X[e] = (c < r && present(ls)) ? t.Bw[(size_t)grow(ls) * r + c] : 0.f;
+  }
+  for (int e = tid; e < rows2 * rows2; e += 1024) RotT[e] = (e / rows2 == e % rows2) ? 1.f : 0.f;
+  if (tid == 0) rotated = 0;
+  __syncthreads();
+
+  constexpr int NV = kJacobiMaxR / 256;      // float4 per lane per row, upper bound
+  const int nv = rp / 4;                     // float4 per row
+  for (int isw = 0; isw < kInnerSweeps; ++isw)
+    for (int ir = 0; ir < rows2 - 1; ++ir) {
+      if (wave < b) {
+        int p, q;
+        if (wave == 0) { p = rows2 - 1; q = ir; }
+        else { p = (ir + wave) % (rows2 - 1); q = (ir - wave + (rows2 - 1)) % (rows2 - 1); }
+        if (p > q) { const int x = p; p = q; q = x; }
+        if (present(p) && present(q)) {          // wave-uniform
+          jf4* xp = reinterpret_cast<jf4*>(X + (size_t)p * rp);
+          jf4* xq = reinterpret_cast<jf4*>(X + (size_t)q * rp);
+          jf4 u[NV], v[NV];
+          float a = 0.f, bb = 0.f, c = 0.f;
+#pragma unroll
+          for (int i = 0; i < NV; ++i) {
+            const int e = lane + 64 * i;
+            if (e < nv) {
+              u[i] = xp[e]; v[i] = xq[e];
+#pragma unroll
+              for (int k = 0; k < 4; ++k) { a += u[i][k] * u[i][k]; bb += v[i][k] * v[i][k]; c += u[i][k] * v[i][k]; }
+            }
+          }
+          a = wave_sum(a); bb = wave_sum(bb); c = wave_sum(c);
+          if (a != 0.f && bb != 0.f && fabsf(c) > kJacobiTol * sqrtf(a) * sqrtf(bb)) {
+            const float zeta = (bb - a) / (2.f * c);
+            const float tt = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+            const float cs = 1.f / sqrtf(1.f + tt * tt);
+            const float sn = cs * tt;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+              const int e = lane + 64 * i;
+              if (e < nv) {
+                xp[e] = cs * u[i] - sn * v[i];
+                xq[e] = sn * u[i] + cs * v[i];
+              }
+            }
+            if (lane < rows2) {  // rows p, q of Rot = columns p, q of RotT
+              const float uu = RotT[lane * rows2 + p], vv = RotT[lane * rows2 + q];
+              RotT[lane * rows2 + p] = cs * uu - sn * vv;
+              RotT[lane * rows2 + q] = sn * uu + cs * vv;
+            }
+            if (lane == 0) rotated = 1;
+          }
+        }
+      }
+      __syncthreads();
+    }
+
+  if (rotated == 0) return;  // nothing changed: leave Bw, Jt and the sweep flag alone (uniform)
+  if (tid == 0) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
+  for (int e = tid; e < rows2 * rp; e += 1024) {
+    const int ls = e / rp, c = e - ls * rp;
+    if (c < r && present(ls)) t.Bw[(size_t)grow(ls) * r + c] = X[e];
+  }
+  // Jt rows <- Rot * Jt rows, one column per thread; RotT[j][:] is read as broadcast float4
+  for (int c = tid; c < r; c += 1024) {
+    float acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+    for (int j = 0; j < rows2; ++j) {
+      if (!present(j)) continue;
+      const float x = t.Jt[(size_t)grow(j) * r + c];
+      const jf4* rt = reinterpret_cast<const jf4*>(RotT + j * rows2);
+#pragma unroll
+      for (int i4 = 0; i4 < 8; ++i4) {
+        if (4 * i4 < rows2) {
+          const jf4 w = rt[i4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[4 * i4 + k] += w[k] * x;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+      if (i < rows2 && present(i)) t.Jt[(size_t)grow(i) * r + c] = acc[i];
+  }
+}
+
 // lambda_i = |row i of Bw| ; order[i] = number of rows that come before row i when sorted by
 // decreasing lambda (ties: lower index first).  The thousands of fp32 rotations let the length
 // of each accumulated eigenvector drift by a few 1e-6; tau[i] (free by now) gets 1 / |row i of Jt|
@@ -596,11 +736,31 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
   GALORE_RETURN_IF(gemm_f32(0));
   GALORE_RETURN_IF(gemm_f32(1));
   hipLaunchKernelGGL(identity_fill_kernel, dim3(blocks_for((int64_t)r * r, 256 * 8, 1024), n), dim3(256), 0, stream, grp, 1);
-  const int players = (r % 2 == 0) ? r : r + 1;
-  if (r > 1)
+  // rows per block so that two blocks of whole rows (plus the 2b x 2b rotation product) fit in LDS
+  int jb = 0;
+  for (int cand : {16, 8})
+    if (jb == 0 && (size_t)2 * cand * ((r + 3) & ~3) * 4 + (size_t)4 * cand * cand * 4 <= 150 * 1024) jb = cand;
+  if (r > kJacobiMaxR) jb = 0;  // the inner loop keeps a row pair in registers, unrolled for rows up to kJacobiMaxR
+  if (r > 1 && jb > 0) {
+    const size_t smem = (size_t)2 * jb * ((r + 3) & ~3) * 4 + (size_t)4 * jb * jb * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+      GALORE_RETURN_IF(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_round_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+      attr_set = true;
+    }
+    const int nblocks = (r + jb - 1) / jb;
+    const int players = (nblocks % 2 == 0) ? nblocks : nblocks + 1;   // >= 2
+    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
+      for (int round = 0; round < players - 1; ++round)
+        hipLaunchKernelGGL(jacobi_block_round_kernel, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players,
+                           jb, sweep);
+  } else if (r > 1) {  // rows too long for LDS: one launch per round of row pairs
+    const int players = (r % 2 == 0) ? r : r + 1;
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
         hipLaunchKernelGGL(jacobi_round_kernel, dim3(players / 2, n), dim3(256), 0, stream, grp, round, players, sweep);
+  }
   GALORE_RETURN_IF(hipGetLastError());
   hipLaunchKernelGGL(ritz_values_kernel, dim3(r, n), dim3(256), 0, stream, grp);
   hipLaunchKernelGGL(ritz_order_kernel, dim3((r + 255) / 256, n), dim3(256), 0, stream, grp);
