@@ -34,7 +34,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kJacobiSweeps = 10;   // upper bound; sweeps after convergence return at once
-constexpr float kJacobiTol = 4e-6f;  // |b_p.b_q| <= tol |b_p||b_q|: the rounding floor of an fp32 dot of length r
+constexpr float kJacobiTol = 1e-5f;  // |b_p.b_q| <= tol |b_p||b_q|: a few times the rounding floor of an fp32 dot of length r
 constexpr int kNB = 8;               // reflectors per Householder panel
 constexpr int kRPT = 4;              // rows per thread in the panel kernels (1024 threads): k - j0 <= 4096
 constexpr int kSW = 8;               // columns per block in the blocked reflector application
@@ -419,46 +419,58 @@ constexpr int kJacobiMaxR = 1280;  // longest row the register-resident inner lo
 
 typedef float jf4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshGroup grp, int round, int nplayers, int b,
-                                                                  int sweep) {
+template <int B>  // rows per block (16 or 8); 2B rows are orthogonalised against each other
+__global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshGroup grp, int round, int nplayers, int sweep) {
+  constexpr int R2 = 2 * B;
   extern __shared__ __align__(16) float jsm[];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
   if (sweep > 0 && t.sweep_flag[sweep - 1] == 0) return;  // converged
-  const int nblocks = (r + b - 1) / b;
+  const int nblocks = (r + B - 1) / B;
   const int s = blockIdx.x;
   int bi, bj;
   if (s == 0) { bi = nplayers - 1; bj = round; }
   else { bi = (round + s) % (nplayers - 1); bj = (round - s + (nplayers - 1)) % (nplayers - 1); }
   if (bi > bj) { const int x = bi; bi = bj; bj = x; }
   if (bi >= nblocks) return;                // both absent
-  const int rows2 = 2 * b;
   const int rp = (r + 3) & ~3;               // LDS row pitch: rows padded with zeros to a multiple of 4
-  float* X = jsm;                            // [2b][rp]
-  float* RotT = jsm + (size_t)rows2 * rp;    // [2b][2b], RotT[j][i] = Rot[i][j]
+  const int nv = rp >> 2;                    // float4 per row
+  float* X = jsm;                            // [2B][rp]
+  float* RotT = jsm + (size_t)R2 * rp;       // [2B][2B], RotT[j][i] = Rot[i][j]
   __shared__ int rotated;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  auto grow = [&](int ls) { return ls < b ? bi * b + ls : bj * b + (ls - b); };  // local row -> row of Bw
-  auto present = [&](int ls) { return (ls < b || bj < nblocks) && grow(ls) < r; };
+  // local row ls -> row of Bw, or -1 when the row does not exist (ragged last block, bye block)
+  auto grow = [&](int ls) {
+    const int g = ls < B ? bi * B + ls : bj * B + (ls - B);
+    return ((ls < B || bj < nblocks) && g < r) ? g : -1;
+  };
+  const bool vec_ok = (r & 3) == 0;          // global rows are 16-byte aligned
 
-  for (int e = tid; e < rows2 * rp; e += 1024) {
-    const int ls = e / rp, c = e - ls * rp;
-    X[e] = (c < r && present(ls)) ? t.Bw[(size_t)grow(ls) * r + c] : 0.f;
+  // each wave moves rows wave, wave + 16, ... with 16-byte accesses
+  for (int ls = wave; ls < R2; ls += 16) {
+    const int g = grow(ls);
+    jf4* dst = reinterpret_cast<jf4*>(X + (size_t)ls * rp);
+    if (g >= 0 && vec_ok) {
+      const jf4* src = reinterpret_cast<const jf4*>(t.Bw + (size_t)g * r);
+      for (int e = lane; e < nv; e += 64) dst[e] = src[e];
+    } else {
+      for (int e = lane; e < rp; e += 64) X[(size_t)ls * rp + e] = (g >= 0 && e < r) ? t.Bw[(size_t)g * r + e] : 0.f;
+    }
   }
-  for (int e = tid; e < rows2 * rows2; e += 1024) RotT[e] = (e / rows2 == e % rows2) ? 1.f : 0.f;
+  for (int e = tid; e < R2 * R2; e += 1024) RotT[e] = ((e / R2) == (e % R2)) ? 1.f : 0.f;
   if (tid == 0) rotated = 0;
   __syncthreads();
 
   constexpr int NV = kJacobiMaxR / 256;      // float4 per lane per row, upper bound
-  const int nv = rp / 4;                     // float4 per row
+  const bool row_ok = wave < B;
   for (int isw = 0; isw < kInnerSweeps; ++isw)
-    for (int ir = 0; ir < rows2 - 1; ++ir) {
-      if (wave < b) {
+    for (int ir = 0; ir < R2 - 1; ++ir) {
+      if (row_ok) {
         int p, q;
-        if (wave == 0) { p = rows2 - 1; q = ir; }
-        else { p = (ir + wave) % (rows2 - 1); q = (ir - wave + (rows2 - 1)) % (rows2 - 1); }
+        if (wave == 0) { p = R2 - 1; q = ir; }
+        else { p = (ir + wave) % (R2 - 1); q = (ir + (R2 - 1) - wave) % (R2 - 1); }
         if (p > q) { const int x = p; p = q; q = x; }
-        if (present(p) && present(q)) {          // wave-uniform
+        if (grow(p) >= 0 && grow(q) >= 0) {          // wave-uniform
           jf4* xp = reinterpret_cast<jf4*>(X + (size_t)p * rp);
           jf4* xq = reinterpret_cast<jf4*>(X + (size_t)q * rp);
           jf4 u[NV], v[NV];
@@ -466,14 +478,13 @@ __global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshG
 #pragma unroll
           for (int i = 0; i < NV; ++i) {
             const int e = lane + 64 * i;
-            if (e < nv) {
-              u[i] = xp[e]; v[i] = xq[e];
+            if (e < nv) { u[i] = xp[e]; v[i] = xq[e]; }
+            else { u[i] = jf4{0.f, 0.f, 0.f, 0.f}; v[i] = u[i]; }
 #pragma unroll
-              for (int k = 0; k < 4; ++k) { a += u[i][k] * u[i][k]; bb += v[i][k] * v[i][k]; c += u[i][k] * v[i][k]; }
-            }
+            for (int k = 0; k < 4; ++k) { a += u[i][k] * u[i][k]; bb += v[i][k] * v[i][k]; c += u[i][k] * v[i][k]; }
           }
           a = wave_sum(a); bb = wave_sum(bb); c = wave_sum(c);
-          if (a != 0.f && bb != 0.f && fabsf(c) > kJacobiTol * sqrtf(a) * sqrtf(bb)) {
+          if (a != 0.f && bb != 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb) {
             const float zeta = (bb - a) / (2.f * c);
             const float tt = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
             const float cs = 1.f / sqrtf(1.f + tt * tt);
@@ -486,10 +497,10 @@ __global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshG
                 xq[e] = sn * u[i] + cs * v[i];
               }
             }
-            if (lane < rows2) {  // rows p, q of Rot = columns p, q of RotT
-              const float uu = RotT[lane * rows2 + p], vv = RotT[lane * rows2 + q];
-              RotT[lane * rows2 + p] = cs * uu - sn * vv;
-              RotT[lane * rows2 + q] = sn * uu + cs * vv;
+            if (lane < R2) {  // rows p, q of Rot = columns p, q of RotT
+              const float uu = RotT[lane * R2 + p], vv = RotT[lane * R2 + q];
+              RotT[lane * R2 + p] = cs * uu - sn * vv;
+              RotT[lane * R2 + q] = sn * uu + cs * vv;
             }
             if (lane == 0) rotated = 1;
           }
@@ -500,31 +511,40 @@ __global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshG
 
   if (rotated == 0) return;  // nothing changed: leave Bw, Jt and the sweep flag alone (uniform)
   if (tid == 0) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
-  for (int e = tid; e < rows2 * rp; e += 1024) {
-    const int ls = e / rp, c = e - ls * rp;
-    if (c < r && present(ls)) t.Bw[(size_t)grow(ls) * r + c] = X[e];
+  for (int ls = wave; ls < R2; ls += 16) {
+    const int g = grow(ls);
+    if (g < 0) continue;
+    const jf4* src = reinterpret_cast<const jf4*>(X + (size_t)ls * rp);
+    if (vec_ok) {
+      jf4* dst = reinterpret_cast<jf4*>(t.Bw + (size_t)g * r);
+      for (int e = lane; e < nv; e += 64) dst[e] = src[e];
+    } else {
+      for (int e = lane; e < r; e += 64) t.Bw[(size_t)g * r + e] = X[(size_t)ls * rp + e];
+    }
   }
   // Jt rows <- Rot * Jt rows, one column per thread; RotT[j][:] is read as broadcast float4
+  int gr[R2];
+#pragma unroll
+  for (int j = 0; j < R2; ++j) gr[j] = grow(j);
   for (int c = tid; c < r; c += 1024) {
-    float acc[32];
+    float acc[R2];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
-    for (int j = 0; j < rows2; ++j) {
-      if (!present(j)) continue;
-      const float x = t.Jt[(size_t)grow(j) * r + c];
-      const jf4* rt = reinterpret_cast<const jf4*>(RotT + j * rows2);
+    for (int i = 0; i < R2; ++i) acc[i] = 0.f;
+#pragma unroll 4
+    for (int j = 0; j < R2; ++j) {
+      if (gr[j] < 0) continue;
+      const float x = t.Jt[(size_t)gr[j] * r + c];
+      const jf4* rt = reinterpret_cast<const jf4*>(RotT + j * R2);
 #pragma unroll
-      for (int i4 = 0; i4 < 8; ++i4) {
-        if (4 * i4 < rows2) {
-          const jf4 w = rt[i4];
+      for (int i4 = 0; i4 < R2 / 4; ++i4) {
+        const jf4 w = rt[i4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) acc[4 * i4 + k] += w[k] * x;
-        }
+        for (int k = 0; k < 4; ++k) acc[4 * i4 + k] += w[k] * x;
       }
     }
 #pragma unroll
-    for (int i = 0; i < 32; ++i)
-      if (i < rows2 && present(i)) t.Jt[(size_t)grow(i) * r + c] = acc[i];
+    for (int i = 0; i < R2; ++i)
+      if (gr[i] >= 0) t.Jt[(size_t)gr[i] * r + c] = acc[i];
   }
 }
 
@@ -745,7 +765,9 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     const size_t smem = (size_t)2 * jb * ((r + 3) & ~3) * 4 + (size_t)4 * jb * jb * 4;
     static bool attr_set = false;
     if (!attr_set) {
-      GALORE_RETURN_IF(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_round_kernel),
+      GALORE_RETURN_IF(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_round_kernel<16>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+      GALORE_RETURN_IF(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_round_kernel<8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
       attr_set = true;
     }
@@ -753,8 +775,10 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     const int players = (nblocks % 2 == 0) ? nblocks : nblocks + 1;   // >= 2
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
-        hipLaunchKernelGGL(jacobi_block_round_kernel, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players,
-                           jb, sweep);
+        if (jb == 16)
+          hipLaunchKernelGGL(jacobi_block_round_kernel<16>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
+        else
+          hipLaunchKernelGGL(jacobi_block_round_kernel<8>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
   } else if (r > 1) {  // rows too long for LDS: one launch per round of row pairs
     const int players = (r % 2 == 0) ? r : r + 1;
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
