@@ -5,38 +5,16 @@
 #include "gemm_mfma.hpp"
 #include "gemm_mfma_dl.hpp"
 
-// Build-time choice of the large-tile configuration (tuning knob; 0 disables the kernel).
-#ifndef GALORE_DL_VARIANT
-#define GALORE_DL_VARIANT 2
-#endif
-
 namespace galore {
 
 using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
-// Measured on the 7B shapes (projection / back-projection TFLOP/s of a single 4096x11008 tensor):
-//   1: 256x256x64, 4 waves (128x128 each)  746 / 650     2: 256x256x64, 8 waves (128x64 each)  876 / 894
-//   3: 256x128x32, 4 waves, 3 stages       828 / 699     4: 128x128x64, 4 waves                878 / 711
-#if GALORE_DL_VARIANT == 1
-using CfgDl = DlCfg<256, 256, 64, 2, 2, 2>;
-#elif GALORE_DL_VARIANT == 2
-using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;
-#elif GALORE_DL_VARIANT == 3
-using CfgDl = DlCfg<256, 128, 32, 2, 2, 3>;
-#elif GALORE_DL_VARIANT == 4
-using CfgDl = DlCfg<128, 128, 64, 2, 2, 2>;
-#elif GALORE_DL_VARIANT == 5
-using CfgDl = DlCfg<256, 128, 64, 2, 2, 3>;
-#elif GALORE_DL_VARIANT == 6
-using CfgDl = DlCfg<256, 128, 64, 4, 2, 3>;
-#elif GALORE_DL_VARIANT == 7
-using CfgDl = DlCfg<128, 256, 64, 2, 4, 3>;
-#elif GALORE_DL_VARIANT == 8
-using CfgDl = DlCfg<128, 256, 64, 1, 4, 3>;
-#endif
+// Large tile of the direct-to-LDS kernel.  Measured alternatives on the 7B shapes were slower:
+// 4 waves of 128x128 (one wave per SIMD cannot overlap its LDS reads with MFMAs), 256x128 and
+// 128x128 tiles (more LDS and L2 traffic per flop).
+using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;  // 8 waves of 128 x 64, two 64 KB stages
 
 template <class T, bool AK, bool BKC, Epilogue EPI>
 inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
-#if GALORE_DL_VARIANT > 0
   if constexpr (std::is_same<T, __bf16>::value) {
     if (group_fits_dl(g, AK, BKC, EPI, CfgDl::BK)) {
       plan_tiles<CfgDl>(g);
@@ -44,7 +22,6 @@ inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
       return launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(g, stream);
     }
   }
-#endif
   plan_tiles<CfgDefault>(g);
   if (g.total_tiles == 0) return hipSuccess;
   if (group_is_aligned<T>(g, AK, BKC))

@@ -105,178 +105,271 @@ template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
   }
 };
 
+// One tile of the launch, as seen by the workgroup that computes it (all wave-uniform).
+struct DlTile {
+  int pi;      // problem index
+  int m0, n0;  // first row / column
+  int tm, tn;
+  int round;   // which pass of the persistent grid produced it
+};
+
+// Persistent kernel: the grid has at most one workgroup per CU and workgroup b walks the tiles
+// of its XCD's share with stride G/8.  The K steps of consecutive tiles form ONE stream through
+// the two-stage LDS ring: the first K step of the next tile is requested while the last K step of
+// the current tile is multiplied, so its latency (and the whole epilogue) hides behind MFMAs and
+// stores, and no workgroup launch sits between two tiles.  The epilogue parks 8-row strips of the
+// accumulators in a wave-private LDS area OUTSIDE the ring, so it never waits for the ring.
 template <bool AK, bool BKC, Epilogue EPI, class Cfg>
 __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, S = Cfg::STAGES;
-  constexpr int TM = Cfg::TM, TN = Cfg::TN;
+  constexpr int TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
   using AOp = DlOperand<AK, BM, BK, NW>;
   using BOp = DlOperand<BKC, BN, BK, NW>;
   constexpr int STAGE_BYTES = AOp::TILE_BYTES + BOp::TILE_BYTES;
-  constexpr int LOADS = AOp::PER_WAVE + BOp::PER_WAVE;  // vector-memory ops per wave per tile
-  static_assert((S - 2) * LOADS <= 63, "too many loads in flight for the wait counter");
+  constexpr int RING_BYTES = S * STAGE_BYTES;
+  static_assert(S == 2, "the cross-tile stream is written for a two-stage ring");
+  static_assert(WN == 64 || WN == 128, "the strip epilogue covers 8 rows with one or two passes of the wave");
+  constexpr int PITCH = WN + 8;           // floats; 4 PITCH = 32 (mod 64) spreads the two half-waves over the banks
+  constexpr int STRIP_FLOATS = 8 * PITCH;
+  constexpr int LPR = WN / 8;             // lanes per strip row (8 columns each)
+  constexpr int RPP = 64 / LPR;           // rows per pass
+  constexpr int PASSES = 8 / RPP;
 
   extern __shared__ __align__(1024) unsigned char smem_dl[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave % Cfg::WGM) * Cfg::WM;
   const int wn0 = (wave / Cfg::WGM) * Cfg::WN;
 
-  const int bid = xcd_contiguous_block_id(blockIdx.x, gridDim.x);
-  int pi = 0;
-  for (int i = 1; i < grp.count; ++i)
-    if (bid >= grp.p[i].tile_begin) pi = i;
-  const GemmProblem& pr = grp.p[pi];
-  int tm, tn;
-  tile_coords(bid - pr.tile_begin, pr.tiles_m, pr.tiles_n, tm, tn);
-  if (EPI == Epilogue::StoreSymF32 && tm > tn) return;
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int M = pr.M, N = pr.N;
-  const __bf16* __restrict__ A = static_cast<const __bf16*>(pr.A);
-  const __bf16* __restrict__ B = static_cast<const __bf16*>(pr.B);
-  const int KT = pr.K / BK;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  AOp opa;
-  BOp opb;
-  opa.plan(pr.lda, m0, M, wave, lane);
-  opb.plan(pr.ldb, n0, N, wave, lane);
-  const size_t a_step = AK ? (size_t)BK * 2 : (size_t)BK * pr.lda * 2;  // bytes per K step
-  const size_t b_step = BKC ? (size_t)BK * 2 : (size_t)BK * pr.ldb * 2;
-  const unsigned lds0 = (unsigned)(uintptr_t)smem_dl;
-  auto issue_tile = [&](int kt) {
-    const unsigned st = lds0 + (kt % S) * STAGE_BYTES;
-    opa.issue(reinterpret_cast<const unsigned char*>(A) + kt * a_step, st, wave);
-    opb.issue(reinterpret_cast<const unsigned char*>(B) + kt * b_step, st + AOp::TILE_BYTES, wave);
+  // Workgroups are dealt to the XCDs round-robin (blockIdx % 8).  XCD x owns one contiguous eighth
+  // of the launch's tile ids and its G/8 workgroups walk it side by side, so the tiles an XCD works
+  // on at a time are consecutive (see tile_coords) and every XCD has the same amount of work.
+  const int per_xcd = gridDim.x >> 3;
+  const int xcd = blockIdx.x & 7, q_in_xcd = blockIdx.x >> 3;
+  const int share = grp.total_tiles >> 3, extra = grp.total_tiles & 7;
+  const int first_id = xcd * share + (xcd < extra ? xcd : extra);
+  const int n_ids = share + (xcd < extra ? 1 : 0);
+  auto locate = [&](int round, DlTile& t) -> bool {
+    for (;; ++round) {
+      const int idx = round * per_xcd + q_in_xcd;
+      if (idx >= n_ids) return false;
+      const int id = first_id + idx;
+      int pi = 0;
+      for (int i = 1; i < grp.count; ++i)
+        if (id >= grp.p[i].tile_begin) pi = i;
+      int tm, tn;
+      tile_coords(id - grp.p[pi].tile_begin, grp.p[pi].tiles_m, grp.p[pi].tiles_n, tm, tn);
+      if (EPI == Epilogue::StoreSymF32 && tm > tn) continue;  // the mirror tile writes this one
+      t.pi = pi; t.m0 = tm * BM; t.n0 = tn * BN; t.tm = tm; t.tn = tn; t.round = round;
+      return true;
+    }
   };
 
-  // Epilogue geometry (see below): after a trip through LDS each lane owns 8 consecutive
-  // columns of row (32 i + ps RPP + rr) of its wave's tile.
-  constexpr int WN = Cfg::WN;
-  constexpr int PITCH = WN + 8;
-  constexpr int LPR = WN / 8;        // lanes per row
-  constexpr int RPP = 64 / LPR;      // rows per pass
-  constexpr int PASSES = 32 / RPP;
-  const int ldc = pr.ldc;
+  DlTile cur;
+  if (!locate(0, cur)) return;
+
+  // load side: plan and source of the tile whose K steps are being requested
+  AOp opa;
+  BOp opb;
+  const unsigned char* a_src = nullptr;
+  const unsigned char* b_src = nullptr;
+  size_t a_step = 0, b_step = 0;  // bytes per K step
+  auto bind = [&](const DlTile& t) {
+    const GemmProblem& p = grp.p[t.pi];
+    opa.plan(p.lda, t.m0, p.M, wave, lane);
+    opb.plan(p.ldb, t.n0, p.N, wave, lane);
+    a_src = static_cast<const unsigned char*>(p.A);
+    b_src = static_cast<const unsigned char*>(p.B);
+    a_step = AK ? (size_t)BK * 2 : (size_t)BK * p.lda * 2;
+    b_step = BKC ? (size_t)BK * 2 : (size_t)BK * p.ldb * 2;
+  };
+  const unsigned lds0 = (unsigned)(uintptr_t)smem_dl;
+  auto issue_step = [&](int kt, int stage) {
+    const unsigned st = lds0 + stage * STAGE_BYTES;
+    opa.issue(a_src + kt * a_step, st, wave);
+    opb.issue(b_src + kt * b_step, st + AOp::TILE_BYTES, wave);
+  };
+
+  // epilogue geometry: a strip is 8 rows x WN columns of the wave's tile (accumulator registers
+  // 4q .. 4q+3 of every 32x32 block); after the trip through LDS each lane owns 8 consecutive
+  // columns of a row, i.e. 16-byte (bf16) or 32-byte (fp32) contiguous global accesses.
+  float* strip = reinterpret_cast<float*>(smem_dl + RING_BYTES) + wave * STRIP_FLOATS;
   const int rr = lane / LPR, cc = (lane % LPR) * 8;
-  const int col = n0 + wn0 + cc;
-  // The weight update reads W; those loads are issued during the last K step so their latency
-  // hides behind its MFMAs instead of sitting in front of the epilogue.
-  bf16x8 wpre[TM][PASSES];
-  bool wok[TM][PASSES];
 
-  // prologue: S - 1 tiles in flight (empty groups keep the wait counts uniform)
+  bind(cur);
+  issue_step(0, 0);
+  int g = 0;  // K steps consumed so far, over all tiles: step g lives in stage g & 1
+
+  for (;;) {
+    const GemmProblem& pr = grp.p[cur.pi];
+    const int M = pr.M, N = pr.N, ldc = pr.ldc;
+    const int KT = pr.K / BK;
+    const int row0 = cur.m0 + wm0 + rr;
+    const int col = cur.n0 + wn0 + cc;
+
+    f32x16 acc[TM][TN];
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s)
-    if (s < KT) issue_tile(s);
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  for (int kt = 0; kt < KT; ++kt) {
-    // tile kt has landed once at most the loads of the younger tiles are outstanding
-    if (kt + S - 2 < KT) wait_vmcnt<(S - 2) * LOADS>();
-    else wait_vmcnt<0>();
-    __syncthreads();  // everyone's pieces of tile kt are visible; everyone is done with tile kt - 1
-    if (kt + S - 1 < KT) issue_tile(kt + S - 1);  // refills the stage consumed at kt - 1
-    if (EPI == Epilogue::ApplyW && kt == KT - 1) {
+    auto multiply_step = [&](int stage) {
+      const unsigned char* as = smem_dl + stage * STAGE_BYTES;
+      const unsigned char* bs = as + AOp::TILE_BYTES;
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 16) {
+        bf16x8 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(as, wm0 + 32 * i, kk, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(bs, wn0 + 32 * j, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    };
+
+    // The weight update reads the W tile.  Its loads are issued in two halves during the last two
+    // K steps (block rows 0 .. TM/2-1 first: the epilogue needs them first), so that their
+    // latency hides behind MFMAs instead of sitting in front of the epilogue.  Every slice is
+    // exactly one load instruction (lanes outside the matrix read a clamped address): the wait
+    // of the last K step counts on that.
+    bf16x8 wpre[TM][4][PASSES];
+    constexpr int W_EARLY = (TM / 2) * 4 * PASSES;  // load instructions of the first half
+    auto fetch_w = [&](int i_begin, int i_end) {
       const __bf16* W = static_cast<const __bf16*>(pr.C);
+      const int colc = col < N ? col : 0;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
+        if (i >= i_begin && i < i_end) {
 #pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-          const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
-          wok[i][ps] = row < M && col < N;
-          if (wok[i][ps]) wpre[i][ps] = *reinterpret_cast<const bf16x8*>(W + (size_t)row * ldc + col);
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+              const int row = row0 + 32 * i + 8 * q + RPP * ps;
+              wpre[i][q][ps] = *reinterpret_cast<const bf16x8*>(W + (size_t)(row < M ? row : M - 1) * ldc + colc);
+            }
         }
+    };
+
+    // All K steps but the last two.  At the top of a step everything this wave requested has
+    // landed (vmcnt also covers the previous epilogue's stores); after the barrier every wave's
+    // pieces of step g are visible and every wave is done reading the other stage, which is refilled.
+    for (int kt = 0; kt + 2 < KT; ++kt) {
+      wait_vmcnt<0>();
+      __syncthreads();
+      issue_step(kt + 1, (g + 1) & 1);
+      multiply_step(g & 1);
+      ++g;
+    }
+    bool w_early = false;
+    if (KT >= 2) {  // step KT - 2
+      wait_vmcnt<0>();
+      __syncthreads();
+      issue_step(KT - 1, (g + 1) & 1);
+      if (EPI == Epilogue::ApplyW) {
+        fetch_w(0, TM / 2);
+        w_early = true;
+      }
+      multiply_step(g & 1);
+      ++g;
     }
 
-    const unsigned char* as = smem_dl + (kt % S) * STAGE_BYTES;
-    const unsigned char* bs = as + AOp::TILE_BYTES;
+    // Last K step: the tile loads are older than the early W loads and vmcnt retires in issue
+    // order, so they have landed once at most W_EARLY operations are outstanding.  The first K
+    // step of the next tile is requested here, so the epilogue and the tile switch hide behind it.
+    if (w_early) wait_vmcnt<W_EARLY>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    DlTile nxt;
+    const bool have_next = locate(cur.round + 1, nxt);
+    if (have_next) {
+      bind(nxt);
+      issue_step(0, (g + 1) & 1);
+    }
+    if (EPI == Epilogue::ApplyW) fetch_w(w_early ? TM / 2 : 0, TM);
+    multiply_step(g & 1);
+    ++g;
+
+    // ---- epilogue: accumulators -> wave-private LDS strip -> row-contiguous global accesses ----
+    // An MFMA accumulator holds one column and 16 scattered rows per lane, which would make every
+    // global access 2 or 4 bytes wide.  LDS operations of one wave execute in order, so the strip
+    // can be rewritten right after it was read without a wait.
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fa[TM], fb[TN];
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(as, wm0 + 32 * i, kk, lane);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(bs, wn0 + 32 * j, kk, lane);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int q = 0; q < 4; ++q) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-  }
-
-  // ---- epilogue: accumulators -> wave-private LDS strip -> row-contiguous 16/32-byte accesses ----
-  // An MFMA accumulator holds one column and 16 scattered rows per lane, which would make every
-  // global access 2 or 4 bytes wide.  Each wave therefore parks a 32-row strip of its tile in LDS
-  // (fp32, row pitch WN + 8 so both the column-wise writes and the row-wise reads spread over
-  // the banks) and re-reads it with 8 consecutive columns per lane.
-  static_assert(NW * 32 * PITCH * 4 <= S * STAGE_BYTES, "epilogue strips must fit the tile ring");
-  __syncthreads();  // every wave has finished reading the last tile
-  float* strip = reinterpret_cast<float*>(smem_dl) + wave * (32 * PITCH);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+          for (int c = 0; c < 4; ++c)
+            strip[(4 * (lane >> 5) + c) * PITCH + 32 * j + (lane & 31)] = acc[i][j][4 * q + c];
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        strip[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PITCH + 32 * j + (lane & 31)] = acc[i][j][v];
-    f32x4 lo[PASSES], hi[PASSES];
-#pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) {
-      const float* src = strip + (ps * RPP + rr) * PITCH + cc;
-      lo[ps] = *reinterpret_cast<const f32x4*>(src);
-      hi[ps] = *reinterpret_cast<const f32x4*>(src + 4);
-    }
-    if (EPI == Epilogue::ApplyW) {
-      __bf16* W = static_cast<__bf16*>(pr.C);
-#pragma unroll
-      for (int ps = 0; ps < PASSES; ++ps) {
-        if (!wok[i][ps]) continue;
-        const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = (__bf16)(pr.s0 * (float)wpre[i][ps][e] - pr.s1 * lo[ps][e]);
-          o[e + 4] = (__bf16)(pr.s0 * (float)wpre[i][ps][e + 4] - pr.s1 * hi[ps][e]);
-        }
-        *reinterpret_cast<bf16x8*>(W + (size_t)row * ldc + col) = o;
-      }
-    } else {
-      float* C = static_cast<float*>(pr.C);
-#pragma unroll
-      for (int ps = 0; ps < PASSES; ++ps) {
-        const int row = m0 + wm0 + 32 * i + ps * RPP + rr;
-        if (row < M && col < N) {
-          float* dst = C + (size_t)row * ldc + col;
-          *reinterpret_cast<f32x4*>(dst) = lo[ps];
-          *reinterpret_cast<f32x4*>(dst + 4) = hi[ps];
-          if (EPI == Epilogue::StoreSymF32 && tm != tn) {
+        for (int ps = 0; ps < PASSES; ++ps) {
+          const float* src = strip + (rr + RPP * ps) * PITCH + cc;
+          const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
+          const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
+          const int row = row0 + 32 * i + 8 * q + RPP * ps;
+          if (row >= M || col >= N) continue;
+          if (EPI == Epilogue::ApplyW) {
+            __bf16* W = static_cast<__bf16*>(pr.C);
+            bf16x8 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              C[(size_t)(col + e) * ldc + row] = lo[ps][e];
-              C[(size_t)(col + e + 4) * ldc + row] = hi[ps][e];
+              o[e] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e] - pr.s1 * lo[e]);
+              o[e + 4] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e + 4] - pr.s1 * hi[e]);
+            }
+            *reinterpret_cast<bf16x8*>(W + (size_t)row * ldc + col) = o;
+          } else {
+            float* C = static_cast<float*>(pr.C);
+            float* dst = C + (size_t)row * ldc + col;
+            *reinterpret_cast<f32x4*>(dst) = lo;
+            *reinterpret_cast<f32x4*>(dst + 4) = hi;
+            if (EPI == Epilogue::StoreSymF32 && cur.tm != cur.tn) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                C[(size_t)(col + e) * ldc + row] = lo[e];
+                C[(size_t)(col + e + 4) * ldc + row] = hi[e];
+              }
             }
           }
         }
       }
     }
+
+    if (!have_next) break;
+    cur = nxt;
   }
+}
+
+// Number of workgroups of the persistent grid: one per CU, a multiple of 8 (one share per XCD).
+inline int dl_grid_size(int total_tiles) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount >= 8)
+      cus = prop.multiProcessorCount & ~7;
+    else
+      cus = 256;
+  }
+  const int want = (total_tiles + 7) & ~7;
+  return want < cus ? want : cus;
 }
 
 template <bool AK, bool BKC, Epilogue EPI, class Cfg>
 inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream) {
   using AOp = DlOperand<AK, Cfg::BM, Cfg::BK, Cfg::NW>;
   using BOp = DlOperand<BKC, Cfg::BN, Cfg::BK, Cfg::NW>;
-  constexpr size_t smem = (size_t)Cfg::STAGES * (AOp::TILE_BYTES + BOp::TILE_BYTES);
-  static_assert(smem <= 160 * 1024, "tile ring does not fit the 160 KB LDS");
+  constexpr size_t smem = (size_t)Cfg::STAGES * (AOp::TILE_BYTES + BOp::TILE_BYTES) +
+                          (size_t)Cfg::NW * 8 * (Cfg::WN + 8) * sizeof(float);  // tile ring + epilogue strips
+  static_assert(smem <= 160 * 1024, "tile ring and strips do not fit the 160 KB LDS");
   auto kern = gemm_dl_kernel<AK, BKC, EPI, Cfg>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -285,7 +378,7 @@ inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(g.total_tiles), dim3(Cfg::NT), smem, stream, g);
+  hipLaunchKernelGGL(kern, dim3(dl_grid_size(g.total_tiles)), dim3(Cfg::NT), smem, stream, g);
   return hipGetLastError();
 }
 
