@@ -258,19 +258,67 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
         }
     };
 
-    // All K steps but the last two.  At the top of a step everything this wave requested has
-    // landed (vmcnt also covers the previous epilogue's stores); after the barrier every wave's
-    // pieces of step g are visible and every wave is done reading the other stage, which is refilled.
-    for (int kt = 0; kt + 2 < KT; ++kt) {
+    // All K steps but the last two run software-pipelined: the fragments of the next 16 k are read
+    // from LDS while the MFMAs of the current 16 k execute, and the MFMAs of a step's last 16 k are
+    // deferred past the next step's barrier, so the matrix cores have work during the barrier, the
+    // load issue and the first LDS reads of every step.
+    // At the top of a step everything this wave requested has landed (vmcnt also covers the
+    // previous epilogue's stores) and its own LDS reads of the other stage have returned; after
+    // the barrier every wave's pieces of step g are visible and the other stage can be refilled.
+    const int n_main = KT - 2;
+    if (n_main > 0) {
+      bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+      auto read_frags = [&](int stage, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+        const unsigned char* as = smem_dl + stage * STAGE_BYTES;
+        const unsigned char* bs = as + AOp::TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = AOp::frag(as, wm0 + 32 * i, kk, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = BOp::frag(bs, wn0 + 32 * j, kk, lane);
+      };
+      auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      };
+      // scheduling hint: alternate one LDS read with one MFMA, then the remaining MFMAs
+      constexpr int NREADS = TM * (AK ? 1 : 2) + TN * (BKC ? 1 : 2);
+      constexpr int NPAIR = NREADS < TM * TN ? NREADS : TM * TN;
+      auto interleave = [&]() {
+#pragma unroll
+        for (int t = 0; t < NPAIR; ++t) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        if (NREADS > NPAIR) __builtin_amdgcn_sched_group_barrier(0x100, NREADS - NPAIR, 0);
+        if (TM * TN > NPAIR) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NPAIR, 0);
+      };
+
       wait_vmcnt<0>();
       __syncthreads();
-      issue_step(kt + 1, (g + 1) & 1);
-      multiply_step(g & 1);
+      issue_step(1, (g + 1) & 1);
+      read_frags(g & 1, 0, fa0, fb0);
+      read_frags(g & 1, 16, fa1, fb1); mma(fa0, fb0); interleave();
+      read_frags(g & 1, 32, fa0, fb0); mma(fa1, fb1); interleave();
+      read_frags(g & 1, 48, fa1, fb1); mma(fa0, fb0); interleave();
       ++g;
+      for (int kt = 1; kt < n_main; ++kt) {
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) and lgkmcnt(0)
+        __syncthreads();
+        issue_step(kt + 1, (g + 1) & 1);
+        read_frags(g & 1, 0, fa0, fb0); mma(fa1, fb1); interleave();
+        read_frags(g & 1, 16, fa1, fb1); mma(fa0, fb0); interleave();
+        read_frags(g & 1, 32, fa0, fb0); mma(fa1, fb1); interleave();
+        read_frags(g & 1, 48, fa1, fb1); mma(fa0, fb0); interleave();
+        ++g;
+      }
+      mma(fa1, fb1);
     }
     bool w_early = false;
     if (KT >= 2) {  // step KT - 2
-      wait_vmcnt<0>();
+      __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) and lgkmcnt(0)
       __syncthreads();
       issue_step(KT - 1, (g + 1) & 1);
       if (EPI == Epilogue::ApplyW) {
