@@ -172,3 +172,35 @@ def test_round_trip_identity_full_rank():
     gb.galore_project_back(P.cuda(), R.t().contiguous(), W, -1.0, 1.0, 0.0)
     torch.cuda.synchronize()
     assert relF(to64(W), to64(G)) <= 1e-5
+
+
+@pytest.mark.parametrize("r", [64, 192, 320])
+@pytest.mark.parametrize("shape", [(4160, 4360), (4360, 4160)])
+def test_more_tiles_than_compute_units_ragged_bf16(shape, r):
+    # 17 x 18 = 306 tiles of 256 x 256 with partial tiles on both edges: every workgroup of the
+    # persistent large-tile kernel walks more than one tile; r = 64 / 192 / 320 gives 1 / 3 / 5
+    # K steps in the back-projection, i.e. its peeled last steps with and without the pipelined loop.
+    m, n = shape
+    W, G, P = _inputs(m, n, r, "bf16", 21)
+    R_ref = orc.project(to64(P), to64(G))
+    R = torch.full(R_ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    gb.galore_project(_transposed(P.cuda()), G.cuda(), R)
+    torch.cuda.synchronize()
+    assert relF(to64(R), R_ref) <= 1e-5
+    rng = np.random.default_rng(22)
+    nshape = (r, n) if m <= n else (m, r)
+    N = torch.from_numpy(rng.uniform(-1, 1, nshape)).to(torch.bfloat16)
+    lr, alpha, wd = f32(1e-2), 0.25, f32(0.1)
+    W_ref = to64(W).copy()
+    orc.apply_update(W_ref, to64(P), to64(N), lr, alpha, wd)
+    Wd = W.cuda().clone()
+    gb.galore_project_back(P.cuda(), _long_by_r(N, m, n), Wd, lr, alpha, wd)
+    torch.cuda.synchronize()
+    W_r = orc.round_storage(W_ref, "bf16")
+    ulp = np.maximum(np.abs(W_r), 2.0 ** -126) * 2.0 ** -7
+    # among 18 M entries a few updates cancel the weight almost exactly; there the fp32 rounding of
+    # the r-term accumulation (worst case r 2^-24 of the terms' size), not the bf16 ulp of the tiny
+    # result, bounds the difference
+    cancel = r * 2.0 ** -24 * (np.abs(to64(W)) + np.abs(W_ref - to64(W)))
+    assert np.all(np.abs(to64(Wd) - W_r) <= ulp + cancel)
+    assert np.mean(to64(Wd) == W_r) >= 0.98
