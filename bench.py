@@ -24,9 +24,9 @@ PEAK_HBM_GBS = 8000.0
 # runs of paper_2403_03507_amd/traffic_probe.py, calibrated with a 1 GiB copy (see
 # profiles/step_llama7b_hbm_traffic.md).  Reported as roofline.traffic; null for other shapes.
 MEASURED_TRAFFIC_BYTES_7B = {
-    "project_left": 581.1e6 + 158.7e6,
-    "project_right": 205.6e6 + 45.2e6,
-    "back": 1093.8e6 + 404.8e6,
+    "project_left": 581.3e6 + 157.6e6,
+    "project_right": 205.7e6 + 45.1e6,
+    "back": 1131.5e6 + 404.8e6,
     "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
 }
 
@@ -141,7 +141,7 @@ def main():
     else:
         peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
         achieved = flops[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
-        roofline = {"kernel": "gemm_group_kernel/" + dominant, "bound": "mfma", "achieved": achieved, "peak": peak,
+        roofline = {"kernel": "gemm_dl_kernel/" + dominant, "bound": "mfma", "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
