@@ -5,7 +5,9 @@ A "step" is one pass of the whole hot path (project, low-rank Adam, project back
 subspace refresh falls on step 0 and is timed apart) over every GaLore matrix of a synthetic
 LLaMA-7B-shaped stack (32 layers x {4x 4096x4096, 2x 4096x11008, 11008x4096}, bf16 W/G, fp32
 M/V, r = 1024), called one layer at a time in backward order, the way a per-layer weight update
-during back-propagation calls it.  Prints ONE JSON line.
+during back-propagation calls it; consecutive calls overlap on the library's two streams, which
+are joined into the caller's stream once per step (galore_join), when the next forward pass
+needs the weights.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -41,6 +43,9 @@ def main():
     ap.add_argument("--refresh-iters", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
+    ap.add_argument("--join-every-call", action="store_true",
+                    help="join the library streams at the end of every per-layer call (3 chains inside each call) "
+                         "instead of overlapping consecutive calls and joining once per step")
 
     args = ap.parse_args()
     if args.gpus != 1:
@@ -85,12 +90,15 @@ def main():
 
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
+    overlap = not args.join_every_call and args.lanes > 1
+    gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
 
     def one_step(step_index):
         for l in reversed(range(L)):  # backward order, one layer per call
             gb.galore_step(opt.ctx, w_descs[l], g_descs[(l + step_index) % POOL], n_per_layer * l, n_per_layer, lr)
+        gb.galore_join(opt.ctx)  # the next forward pass needs the weights: one join per step
 
     def timed(fn):
         torch.cuda.synchronize()
@@ -116,12 +124,14 @@ def main():
     # Same K steps again, serial (one chain) and with every kernel group bracketed by HIP events on
     # the library's stream: concurrent chains share the CUs, so per-kernel durations are only
     # meaningful without overlap.
+    gb.galore_set_call_overlap(opt.ctx, False)
     gb.galore_set_concurrency(opt.ctx, 1)
     serial_ms = timed(lambda: [one_step(base + K + i) for i in range(K)]) / K
     gb.galore_profile_start(opt.ctx)
     prof_total_ms = timed(lambda: [one_step(base + 2 * K + i) for i in range(K)])
     prof = gb.galore_profile_stop(opt.ctx)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
+    gb.galore_set_call_overlap(opt.ctx, overlap)
 
     # ---- roofline of the dominant kernel -----------------------------------------------------------
     left = [(m, n) for (m, n) in shapes if m <= n]
@@ -183,7 +193,8 @@ def main():
         "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, fp32 M/V, r=%d, per-layer calls in "
                                "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype, r, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
-                   "concurrent_chains": args.lanes},
+                   "schedule": "consecutive calls overlap on two library streams, one join per step" if overlap else
+                               "%d concurrent chains inside each call, joined every call" % args.lanes},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "stages": per_stage,

@@ -146,6 +146,25 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
  * context's stream.  Results do not depend on the setting. */
 galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
 
+/* Overlap of consecutive calls (off by default).  When on, every galore_step call runs as ONE
+ * chain (all its tensors grouped in each kernel launch) on one of two library-owned streams of
+ * default priority, alternating from call to call.  The stream waits for the context's stream at
+ * the start of the call (so gradients produced there are ready) but is NOT joined back into it at
+ * the end: the bandwidth-bound Adam pass and the GEMM tails of one call overlap with the GEMMs
+ * of the next one (per-layer calls of one optimizer step).  Call c uses half (c mod 2) of the
+ * workspace, so it runs this way only if its tensors fit half of it; otherwise, and whenever a
+ * tensor of the call is still in flight on the other stream or a subspace refresh is due, the
+ * library joins first and proceeds as without overlap.  The caller must call galore_join()
+ * before work on the context's stream (or the host) reads or writes W, M, V or the projectors of
+ * tensors passed since the last join, and must not overwrite their G buffers before it.
+ * galore_set_concurrency does not apply to overlapped calls.  Results do not depend on the
+ * setting.  Turning it off joins. */
+galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on);
+
+/* Make the context's stream wait for everything the library streams hold (no host wait).
+ * A no-op when nothing is pending. */
+galore_status galore_join(galore_ctx* ctx);
+
 /* Step counter t of one tensor (number of steps taken); set is for checkpoint resume. */
 galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t);
 galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t);

@@ -44,7 +44,8 @@ class GaloreError(RuntimeError):
 EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_project_back",
-           "galore_profile_start", "galore_profile_stop", "galore_set_concurrency"]
+           "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
+           "galore_set_call_overlap", "galore_join"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
 _lib = None
@@ -76,6 +77,8 @@ def lib():
         L.galore_adam.argtypes = [tp, tp, tp, tp, i32, f32, f32, f32, i64, vp]
         L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
         L.galore_set_concurrency.argtypes = [vp, i32]
+        L.galore_set_call_overlap.argtypes = [vp, i32]
+        L.galore_join.argtypes = [vp]
         L.galore_profile_start.argtypes = [vp]
         L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
@@ -175,6 +178,14 @@ def galore_set_concurrency(ctx, lanes):
     _check(lib().galore_set_concurrency(ctx, lanes), ctx)
 
 
+def galore_set_call_overlap(ctx, on):
+    _check(lib().galore_set_call_overlap(ctx, 1 if on else 0), ctx)
+
+
+def galore_join(ctx):
+    _check(lib().galore_join(ctx), ctx)
+
+
 def galore_profile_start(ctx):
     _check(lib().galore_profile_start(ctx), ctx)
 
@@ -214,6 +225,12 @@ class GaLore:
 
     def step(self, weights, grads, lr, first=0):
         galore_step(self.ctx, [desc(w) for w in weights], [desc(g) for g in grads], first, len(weights), lr)
+
+    def set_call_overlap(self, on):
+        galore_set_call_overlap(self.ctx, on)
+
+    def join(self):
+        galore_join(self.ctx)
 
     def refresh(self, grads, first=0):
         galore_refresh_subspace(self.ctx, [desc(g) for g in grads], first, len(grads))

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <new>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -55,6 +56,14 @@ struct galore_ctx {
   hipStream_t aux[2] = {nullptr, nullptr};
   hipEvent_t fork_ev = nullptr;
   hipEvent_t join_ev[2] = {nullptr, nullptr};
+  // Overlap of consecutive calls (galore_set_call_overlap): every call (chunk) runs as ONE chain on
+  // one of the two library streams, alternating, and the context's stream is not made to wait
+  // until galore_join.  The chunk on stream h uses half h of the workspace, so stream order
+  // alone protects the workspace.
+  bool overlap_calls = false;
+  bool unjoined = false;          // library streams hold work the context's stream has not waited for
+  int parity = 0;
+  std::vector<char> in_flight;    // per tensor: 0, or 1 + the library stream its last chain ran on
 };
 
 namespace {
@@ -250,17 +259,61 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
   return GALORE_OK;
 }
 
+// Make the context's stream wait for everything the library streams hold.
+galore_status join_all(galore_ctx* ctx) {
+  galore_status st = GALORE_OK;
+  for (int c = 0; c < 2; ++c) {
+    if (!ctx->aux[c] || !ctx->join_ev[c]) continue;
+    hipError_t e = hipEventRecord(ctx->join_ev[c], ctx->aux[c]);
+    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_ev[c], 0);
+    if (e != hipSuccess && st == GALORE_OK) st = hip_fail(ctx, e, "joining streams");
+  }
+  ctx->unjoined = false;
+  std::fill(ctx->in_flight.begin(), ctx->in_flight.end(), 0);
+  return st;
+}
+
+size_t workspace_half(const galore_ctx* ctx) { return (ctx->ws_bytes / 2) & ~(size_t)255; }
+
 // One chunk of the step: carve the workspace, split the tensors into chains of similar cost and
 // run the chains concurrently.  Chains touch disjoint tensors and disjoint workspace regions.
 galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, float lr) {
   const int r = ctx->hp.rank;
-  size_t off = 0;
+  size_t need = 0;
+  for (const StepItem& it : items) {
+    const TensorInfo& ti = ctx->tensors[it.tensor];
+    need += align_up((size_t)r * ti.ldim * 4) + align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+  }
+  const bool overlap = ctx->overlap_calls && ctx->aux[0] && ctx->aux[1] && ctx->fork_ev && need <= workspace_half(ctx);
+  if (ctx->unjoined) {
+    // Order everything first when this chunk cannot run on a library stream, or when one of its
+    // tensors is still in flight on the OTHER library stream.
+    bool clash = !overlap;
+    for (const StepItem& it : items) clash = clash || (ctx->in_flight[it.tensor] != 0 && ctx->in_flight[it.tensor] != 1 + ctx->parity);
+    if (clash) {
+      galore_status s = join_all(ctx);
+      if (s) return s;
+    }
+  }
+  size_t off = overlap ? (size_t)ctx->parity * workspace_half(ctx) : 0;
   for (StepItem& it : items) {
     const TensorInfo& ti = ctx->tensors[it.tensor];
     it.R = reinterpret_cast<float*>(ctx->ws + off);
     off += align_up((size_t)r * ti.ldim * 4);
     it.N = ctx->ws + off;
     off += align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+  }
+  if (overlap) {
+    const int h = ctx->parity;
+    hipError_t e = hipEventRecord(ctx->fork_ev, ctx->stream);  // inputs produced on the context's stream are ready
+    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux[h], ctx->fork_ev, 0);
+    if (e != hipSuccess) return hip_fail(ctx, e, "forking streams");
+    const galore_status st = run_chain(ctx, items, lr, ctx->aux[h]);
+    for (const StepItem& it : items) ctx->in_flight[it.tensor] = (char)(1 + h);
+    ctx->unjoined = true;
+    ctx->parity ^= 1;
+    if (st != GALORE_OK) (void)join_all(ctx);  // keep the context's stream ordered after a failed launch
+    return st;
   }
   int lanes = ctx->lanes;
   if (lanes > 1 && (!ctx->aux[0] || !ctx->aux[1] || !ctx->fork_ev)) lanes = 1;
@@ -443,6 +496,7 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
   ctx->ws = static_cast<unsigned char*>(workspace);
   ctx->ws_bytes = workspace_bytes;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->in_flight.assign(ctx->tensors.size(), 0);
   {
     hipError_t e = hipSuccess;
     for (int i = 0; i < 2 && e == hipSuccess; ++i) {
@@ -493,10 +547,16 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
     for (int i = 0; i < count; ++i)
       if (ctx->tensors[first + i].t % ctx->hp.update_gap == 0) due.push_back(i);
     if (!due.empty()) {
+      if (ctx->unjoined) {  // the refresh runs on the context's stream and uses the whole workspace
+        galore_status s = join_all(ctx);
+        if (s) return s;
+      }
       galore_status s = run_refresh(ctx, G, first, due);
       if (s) return s;
     }
   }
+  // with overlapping calls a chunk has to fit half of the workspace
+  const size_t limit = ctx->overlap_calls ? workspace_half(ctx) : ctx->ws_bytes;
   int pos = 0;
   while (pos < count) {
     std::vector<StepItem> items;
@@ -504,7 +564,7 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
     while (pos < count && (int)items.size() < kMaxGroup) {
       const TensorInfo& ti = ctx->tensors[first + pos];
       const size_t need = step_need(ti.ldim, ctx->hp.rank, ti.dt);
-      if (!items.empty() && used + need > ctx->ws_bytes) break;
+      if (!items.empty() && used + need > limit) break;
       items.push_back(StepItem{first + pos, &W[pos], &G[pos], nullptr, nullptr});
       used += need;
       ++pos;
@@ -528,6 +588,10 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
     galore_status s = check_step_tensor(ctx, ctx->tensors[first + i], G[i], "G", i);
     if (s) return s;
     all[i] = i;
+  }
+  if (ctx->unjoined) {
+    galore_status s = join_all(ctx);
+    if (s) return s;
   }
   return run_refresh(ctx, G, first, all);
 }
@@ -569,6 +633,19 @@ galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes) {
   if (lanes < 1 || lanes > 3) return fail(ctx, GALORE_ERR_INVALID_ARG, "lanes must be 1, 2 or 3");
   ctx->lanes = lanes;
   return GALORE_OK;
+}
+
+galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  ctx->overlap_calls = on != 0;
+  if (!ctx->overlap_calls && ctx->unjoined) return join_all(ctx);
+  return GALORE_OK;
+}
+
+galore_status galore_join(galore_ctx* ctx) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  if (!ctx->unjoined) return GALORE_OK;
+  return join_all(ctx);
 }
 
 galore_status galore_profile_start(galore_ctx* ctx) {

@@ -167,3 +167,52 @@ def test_checkpoint_resume_is_bit_identical():
     a, b = run(None), run(2)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+def _run_layers(overlap, update_gap, steps=4, workspace_factor=2, repeat_layer=False):
+    # three "layers" of mixed shapes and dtypes, one galore_step call per layer in backward order
+    layer = [((256, 688), "bf16"), ((688, 256), "bf16"), ((256, 256), "bf16"), ((320, 256), "f32")]
+    n_layers, nl = 3, 4
+    specs = layer * n_layers
+    W = [wl.make_weight(m, n, 700 + i, dt).cuda() for i, ((m, n), dt) in enumerate(specs)]
+    hp = gb.make_hparams(48, update_gap=update_gap, auto_refresh=True, refresh_iters=2)
+    descs = [gb.shape_desc(m, n, w.dtype) for ((m, n), _), w in zip(specs, W)]
+    need = gb.galore_workspace_bytes(hp, descs)
+    if workspace_factor == 0:  # just the largest single-tensor need: no call fits half of it
+        need = max(gb.galore_workspace_bytes(hp, [dsc]) for dsc in descs)
+        workspace_factor = 1
+    need = (need + 255) // 256 * 256
+    opt = gb.GaLore(W, 48, workspace_bytes=workspace_factor * need, update_gap=update_gap, auto_refresh=True, refresh_iters=2)
+    opt.set_call_overlap(overlap)
+    srcs = [wl.GradientSource(m, n, 800 + i, "gapped", dtype=dt, gap_rank=48) for i, ((m, n), dt) in enumerate(specs)]
+    for step in range(steps):
+        G = [s.grad(step).cuda() for s in srcs]
+        torch.cuda.synchronize()
+        for l in reversed(range(n_layers)):
+            opt.step(W[nl * l: nl * l + nl], G[nl * l: nl * l + nl], 1e-2, first=nl * l)
+            if repeat_layer and l == 1:  # the same tensors again with nothing joined in between
+                opt.step(W[nl * l: nl * l + nl], G[nl * l: nl * l + nl], 1e-2, first=nl * l)
+        opt.join()
+        torch.cuda.synchronize()
+    out = [w.clone() for w in W] + [x.clone() for x in opt.M + opt.V + opt.proj]
+    opt.close()
+    return out
+
+
+@pytest.mark.parametrize("update_gap", [1000, 2])
+def test_overlapped_calls_match_joined_calls_bitwise(update_gap):
+    # Overlapping consecutive calls only changes stream placement and which workspace half a call
+    # uses; a refresh falling due in the middle (update_gap = 2) forces a join inside the library.
+    a = _run_layers(False, update_gap)
+    b = _run_layers(True, update_gap)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_overlapped_calls_same_tensors_twice_and_small_workspace():
+    a = _run_layers(False, 1000, repeat_layer=True)
+    b = _run_layers(True, 1000, repeat_layer=True)
+    c = _run_layers(True, 1000, repeat_layer=True, workspace_factor=0)  # nothing fits half: joined path
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x, y)
+        assert torch.equal(x, z)
