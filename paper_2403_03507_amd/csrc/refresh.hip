@@ -415,6 +415,10 @@ __global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup gr
 // blocks), so a sweep over all pairs of rows costs (blocks - 1) launches that each read and write
 // Bw and Jt once, instead of (r - 1) launches.
 constexpr int kInnerSweeps = 1;
+#ifndef GALORE_GRAM_INNER
+#define GALORE_GRAM_INNER 1
+#endif
+constexpr int kGramInnerSweeps = GALORE_GRAM_INNER;  // inner sweeps of the Gram-maintained block round
 constexpr int kJacobiMaxR = 1280;  // longest row the register-resident inner loop is unrolled for (5 float4 per lane and row)
 
 typedef float jf4 __attribute__((ext_vector_type(4)));
@@ -545,6 +549,168 @@ __global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshG
 #pragma unroll
     for (int i = 0; i < R2; ++i)
       if (gr[i] >= 0) t.Jt[(size_t)gr[i] * r + c] = acc[i];
+  }
+}
+
+// Block round on the Gram matrix.  The 32 rows of a block pair are never staged in LDS:
+//   1. G = X X^T (32 x 32) is formed on the matrix cores (v_mfma_f32_16x16x4_f32) straight from
+//      global memory;
+//   2. one inner sweep (31 rounds of 16 disjoint row pairs) works on G alone: every rotation reads
+//      its three inner products from G, the 16 rotations of a round update it together as
+//      G <- J^T G J (one entry per thread) and are accumulated into the 32 x 32 product Rot;
+//   3. X <- Rot X and the matching rows of the eigenvector matrix Jt <- Rot Jt are two small
+//      matrix products on the matrix cores, 16 columns per wave at a time, in place.
+// Needs r % 4 == 0 (16-byte row segments); no limit on r.
+typedef float jf4m __attribute__((ext_vector_type(4)));
+constexpr int kGramB = 16, kGramR2 = 32;
+
+// Y (32 rows picked by rows[], length r) <- Rot Y, in place.  rot[h][s] = Rot[16 h + i][4 s + g]
+// for lane (i = lane % 16, g = lane / 16).  A wave owns whole columns, so it reads all 32 inputs
+// of a column before it writes any.
+__device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r, const int (&rows)[8], const int (&out_rows)[2][4],
+                                                    const float (&rot)[2][8], int wave, int lane) {
+  const int j = lane & 15;
+  for (int cb = wave; cb * 16 < r; cb += 16) {
+    const int col = cb * 16 + j;
+    float b[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) b[s] = (rows[s] >= 0 && col < r) ? Y[(size_t)rows[s] * r + col] : 0.f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      jf4m acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(rot[h][s], b[s], acc, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (out_rows[h][v] >= 0 && col < r) Y[(size_t)out_rows[h][v] * r + col] = acc[v];
+    }
+  }
+}
+
+__global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGroup grp, int round, int nplayers, int sweep) {
+  constexpr int B = kGramB, R2 = kGramR2, GP = R2 + 1;
+  __shared__ float Gm[2][R2 * GP];
+  __shared__ float Rot[R2 * GP];             // Rot[i][k]: new row i = sum_k Rot[i][k] old row k
+  __shared__ float stage[16 * 256];          // per wave: a 16 x 16 partial Gram block
+  __shared__ float alpha[R2], beta[R2];      // per row: new_row = alpha * row + beta * partner row
+  __shared__ int partner[R2];
+  __shared__ int rotated;
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int r = grp.r;
+  if (sweep > 0 && t.sweep_flag[sweep - 1] == 0) return;  // converged
+  const int nblocks = (r + B - 1) / B;
+  const int s = blockIdx.x;
+  int bi, bj;
+  if (s == 0) { bi = nplayers - 1; bj = round; }
+  else { bi = (round + s) % (nplayers - 1); bj = (round - s + (nplayers - 1)) % (nplayers - 1); }
+  if (bi > bj) { const int x = bi; bi = bj; bj = x; }
+  if (bi >= nblocks) return;                // both absent
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // local row ls -> row of Bw, or -1 when the row does not exist (ragged last block, bye block)
+  auto grow = [&](int ls) {
+    const int g = ls < B ? bi * B + ls : bj * B + (ls - B);
+    return ((ls < B || bj < nblocks) && g < r) ? g : -1;
+  };
+
+  // 1. Gram matrix: wave w computes the 16 x 16 block (I0, J0) over a quarter of the columns.  MFMA
+  // operand lane (i = lane % 16, g = lane / 16) supplies k = 4 g + (0..3) of every 16 columns, the
+  // same for A and B, so one 16-byte load feeds four MFMAs.
+  {
+    const int I0 = (wave & 1) * 16, J0 = ((wave >> 1) & 1) * 16, kq = wave >> 2;
+    const int i = lane & 15, g = lane >> 4;
+    const int ga = grow(I0 + i), gb = grow(J0 + i);
+    const float* arow = t.Bw + (size_t)(ga >= 0 ? ga : 0) * r;
+    const float* brow = t.Bw + (size_t)(gb >= 0 ? gb : 0) * r;
+    jf4m acc = {0.f, 0.f, 0.f, 0.f};
+    const int ngroups = (r + 15) >> 4;       // groups of 16 columns
+#pragma unroll 4
+    for (int S = kq; S < ngroups; S += 4) {
+      const int col = 16 * S + 4 * g;
+      jf4m a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+      if (col < r) {                         // r % 4 == 0: the whole 16-byte piece is inside the row
+        if (ga >= 0) a = *reinterpret_cast<const jf4m*>(arow + col);
+        if (gb >= 0) b = *reinterpret_cast<const jf4m*>(brow + col);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
+  }
+  if (tid == 0) rotated = 0;
+  __syncthreads();
+  {
+    const int i = tid >> 5, j = tid & 31;
+    const int blk = (i >> 4) | ((j >> 4) << 1);
+    float sum = 0.f;
+#pragma unroll
+    for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    Gm[0][i * GP + j] = sum;
+    Rot[i * GP + j] = i == j ? 1.f : 0.f;
+  }
+  __syncthreads();
+
+  // 2. inner sweeps on the Gram matrix
+  int cur = 0;
+  for (int isw = 0; isw < kGramInnerSweeps; ++isw)
+    for (int ir = 0; ir < R2 - 1; ++ir) {
+      // phase A: every wave derives the rotation of its pair
+      int p, q;
+      if (wave == 0) { p = R2 - 1; q = ir; }
+      else { p = (ir + wave) % (R2 - 1); q = (ir + (R2 - 1) - wave) % (R2 - 1); }
+      if (p > q) { const int x = p; p = q; q = x; }
+      const float* G = Gm[cur];
+      const float a = G[p * GP + p], bb = G[q * GP + q], c = G[p * GP + q];
+      const bool rot = grow(p) >= 0 && grow(q) >= 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
+      float cs = 1.f, sn = 0.f;
+      if (rot) {
+        const float zeta = (bb - a) / (2.f * c);
+        const float tt = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+        cs = 1.f / sqrtf(1.f + tt * tt);
+        sn = cs * tt;
+      }
+      if (lane == 0) {
+        alpha[p] = cs; beta[p] = -sn; partner[p] = q;
+        alpha[q] = cs; beta[q] = sn;  partner[q] = p;
+        if (rot) rotated = 1;
+      }
+      if (rot && lane < R2) {  // rows p, q of the accumulated rotation (only this wave touches them)
+        const float uu = Rot[p * GP + lane], vv = Rot[q * GP + lane];
+        Rot[p * GP + lane] = cs * uu - sn * vv;
+        Rot[q * GP + lane] = sn * uu + cs * vv;
+      }
+      __syncthreads();
+      // phase B: G <- J^T G J for the 16 disjoint rotations of this round
+      {
+        const int i = tid >> 5, j = tid & 31;
+        const int pi = partner[i], pj = partner[j];
+        const float ai = alpha[i], bi2 = beta[i], aj = alpha[j], bj2 = beta[j];
+        Gm[cur ^ 1][i * GP + j] = ai * (aj * G[i * GP + j] + bj2 * G[i * GP + pj]) + bi2 * (aj * G[pi * GP + j] + bj2 * G[pi * GP + pj]);
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
+
+  if (rotated == 0) return;  // nothing changed: leave Bw, Jt and the sweep flag alone (uniform)
+  if (tid == 0) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
+
+  // 3. apply the accumulated rotation to the rows of Bw and of Jt
+  {
+    const int i = lane & 15, g = lane >> 4;
+    float rot[2][8];
+    int rows[8], out_rows[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int sidx = 0; sidx < 8; ++sidx) rot[h][sidx] = Rot[(16 * h + i) * GP + 4 * sidx + g];
+#pragma unroll
+    for (int sidx = 0; sidx < 8; ++sidx) rows[sidx] = grow(4 * sidx + g);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) out_rows[h][v] = grow(16 * h + 4 * g + v);
+    gram_apply_rotation(t.Bw, r, rows, out_rows, rot, wave, lane);
+    gram_apply_rotation(t.Jt, r, rows, out_rows, rot, wave, lane);
   }
 }
 
@@ -761,6 +927,8 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
   for (int cand : {16, 8})
     if (jb == 0 && (size_t)2 * cand * ((r + 3) & ~3) * 4 + (size_t)4 * cand * cand * 4 <= 150 * 1024) jb = cand;
   if (r > kJacobiMaxR) jb = 0;  // the inner loop keeps a row pair in registers, unrolled for rows up to kJacobiMaxR
+  const bool use_gram = r % 4 == 0 && r >= 4;  // the Gram-matrix kernel stages no rows: any such r
+  if (use_gram) jb = kGramB;
   if (r > 1 && jb > 0) {
     const size_t smem = (size_t)2 * jb * ((r + 3) & ~3) * 4 + (size_t)4 * jb * jb * 4;
     static bool attr_set = false;
@@ -775,7 +943,9 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     const int players = (nblocks % 2 == 0) ? nblocks : nblocks + 1;   // >= 2
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
-        if (jb == 16)
+        if (use_gram)
+          hipLaunchKernelGGL(jacobi_gram_round_kernel, dim3(players / 2, n), dim3(1024), 0, stream, grp, round, players, sweep);
+        else if (jb == 16)
           hipLaunchKernelGGL(jacobi_block_round_kernel<16>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
         else
           hipLaunchKernelGGL(jacobi_block_round_kernel<8>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
