@@ -48,6 +48,9 @@ struct RefreshTensor {
   float* S;      // St: r x r, rows = eigenvectors, ordered by decreasing Ritz value, unit length
   float* tau;    // r
   float* vscale; // r
+  float* vclean; // round_up(r, 32) x k: reflectors as plain vectors (unit diagonal, zeros above, scaled), transposed
+  float* tmat;   // (r / 32 macro panels) x 32 x 32: triangular factors T of the compact WY form
+  float* tpart;  // 8 x 32 x 32: shares of V^T V of the macro panel being prepared
   float* lambda; // r
   int32_t* order;// r : order[i] = output column of eigenvector i
   int32_t* sweep_flag;  // kJacobiSweeps + 1 : sweep s rotated something
@@ -64,7 +67,7 @@ struct RefreshGroup {
 };
 
 struct Layout {
-  size_t C, Q, Z, Bw, Jt, S, tau, vscale, lambda, order, sweep_flag, total;
+  size_t C, Q, Z, Bw, Jt, S, tau, vscale, vclean, tmat, tpart, lambda, order, sweep_flag, total;
 };
 
 Layout layout_for(int64_t k, int64_t r) {
@@ -79,6 +82,9 @@ Layout layout_for(int64_t k, int64_t r) {
   L.S = take((size_t)r * r * 4);
   L.tau = take((size_t)r * 4);
   L.vscale = take((size_t)r * 4);
+  L.vclean = take((size_t)((r + 31) / 32 * 32) * k * 4);
+  L.tmat = take((size_t)((r + 31) / 32) * 1024 * 4);
+  L.tpart = take((size_t)8 * 1024 * 4);
   L.lambda = take((size_t)r * 4);
   L.order = take((size_t)r * 4);
   L.sweep_flag = take((size_t)(kJacobiSweeps + 1) * 4);
@@ -288,10 +294,10 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
 // of the target (Z itself while factoring, Q while forming the orthogonal factor), rows >= j0,
 // in forward order (H_nb-1 ... H_0 X: factoring) or reverse order (H_0 ... H_nb-1 X: forming Q).
 __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const RefreshGroup grp, int j0, int nb, int col_begin,
-                                                                       int target_is_q, int reverse) {
+                                                                       int target_is_q, int reverse, int col_end) {
   __shared__ float red[17 * kSW];
   const RefreshTensor& t = grp.t[blockIdx.y];
-  const int r = grp.r, k = t.k;
+  const int k = t.k;
   const float* __restrict__ Zv = t.Z;
   float* __restrict__ X = target_is_q ? t.Q : t.Z;
   const int tid = threadIdx.x;
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
       v[s][ii] = e;
     }
 #pragma unroll
-    for (int c = 0; c < kSW; ++c) x[s][c] = (row < k && c0 + c < r) ? X[(size_t)(c0 + c) * k + row] : 0.f;
+    for (int c = 0; c < kSW; ++c) x[s][c] = (row < k && c0 + c < col_end) ? X[(size_t)(c0 + c) * k + row] : 0.f;
   }
 #pragma unroll
   for (int ii = 0; ii < kNB; ++ii) {
@@ -341,7 +347,239 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
     if (row < k) {
 #pragma unroll
       for (int c = 0; c < kSW; ++c)
-        if (c0 + c < r) X[(size_t)(c0 + c) * k + row] = x[s][c];
+        if (c0 + c < col_end) X[(size_t)(c0 + c) * k + row] = x[s][c];
+    }
+  }
+}
+
+// Partial inner products for a 16 x 16 block on the matrix cores: lane (i = lane % 16, g = lane / 16)
+// holds row i of A and row i of B; every group of 16 positions base + 16 S .. + 15 contributes
+// sum_p A[i][p] B[j][p] through four v_mfma_f32_16x16x4_f32 (lane group g supplies positions
+// 4 g .. 4 g + 3 of the group, the same for A and B).  This wave takes groups kq, kq + 4, ...
+// Rows that do not exist (aok / bok false) count as zero.  limit - base need not be a multiple of 16,
+// but every 4-float piece is entirely inside or outside [base, limit).  Eight groups are loaded
+// before they are consumed, so the loop is not bound by one load latency per group.
+typedef float gf4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ gf4 gram_partial(const float* __restrict__ arow, bool aok, const float* __restrict__ brow, bool bok,
+                                            int base, int limit, int kq, int g) {
+  gf4 acc = {0.f, 0.f, 0.f, 0.f};
+  const gf4 zero = {0.f, 0.f, 0.f, 0.f};
+  const int ngroups = (limit - base + 15) >> 4;
+  const int nfull = (limit - base) >> 4;      // groups with all 16 positions inside
+  int S = kq;
+  for (; S + 28 < nfull; S += 32) {
+    gf4 a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int pos = base + 16 * (S + 4 * u) + 4 * g;
+      a[u] = *reinterpret_cast<const gf4*>(arow + pos);
+      b[u] = *reinterpret_cast<const gf4*>(brow + pos);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const gf4 au = aok ? a[u] : zero, bu = bok ? b[u] : zero;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(au[e], bu[e], acc, 0, 0, 0);
+    }
+  }
+  for (; S < ngroups; S += 4) {
+    const int pos = base + 16 * S + 4 * g;
+    gf4 a = zero, b = zero;
+    if (pos < limit) {
+      a = *reinterpret_cast<const gf4*>(arow + pos);
+      b = *reinterpret_cast<const gf4*>(brow + pos);
+    }
+    if (!aok) a = zero;
+    if (!bok) b = zero;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+// ---- compact WY form of a macro panel of up to 32 reflectors ---------------------------------------
+// H_0 H_1 ... H_{nb-1} = I - V T V^T with T upper triangular (T_jj = tau_j,
+// T_{0:j,j} = -tau_j T_{0:j,0:j} V_{:,0:j}^T v_j).  With it the trailing matrix is updated once per 32
+// reflectors, by matrix products on the matrix cores, instead of once per 8 with reductions.
+typedef float wf4 __attribute__((ext_vector_type(4)));
+constexpr int kWY = 32;
+
+// Slice blockIdx.x of kWYSlices of the positions >= J0: write the reflectors of macro panel J0 as plain
+// vectors into vclean (rows beyond nb are zero) and form this slice's share of S = V^T V on the
+// matrix cores (left in tpart; wy_tfactor_kernel adds the shares).
+constexpr int kWYSlices = 8;
+__global__ __launch_bounds__(1024) void wy_gram_kernel(const RefreshGroup grp, int J0, int nb) {
+  __shared__ float stage[16 * 256];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int k = t.k;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // slice of the positions, in units of 16 so that every 16-byte piece belongs to one slice
+  const int units = (k - J0 + 15) >> 4;
+  const int per = (units + kWYSlices - 1) / kWYSlices;
+  const int p_begin = J0 + 16 * per * blockIdx.x;
+  const int p_end = min(k, p_begin + 16 * per);
+  for (int j = wave; j < kWY; j += 16) {
+    const int col = J0 + j;                   // reflector index = row of Zt
+    const float vs = j < nb ? t.vscale[col] : 0.f;
+    const float* src = t.Z + (size_t)(j < nb ? col : 0) * k;
+    float* dst = t.vclean + (size_t)col * k;
+    for (int pos = p_begin + 4 * lane; pos < p_end; pos += 256) {
+      wf4 v = {0.f, 0.f, 0.f, 0.f};
+      if (j < nb) {
+        const wf4 z = *reinterpret_cast<const wf4*>(src + pos);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = pos + e > col ? z[e] * vs : (pos + e == col ? 1.f : 0.f);
+      }
+      *reinterpret_cast<wf4*>(dst + pos) = v;
+    }
+  }
+  __syncthreads();  // the rows written above are read back below by other waves of this workgroup
+  {
+    const int I0 = (wave & 1) * 16, Jb = ((wave >> 1) & 1) * 16, kq = wave >> 2;
+    const int i = lane & 15, g = lane >> 4;
+    const float* arow = t.vclean + (size_t)(J0 + I0 + i) * k;
+    const float* brow = t.vclean + (size_t)(J0 + Jb + i) * k;
+    wf4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (p_begin < p_end) acc = gram_partial(arow, true, brow, true, p_begin, p_end, kq, g);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];
+  }
+  __syncthreads();
+  {
+    const int i = tid >> 5, j = tid & 31;
+    const int blk = (i >> 4) | ((j >> 4) << 1);
+    float sum = 0.f;
+#pragma unroll
+    for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    t.tpart[blockIdx.x * (kWY * kWY) + tid] = sum;
+  }
+}
+
+// One workgroup of 64 lanes per tensor: S = sum of the slices' shares, then T column by column;
+// lane i owns row i of T in registers (the masked update keeps register indices static).
+__global__ __launch_bounds__(64) void wy_tfactor_kernel(const RefreshGroup grp, int J0, int nb) {
+  __shared__ float Sm[kWY * (kWY + 1)];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int lane = threadIdx.x;
+  for (int e = lane; e < kWY * kWY; e += 64) {
+    float sum = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < kWYSlices; ++sl) sum += t.tpart[sl * (kWY * kWY) + e];
+    Sm[(e >> 5) * (kWY + 1) + (e & 31)] = sum;
+  }
+  __syncthreads();
+  if (lane < kWY) {
+    const int i = lane;
+    float trow[kWY];
+#pragma unroll
+    for (int j = 0; j < kWY; ++j) trow[j] = 0.f;
+#pragma unroll 1
+    for (int j = 0; j < kWY; ++j) {
+      const float tau = j < nb ? t.tau[J0 + j] : 0.f;
+      float acc = 0.f;
+#pragma unroll
+      for (int l = 0; l < kWY; ++l) acc += trow[l] * Sm[l * (kWY + 1) + j];  // trow[l] = 0 unless i <= l < j
+      const float val = i == j ? tau : (i < j ? -tau * acc : 0.f);
+#pragma unroll
+      for (int jj = 0; jj < kWY; ++jj) trow[jj] = jj == j ? val : trow[jj];
+    }
+    float* out = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
+#pragma unroll
+    for (int j = 0; j < kWY; ++j) out[i * kWY + j] = trow[j];
+  }
+}
+
+// Apply macro panel J0 to 32 columns of the target (rows c0 .. c0+31 of the transposed storage),
+// positions >= J0:  x <- x - V Tf^T (V^T x)  with Tf = T when factoring (Q_p^T x) and T^T when
+// forming Q (Q_p x);  in row form w = x V^T, y = w Tf, x -= y V.
+__global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
+                                                        int target_is_q, int backward) {
+  __shared__ float stage[16 * 256];
+  __shared__ float Wm[kWY * (kWY + 1)];
+  __shared__ float Ym[kWY * (kWY + 1)];
+  __shared__ float Tf[kWY * (kWY + 1)];
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int k = t.k;
+  float* __restrict__ X = target_is_q ? t.Q : t.Z;
+  const float* __restrict__ V = t.vclean + (size_t)J0 * k;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c0 = col_begin + kWY * blockIdx.x;
+  {
+    const float* T = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
+    const int i = tid >> 5, j = tid & 31;
+    Tf[i * (kWY + 1) + j] = backward ? T[j * kWY + i] : T[i * kWY + j];
+  }
+  // w = x V^T: block (I0 target rows, Jb reflectors) over a quarter of the positions per wave
+  {
+    const int I0 = (wave & 1) * 16, Jb = ((wave >> 1) & 1) * 16, kq = wave >> 2;
+    const int i = lane & 15, g = lane >> 4;
+    const int xr = c0 + I0 + i;
+    const bool xok = xr < col_end;
+    const float* arow = X + (size_t)(xok ? xr : col_begin) * k;
+    const float* brow = V + (size_t)(Jb + i) * k;
+    const wf4 acc = gram_partial(arow, xok, brow, true, J0, k, kq, g);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];
+  }
+  __syncthreads();
+  {
+    const int i = tid >> 5, j = tid & 31;
+    const int blk = (i >> 4) | ((j >> 4) << 1);
+    float sum = 0.f;
+#pragma unroll
+    for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    Wm[i * (kWY + 1) + j] = sum;
+  }
+  __syncthreads();
+  {
+    const int i = tid >> 5, j = tid & 31;
+    float y = 0.f;
+#pragma unroll 8
+    for (int l = 0; l < kWY; ++l) y += Wm[i * (kWY + 1) + l] * Tf[l * (kWY + 1) + j];
+    Ym[i * (kWY + 1) + j] = y;
+  }
+  __syncthreads();
+  // x -= y V, 16 positions per wave at a time: acc starts as x, A = -y, B = V
+  {
+    const int i = lane & 15, g = lane >> 4;
+    float ya[2][8];
+    int xrow[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int sidx = 0; sidx < 8; ++sidx) ya[h][sidx] = -Ym[(16 * h + i) * (kWY + 1) + 4 * sidx + g];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int xr = c0 + 16 * h + 4 * g + v;
+        xrow[h][v] = xr < col_end ? xr : -1;
+      }
+    }
+    // two chunks of 16 positions per trip, all loads of a trip issued before its MFMAs
+    for (int n0 = J0 + 32 * wave; n0 < k; n0 += 512) {
+      float b[2][8];
+      wf4 acc[2][2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int pos = n0 + 16 * c + i;      // here i indexes the position inside the chunk
+#pragma unroll
+        for (int sidx = 0; sidx < 8; ++sidx) b[c][sidx] = pos < k ? V[(size_t)(4 * sidx + g) * k + pos] : 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[c][h][v] = (xrow[h][v] >= 0 && pos < k) ? X[(size_t)xrow[h][v] * k + pos] : 0.f;
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int pos = n0 + 16 * c + i;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int sidx = 0; sidx < 8; ++sidx) acc[c][h] = __builtin_amdgcn_mfma_f32_16x16x4f32(ya[h][sidx], b[c][sidx], acc[c][h], 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (xrow[h][v] >= 0 && pos < k) X[(size_t)xrow[h][v] * k + pos] = acc[c][h][v];
+        }
+      }
     }
   }
 }
@@ -570,19 +808,27 @@ constexpr int kGramB = 16, kGramR2 = 32;
 __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r, const int (&rows)[8], const int (&out_rows)[2][4],
                                                     const float (&rot)[2][8], int wave, int lane) {
   const int j = lane & 15;
-  for (int cb = wave; cb * 16 < r; cb += 16) {
-    const int col = cb * 16 + j;
-    float b[8];
+  // two blocks of 16 columns per trip, all loads of a trip issued before its MFMAs
+  for (int n0 = 32 * wave; n0 < r; n0 += 512) {
+    float b[2][8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) b[s] = (rows[s] >= 0 && col < r) ? Y[(size_t)rows[s] * r + col] : 0.f;
+    for (int c = 0; c < 2; ++c) {
+      const int col = n0 + 16 * c + j;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      jf4m acc = {0.f, 0.f, 0.f, 0.f};
+      for (int s = 0; s < 8; ++s) b[c][s] = (rows[s] >= 0 && col < r) ? Y[(size_t)rows[s] * r + col] : 0.f;
+    }
 #pragma unroll
-      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(rot[h][s], b[s], acc, 0, 0, 0);
+    for (int c = 0; c < 2; ++c) {
+      const int col = n0 + 16 * c + j;
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        if (out_rows[h][v] >= 0 && col < r) Y[(size_t)out_rows[h][v] * r + col] = acc[v];
+      for (int h = 0; h < 2; ++h) {
+        jf4m acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(rot[h][s], b[c][s], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (out_rows[h][v] >= 0 && col < r) Y[(size_t)out_rows[h][v] * r + col] = acc[v];
+      }
     }
   }
 }
@@ -621,19 +867,7 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
     const int ga = grow(I0 + i), gb = grow(J0 + i);
     const float* arow = t.Bw + (size_t)(ga >= 0 ? ga : 0) * r;
     const float* brow = t.Bw + (size_t)(gb >= 0 ? gb : 0) * r;
-    jf4m acc = {0.f, 0.f, 0.f, 0.f};
-    const int ngroups = (r + 15) >> 4;       // groups of 16 columns
-#pragma unroll 4
-    for (int S = kq; S < ngroups; S += 4) {
-      const int col = 16 * S + 4 * g;
-      jf4m a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-      if (col < r) {                         // r % 4 == 0: the whole 16-byte piece is inside the row
-        if (ga >= 0) a = *reinterpret_cast<const jf4m*>(arow + col);
-        if (gb >= 0) b = *reinterpret_cast<const jf4m*>(brow + col);
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], acc, 0, 0, 0);
-    }
+    const jf4m acc = gram_partial(arow, ga >= 0, brow, gb >= 0, 0, r, kq, g);
 #pragma unroll
     for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
   }
@@ -830,6 +1064,9 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     t.S = reinterpret_cast<float*>(it.ws + L.S);
     t.tau = reinterpret_cast<float*>(it.ws + L.tau);
     t.vscale = reinterpret_cast<float*>(it.ws + L.vscale);
+    t.vclean = reinterpret_cast<float*>(it.ws + L.vclean);
+    t.tmat = reinterpret_cast<float*>(it.ws + L.tmat);
+    t.tpart = reinterpret_cast<float*>(it.ws + L.tpart);
     t.lambda = reinterpret_cast<float*>(it.ws + L.lambda);
     t.order = reinterpret_cast<int32_t*>(it.ws + L.order);
     t.sweep_flag = reinterpret_cast<int32_t*>(it.ws + L.sweep_flag);
@@ -879,18 +1116,46 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     return launch_gemm_group(g, DType::F32, true, which == 1, Epilogue::StoreF32, stream);
   };
 
+  bool wy_ok = true;  // compact WY path: 16-byte pieces of the transposed rows
+  for (int i = 0; i < n; ++i) wy_ok = wy_ok && grp.t[i].k % 4 == 0;
   for (int it = 0; it < iters; ++it) {
     GALORE_RETURN_IF(gemm_f32(0));
     // Householder QR of Z
     if (kmax <= 1024 * kRPT) {
       // blocked: factor a panel of kNB columns, apply its reflectors to the trailing columns
+      if (wy_ok) {
+        // two levels: inside a macro panel of 32 columns the 8-column panels update only the macro
+        // panel; the rest of the matrix is updated once per macro panel in compact WY form
+        for (int J0 = 0; J0 < r; J0 += kWY) {
+          const int nb32 = r - J0 < kWY ? r - J0 : kWY;
+          for (int j0 = J0; j0 < J0 + nb32; j0 += kNB) {
+            const int nb = J0 + nb32 - j0 < kNB ? J0 + nb32 - j0 : kNB;
+            hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
+            const int inner = J0 + nb32 - (j0 + nb);
+            if (inner > 0)
+              hipLaunchKernelGGL(householder_block_apply_kernel, dim3((inner + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+                                 j0, nb, j0 + nb, 0, 0, J0 + nb32);
+          }
+          hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, grp, J0, nb32);
+          hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(64), 0, stream, grp, J0, nb32);
+          const int trailing = r - (J0 + nb32);
+          if (trailing > 0)
+            hipLaunchKernelGGL(wy_apply_kernel, dim3((trailing + kWY - 1) / kWY, n), dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0, 0);
+        }
+        GALORE_RETURN_IF(hipGetLastError());
+        hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+        for (int J0 = (r - 1) / kWY * kWY; J0 >= 0; J0 -= kWY)
+          hipLaunchKernelGGL(wy_apply_kernel, dim3((r - J0 + kWY - 1) / kWY, n), dim3(1024), 0, stream, grp, J0, J0, r, 1, 1);
+        GALORE_RETURN_IF(hipGetLastError());
+        continue;
+      }
       for (int j0 = 0; j0 < r; j0 += kNB) {
         const int nb = r - j0 < kNB ? r - j0 : kNB;
         hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
         const int ncols = r - (j0 + nb);
         if (ncols > 0)
           hipLaunchKernelGGL(householder_block_apply_kernel, dim3((ncols + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
-                             j0, nb, j0 + nb, 0, 0);
+                             j0, nb, j0 + nb, 0, 0, r);
       }
       GALORE_RETURN_IF(hipGetLastError());
       hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
@@ -898,7 +1163,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
       for (int j0 = last; j0 >= 0; j0 -= kNB) {
         const int nb = r - j0 < kNB ? r - j0 : kNB;
         hipLaunchKernelGGL(householder_block_apply_kernel, dim3((r - j0 + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
-                           j0, nb, j0, 1, 1);
+                           j0, nb, j0, 1, 1, r);
       }
       GALORE_RETURN_IF(hipGetLastError());
     } else {
