@@ -898,9 +898,11 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
       const bool rot = grow(p) >= 0 && grow(q) >= 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
       float cs = 1.f, sn = 0.f;
       if (rot) {
-        const float zeta = (bb - a) / (2.f * c);
-        const float tt = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
-        cs = 1.f / sqrtf(1.f + tt * tt);
+        // hardware reciprocal / square-root approximations (1 ulp): a rotation with c^2 + s^2 = 1 to
+        // within a few ulps is all that is needed, and this chain is the latency of every inner round
+        const float zeta = (bb - a) * __builtin_amdgcn_rcpf(2.f * c);
+        const float tt = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+        cs = __builtin_amdgcn_rsqf(1.f + tt * tt);
         sn = cs * tt;
       }
       if (lane == 0) {
