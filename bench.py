@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--refresh-iters", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
+    ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
+                    help="f32: the BASELINE configuration; q8: 8-bit block-wise moments (reported under its own metric name)")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")
@@ -88,7 +90,7 @@ def main():
     del srcs
     torch.cuda.synchronize()
 
-    opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True)
+    opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     overlap = not args.join_every_call and args.lanes > 1
     gb.galore_set_call_overlap(opt.ctx, overlap)
@@ -139,7 +141,10 @@ def main():
     flops = {"project_left": sum(2.0 * m * n * r for m, n in left), "project_right": sum(2.0 * m * n * r for m, n in right)}
     flops["back"] = flops["project_left"] + flops["project_right"]
     sN = 2 if dtype == "bf16" else 4
-    adam_bytes = sum(r * max(m, n) * (4 * 5 + sN) for m, n in shapes)  # read R, M, V; write M, V, N
+    if args.moments == "q8":  # read R and two code bytes, write two code bytes and N; four scale accesses per 256 elements
+        adam_bytes = sum(r * max(m, n) * (4 + 4 + sN + 16.0 / 256) for m, n in shapes)
+    else:
+        adam_bytes = sum(r * max(m, n) * (4 * 5 + sN) for m, n in shapes)  # read R, M, V; write M, V, N
     stage_ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}        # average duration of one launch
     stage_ms["adam"] = prof["adam"][0] / max(K * L, 1)                  # Adam: two launches (one per orientation) per layer
     gemm_stages = ["project_left", "project_right", "back"]
@@ -165,7 +170,7 @@ def main():
 
     # ---- CPU baseline: the fp64 oracle on a bounded sample --------------------------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.moments == "f32":  # the timed oracle is the fp32-moment step
         from oracle import galore_oracle as orc
         m, n = shapes[0]
         rng = np.random.default_rng(0)
@@ -183,15 +188,16 @@ def main():
                          "scaled by the layer set's flop ratio %.2f" % (m, n, r, dt, scale)}
 
     out = {
-        "metric": "GaLore step ms per LLaMA-7B layer set @r=1024",
+        "metric": "GaLore step ms per LLaMA-7B layer set @r=1024" + (" (8-bit moments)" if args.moments == "q8" else ""),
         "value": ms_per_step / L,
         "unit": "ms per layer set (7 matrices)",
         "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, fp32 M/V, r=%d, per-layer calls in "
-                               "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype, r, POOL),
+        "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, %s M/V, r=%d, per-layer calls in "
+                               "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype,
+                                                                                   "fp32" if args.moments == "f32" else "8-bit", r, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
                    "schedule": "consecutive calls overlap on two library streams, one join per step" if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},

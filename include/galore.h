@@ -52,7 +52,7 @@ typedef enum {
   GALORE_ERR_UNIMPLEMENTED = 9
 } galore_status;
 
-typedef enum { GALORE_F32 = 0, GALORE_BF16 = 1 } galore_dtype;
+typedef enum { GALORE_F32 = 0, GALORE_BF16 = 1, GALORE_U8 = 2 /* 8-bit moment codes only */ } galore_dtype;
 
 /* A row-major matrix in device memory.  BORROWED. */
 typedef struct {
@@ -72,12 +72,25 @@ typedef struct {
  *            projector with its contraction index contiguous.  Its initial contents do not
  *            matter and a checkpoint need not save it.
  * proj, m, v hold min(rows,cols)*r + 2*max(rows,cols)*r elements, the paper's mr + 2nr
- * (Sec. 4.2); proj_t adds another min(rows,cols)*r. */
+ * (Sec. 4.2); proj_t adds another min(rows,cols)*r.
+ *
+ * 8-bit moments (the "8-bit GaLore" of Sec. 4.3; the number format is this library's own, the
+ * paper prints none): give m and v dtype GALORE_U8 (same shapes, one byte per element) and set
+ *   m_scale, v_scale : fp32, (rows of m) x (cols of m / 256), ld == cols: one scale per block of
+ *                      256 consecutive elements of a row (max |m| and max v of the block).
+ * m code: sign | 4 exponent bits e | 3 mantissa bits f, magnitude (1 + f/8) 2^(e-15) for e > 0,
+ * (f/8) 2^-14 for e = 0; v code: 5 exponent bits | 3 mantissa bits, (1 + f/8) 2^(e-31) and
+ * (f/8) 2^-30; value = magnitude * scale; quantisation rounds |x| / scale to the nearest
+ * magnitude, ties to the even mantissa field.  Needs cols of m to be a multiple of 256
+ * (GALORE_ERR_UNIMPLEMENTED otherwise).  With fp32 moments m_scale and v_scale are ignored
+ * (data may be NULL). */
 typedef struct {
   galore_tensor proj;
   galore_tensor m;
   galore_tensor v;
   galore_tensor proj_t;
+  galore_tensor m_scale;
+  galore_tensor v_scale;
 } galore_state;
 
 /* Hyper-parameters (Algorithm 2 inputs; Sec. 4.4).  Paper defaults: update_gap 200,
@@ -196,6 +209,13 @@ galore_status galore_project(const galore_tensor* proj_t, const galore_tensor* G
 galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V,
                           const galore_tensor* N, int32_t transpose_n, float beta1, float beta2,
                           float eps, int64_t k, void* hip_stream);
+
+/* The same stage with 8-bit moments (see galore_state): Mc, Vc are GALORE_U8 with R's shape,
+ * Ms, Vs fp32 (R rows) x (R cols / 256); R's cols must be a multiple of 256.  Codes and scales
+ * are updated in place; N as in galore_adam. */
+galore_status galore_adam_q8(const galore_tensor* R, const galore_tensor* Mc, const galore_tensor* Vc,
+                             const galore_tensor* Ms, const galore_tensor* Vs, const galore_tensor* N,
+                             int32_t transpose_n, float beta1, float beta2, float eps, int64_t k, void* hip_stream);
 
 /* W <- (1 - lr*weight_decay) W - lr*scale * (P N  or  N Q^T) (Algorithm 2, last lines),
  * applied inside the GEMM epilogue; the full-size update is never stored.  N is

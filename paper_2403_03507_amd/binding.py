@@ -15,8 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libgalore.so")
 GALORE_OK = 0
 STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "DTYPE", 4: "RANK", 5: "ALIGN",
                 6: "WORKSPACE", 7: "STATE", 8: "HIP", 9: "UNIMPLEMENTED"}
-GALORE_F32, GALORE_BF16 = 0, 1
-_DTYPES = {torch.float32: GALORE_F32, torch.bfloat16: GALORE_BF16}
+GALORE_F32, GALORE_BF16, GALORE_U8 = 0, 1, 2
+_DTYPES = {torch.float32: GALORE_F32, torch.bfloat16: GALORE_BF16, torch.uint8: GALORE_U8}
 
 
 class galore_tensor(ctypes.Structure):
@@ -25,7 +25,8 @@ class galore_tensor(ctypes.Structure):
 
 
 class galore_state(ctypes.Structure):
-    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("v", galore_tensor), ("proj_t", galore_tensor)]
+    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("v", galore_tensor), ("proj_t", galore_tensor),
+                ("m_scale", galore_tensor), ("v_scale", galore_tensor)]
 
 
 class galore_hparams(ctypes.Structure):
@@ -43,7 +44,7 @@ class GaloreError(RuntimeError):
 
 EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
-           "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_project_back",
+           "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
            "galore_set_call_overlap", "galore_join"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
@@ -75,6 +76,7 @@ def lib():
         L.galore_transpose.argtypes = [tp, tp, vp]
         L.galore_project.argtypes = [tp, tp, tp, vp]
         L.galore_adam.argtypes = [tp, tp, tp, tp, i32, f32, f32, f32, i64, vp]
+        L.galore_adam_q8.argtypes = [tp, tp, tp, tp, tp, tp, i32, f32, f32, f32, i64, vp]
         L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
         L.galore_set_concurrency.argtypes = [vp, i32]
         L.galore_set_call_overlap.argtypes = [vp, i32]
@@ -169,6 +171,12 @@ def galore_adam(R, M, V, N, transpose_n, beta1, beta2, eps, k):
                              1 if transpose_n else 0, beta1, beta2, eps, k, _stream()))
 
 
+def galore_adam_q8(R, Mc, Vc, Ms, Vs, N, transpose_n, beta1, beta2, eps, k):
+    _check(lib().galore_adam_q8(ctypes.byref(desc(R)), ctypes.byref(desc(Mc)), ctypes.byref(desc(Vc)), ctypes.byref(desc(Ms)),
+                                ctypes.byref(desc(Vs)), ctypes.byref(desc(N)), 1 if transpose_n else 0, beta1, beta2, eps, k,
+                                _stream()))
+
+
 def galore_project_back(proj, N, W, lr, scale, weight_decay=0.0):
     _check(lib().galore_project_back(ctypes.byref(desc(proj)), ctypes.byref(desc(N)), ctypes.byref(desc(W)), lr, scale,
                                      weight_decay, _stream()))
@@ -203,24 +211,35 @@ class GaLore:
     """Owns the device memory of a tensor list's optimizer state (allocated with torch) and a
     library context bound to torch's current stream.  All arithmetic happens in the library."""
 
-    def __init__(self, weights, rank, device="cuda", workspace_bytes=None, **hparams):
+    def __init__(self, weights, rank, device="cuda", workspace_bytes=None, moments="f32", **hparams):
+        """moments: "f32" (Algorithm 2 as printed) or "q8" (8-bit codes + one fp32 scale per 256 elements)."""
+        assert moments in ("f32", "q8")
+        self.moments = moments
         self.hp = make_hparams(rank, **hparams)
         self.shapes = [(w.shape[0], w.shape[1]) for w in weights]
         self.dtypes = [w.dtype for w in weights]
         self.proj, self.M, self.V, self.proj_t = [], [], [], []
+        self.M_scale, self.V_scale = [], []
         for (m, n), dt in zip(self.shapes, self.dtypes):
             k, l = (m, n) if m <= n else (n, m)
             self.proj.append(torch.zeros(k, rank, dtype=dt, device=device))
             self.proj_t.append(torch.empty(rank, k, dtype=dt, device=device))
             shape = (rank, l) if m <= n else (l, rank)
-            self.M.append(torch.empty(shape, dtype=torch.float32, device=device))
-            self.V.append(torch.empty(shape, dtype=torch.float32, device=device))
+            mdt = torch.float32 if moments == "f32" else torch.uint8
+            self.M.append(torch.empty(shape, dtype=mdt, device=device))
+            self.V.append(torch.empty(shape, dtype=mdt, device=device))
+            if moments == "q8":
+                self.M_scale.append(torch.empty(shape[0], shape[1] // 256, dtype=torch.float32, device=device))
+                self.V_scale.append(torch.empty(shape[0], shape[1] // 256, dtype=torch.float32, device=device))
         w_descs = [shape_desc(m, n, dt) for (m, n), dt in zip(self.shapes, self.dtypes)]
         if workspace_bytes is None:
             workspace_bytes = galore_workspace_bytes(self.hp, w_descs)
         self.workspace = torch.empty(max(workspace_bytes, 256), dtype=torch.uint8, device=device)
-        states = [galore_state(desc(p), desc(m), desc(v), desc(pt))
-                  for p, m, v, pt in zip(self.proj, self.M, self.V, self.proj_t)]
+        none = galore_tensor(None, 0, 0, 0, GALORE_F32)
+        states = [galore_state(desc(p), desc(m), desc(v), desc(pt),
+                               desc(self.M_scale[i]) if moments == "q8" else none,
+                               desc(self.V_scale[i]) if moments == "q8" else none)
+                  for i, (p, m, v, pt) in enumerate(zip(self.proj, self.M, self.V, self.proj_t))]
         self.ctx = galore_init(self.hp, w_descs, states, self.workspace.data_ptr(), workspace_bytes)
 
     def step(self, weights, grads, lr, first=0):

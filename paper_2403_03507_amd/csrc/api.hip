@@ -30,6 +30,7 @@ struct TensorInfo {
   galore_state st;
   int64_t t;
   bool proj_t_valid;  // state.proj_t mirrors state.proj (only trusted when the library owns the projector)
+  bool q8;            // moments stored as 8-bit codes with block scales
 };
 
 }  // namespace
@@ -79,7 +80,7 @@ galore_status fail(galore_ctx* ctx, galore_status s, const char* fmt, ...) {
   return s;
 }
 
-bool valid_dtype(int32_t d) { return d == GALORE_F32 || d == GALORE_BF16; }
+bool valid_dtype(int32_t d, bool allow_u8) { return d == GALORE_F32 || d == GALORE_BF16 || (allow_u8 && d == GALORE_U8); }
 
 size_t step_need(int64_t ldim, int64_t r, DType dt) {
   return align_up((size_t)r * ldim * 4) + align_up((size_t)r * ldim * dtype_size(dt));
@@ -103,7 +104,8 @@ galore_status check_hparams(galore_ctx* ctx, const galore_hparams* hp) {
   return GALORE_OK;
 }
 
-galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* what, int idx, bool need_data) {
+galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* what, int idx, bool need_data,
+                           bool allow_u8 = false) {
   if (need_data && !t.data) return fail(ctx, GALORE_ERR_INVALID_ARG, "%s[%d].data is NULL", what, idx);
   if (t.rows < 1 || t.cols < 1) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] has empty shape %lld x %lld", what, idx,
                                             (long long)t.rows, (long long)t.cols);
@@ -111,7 +113,7 @@ galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* 
                                  (long long)t.cols);
   if (t.rows > INT32_MAX / 2 || t.ld > INT32_MAX / 2)
     return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] dimension too large", what, idx);
-  if (!valid_dtype(t.dtype)) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d].dtype %d unknown", what, idx, t.dtype);
+  if (!valid_dtype(t.dtype, allow_u8)) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d].dtype %d not allowed here", what, idx, t.dtype);
   return GALORE_OK;
 }
 
@@ -210,12 +212,29 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
     // K2: Adam on R.  N always leaves as (long side) x r: transposed for LEFT tensors.
     for (int left = 1; left >= 0; --left) {
       AdamGroup g{};
+      AdamQ8Group g8{};
       g.beta1 = hp.beta1; g.beta2 = hp.beta2; g.eps = hp.eps;
+      g8.beta1 = hp.beta1; g8.beta2 = hp.beta2; g8.eps = hp.eps;
+      g8.omb1 = 1.0f - hp.beta1; g8.omb2 = 1.0f - hp.beta2;
       for (const StepItem& it : items) {
         const TensorInfo& ti = ctx->tensors[it.tensor];
         if (ti.dt != dt || (int)ti.left != left) continue;
-        AdamProblem& p = g.p[g.count++];
         const double k = (double)(ti.t + 1);
+        const float ic1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
+        const float ic2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
+        if (ti.q8) {
+          AdamQ8Problem& p = g8.p[g8.count++];
+          p.R = it.R;
+          p.Mc = static_cast<uint8_t*>(ti.st.m.data); p.Vc = static_cast<uint8_t*>(ti.st.v.data);
+          p.Ms = static_cast<float*>(ti.st.m_scale.data); p.Vs = static_cast<float*>(ti.st.v_scale.data);
+          p.N = it.N;
+          p.rows = left ? r : (int)ti.rows;
+          p.cols = left ? (int)ti.cols : r;
+          p.transpose_n = left;
+          p.inv_c1 = ic1; p.inv_c2 = ic2;
+          continue;
+        }
+        AdamProblem& p = g.p[g.count++];
         p.R = it.R;
         p.M = static_cast<float*>(ti.st.m.data);
         p.V = static_cast<float*>(ti.st.v.data);
@@ -224,11 +243,12 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
         p.cols = left ? (int)ti.cols : r;
         p.count = (int64_t)r * ti.ldim;
         p.transpose_n = left;
-        p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
-        p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
+        p.inv_c1 = ic1;
+        p.inv_c2 = ic2;
       }
-      ProfScope prof(ctx, GALORE_STAGE_ADAM, g.count > 0, stream);
+      ProfScope prof(ctx, GALORE_STAGE_ADAM, g.count + g8.count > 0, stream);
       hipError_t e = launch_adam_group(g, dt, stream);
+      if (e == hipSuccess) e = launch_adam_q8_group(g8, dt, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "Adam launch");
     }
     // K3: project back + apply; with N as (long side) x r both orientations share one layout
@@ -474,15 +494,31 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
     ti.proj_t_valid = false;
     const int64_t mr = ti.left ? r : ti.rows, mc = ti.left ? ti.cols : r;
     const galore_tensor* mv[2] = {&S[i].m, &S[i].v};
+    ti.q8 = S[i].m.dtype == GALORE_U8 || S[i].v.dtype == GALORE_U8;
     for (int q = 0; q < 2; ++q) {
       const galore_tensor& x = *mv[q];
-      s = check_matrix(nullptr, x, q ? "S.v" : "S.m", i, true);
+      s = check_matrix(nullptr, x, q ? "S.v" : "S.m", i, true, true);
       if (s) return s;
-      if (x.dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d] moments must be fp32", i);
+      if (x.dtype != (ti.q8 ? GALORE_U8 : GALORE_F32))
+        return fail(nullptr, GALORE_ERR_DTYPE, "S[%d] moments must both be fp32 or both be 8-bit codes", i);
       if (x.rows != mr || x.cols != mc || x.ld != mc)
         return fail(nullptr, GALORE_ERR_SHAPE, "S[%d] moments must be dense %lld x %lld", i, (long long)mr, (long long)mc);
       if (reinterpret_cast<uintptr_t>(x.data) & 15)
         return fail(nullptr, GALORE_ERR_ALIGN, "S[%d] moments must be 16-byte aligned", i);
+    }
+    if (ti.q8) {
+      if (mc % 256 != 0)
+        return fail(nullptr, GALORE_ERR_UNIMPLEMENTED, "S[%d]: 8-bit moments need rows of a multiple of 256 elements, got %lld", i,
+                    (long long)mc);
+      const galore_tensor* sc[2] = {&S[i].m_scale, &S[i].v_scale};
+      for (int q = 0; q < 2; ++q) {
+        const galore_tensor& x = *sc[q];
+        s = check_matrix(nullptr, x, q ? "S.v_scale" : "S.m_scale", i, true);
+        if (s) return s;
+        if (x.dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d] moment scales must be fp32", i);
+        if (x.rows != mr || x.cols != mc / 256 || x.ld != x.cols)
+          return fail(nullptr, GALORE_ERR_SHAPE, "S[%d] moment scales must be dense %lld x %lld", i, (long long)mr, (long long)(mc / 256));
+      }
     }
     if (tensor_need(*hp, ti.kdim, ti.ldim, ti.dt) > workspace_bytes)
       return fail(nullptr, GALORE_ERR_WORKSPACE, "workspace of %zu bytes cannot hold tensor %d (needs %zu)", workspace_bytes,
@@ -512,9 +548,11 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
   }
   // M_0 = V_0 = 0 (Algorithm 2, initialisation)
   for (const TensorInfo& ti : ctx->tensors) {
-    const size_t bytes = (size_t)r * ti.ldim * 4;
+    const size_t bytes = (size_t)r * ti.ldim * (ti.q8 ? 1 : 4);  // code 0 decodes to 0
     hipError_t e = launch_fill_zero(ti.st.m.data, bytes, ctx->stream);
     if (e == hipSuccess) e = launch_fill_zero(ti.st.v.data, bytes, ctx->stream);
+    if (ti.q8 && e == hipSuccess) e = launch_fill_zero(ti.st.m_scale.data, (size_t)r * ti.ldim / 256 * 4, ctx->stream);
+    if (ti.q8 && e == hipSuccess) e = launch_fill_zero(ti.st.v_scale.data, (size_t)r * ti.ldim / 256 * 4, ctx->stream);
     if (e != hipSuccess) {
       galore_status st = hip_fail(nullptr, e, "zero-filling moments");
       delete ctx;
@@ -745,6 +783,43 @@ galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const 
   p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
   p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
   hipError_t e = launch_adam_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "Adam launch");
+}
+
+galore_status galore_adam_q8(const galore_tensor* R, const galore_tensor* Mc, const galore_tensor* Vc,
+                             const galore_tensor* Ms, const galore_tensor* Vs, const galore_tensor* N,
+                             int32_t transpose_n, float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
+  if (!R || !Mc || !Vc || !Ms || !Vs || !N) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
+  const galore_tensor* all[6] = {R, Mc, Vc, N, Ms, Vs};
+  const char* names[6] = {"R", "Mc", "Vc", "N", "Ms", "Vs"};
+  for (int i = 0; i < 6; ++i) {
+    galore_status s = check_matrix(nullptr, *all[i], names[i], 0, true, i == 1 || i == 2);
+    if (s) return s;
+    if (all[i]->ld != all[i]->cols) return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense", names[i]);
+    if (reinterpret_cast<uintptr_t>(all[i]->data) & 15) return fail(nullptr, GALORE_ERR_ALIGN, "%s must be 16-byte aligned", names[i]);
+  }
+  if (R->dtype != GALORE_F32 || Ms->dtype != GALORE_F32 || Vs->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "R, Ms, Vs must be fp32");
+  if (Mc->dtype != GALORE_U8 || Vc->dtype != GALORE_U8) return fail(nullptr, GALORE_ERR_DTYPE, "Mc, Vc must be 8-bit codes");
+  if (R->cols % 256 != 0) return fail(nullptr, GALORE_ERR_UNIMPLEMENTED, "8-bit moments need rows of a multiple of 256 elements");
+  for (int i = 1; i < 3; ++i)
+    if (all[i]->rows != R->rows || all[i]->cols != R->cols) return fail(nullptr, GALORE_ERR_SHAPE, "%s must have R's shape", names[i]);
+  for (int i = 4; i < 6; ++i)
+    if (all[i]->rows != R->rows || all[i]->cols != R->cols / 256) return fail(nullptr, GALORE_ERR_SHAPE, "%s must be rows x cols/256 of R", names[i]);
+  if (N->rows != (transpose_n ? R->cols : R->rows) || N->cols != (transpose_n ? R->rows : R->cols))
+    return fail(nullptr, GALORE_ERR_SHAPE, "N must have R's shape%s", transpose_n ? " transposed" : "");
+  if (k < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "k must be >= 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+    return fail(nullptr, GALORE_ERR_INVALID_ARG, "betas / eps out of range");
+  AdamQ8Group g{};
+  g.count = 1; g.beta1 = beta1; g.beta2 = beta2; g.omb1 = 1.0f - beta1; g.omb2 = 1.0f - beta2; g.eps = eps;
+  AdamQ8Problem& p = g.p[0];
+  p.R = static_cast<const float*>(R->data);
+  p.Mc = static_cast<uint8_t*>(Mc->data); p.Vc = static_cast<uint8_t*>(Vc->data);
+  p.Ms = static_cast<float*>(Ms->data); p.Vs = static_cast<float*>(Vs->data);
+  p.N = N->data; p.rows = (int)R->rows; p.cols = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
+  p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
+  p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
+  hipError_t e = launch_adam_q8_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "Adam launch");
 }
 

@@ -70,6 +70,33 @@ struct AdamGroup {
 // All problems of a group share n_dtype and transpose_n.
 hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream);
 
+// ---- grouped low-rank Adam with 8-bit block-wise moments ------------------------------------------
+// Moments are stored as one byte per element plus one fp32 scale per block of 256 consecutive
+// elements of the row-major matrix; cols must be a multiple of 256 so that a block never
+// straddles two rows.
+struct AdamQ8Problem {
+  const float* R;
+  uint8_t* Mc;     // first-moment codes: sign, 4 exponent bits, 3 mantissa bits
+  uint8_t* Vc;     // second-moment codes: 5 exponent bits, 3 mantissa bits
+  float* Ms;       // per block: max |m|
+  float* Vs;       // per block: max v
+  void* N;         // fp32 or bf16
+  int32_t rows;    // shape of R and of the code matrices (dense, row-major)
+  int32_t cols;
+  int32_t transpose_n;
+  float inv_c1, inv_c2;
+};
+
+struct AdamQ8Group {
+  int32_t count;
+  float beta1, beta2;
+  float omb1, omb2;  // 1 - beta, formed in fp32 on the host
+  float eps;
+  AdamQ8Problem p[kMaxGroup];
+};
+
+hipError_t launch_adam_q8_group(const AdamQ8Group& g, DType n_dtype, hipStream_t stream);
+
 // ---- grouped matrix transpose (projector k x r -> r x k) ------------------------------------
 struct TransposeProblem {
   const void* src;  // rows x cols, leading dimension lds
