@@ -178,6 +178,12 @@ galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on);
  * A no-op when nothing is pending. */
 galore_status galore_join(galore_ctx* ctx);
 
+/* The two library-owned HIP streams (which = 0, 1), for callers whose allocator must know which
+ * streams still read a gradient buffer it is about to recycle (with overlapped calls the library
+ * reads G on these streams after galore_step has returned).  The streams stay owned by the
+ * library and die with the context. */
+galore_status galore_get_stream(const galore_ctx* ctx, int32_t which, void** out_stream);
+
 /* Step counter t of one tensor (number of steps taken); set is for checkpoint resume. */
 galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t);
 galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t);

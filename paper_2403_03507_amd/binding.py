@@ -46,7 +46,7 @@ EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "gal
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
-           "galore_set_call_overlap", "galore_join"]
+           "galore_set_call_overlap", "galore_join", "galore_get_stream"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
 _lib = None
@@ -81,6 +81,7 @@ def lib():
         L.galore_set_concurrency.argtypes = [vp, i32]
         L.galore_set_call_overlap.argtypes = [vp, i32]
         L.galore_join.argtypes = [vp]
+        L.galore_get_stream.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_void_p)]
         L.galore_profile_start.argtypes = [vp]
         L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
@@ -194,6 +195,12 @@ def galore_join(ctx):
     _check(lib().galore_join(ctx), ctx)
 
 
+def galore_get_stream(ctx, which):
+    out = ctypes.c_void_p(None)
+    _check(lib().galore_get_stream(ctx, which, ctypes.byref(out)), ctx)
+    return out.value
+
+
 def galore_profile_start(ctx):
     _check(lib().galore_profile_start(ctx), ctx)
 
@@ -250,6 +257,10 @@ class GaLore:
 
     def join(self):
         galore_join(self.ctx)
+
+    def library_streams(self):
+        """The library's two streams as torch streams (for Tensor.record_stream)."""
+        return [torch.cuda.ExternalStream(galore_get_stream(self.ctx, i)) for i in range(2)]
 
     def refresh(self, grads, first=0):
         galore_refresh_subspace(self.ctx, [desc(g) for g in grads], first, len(grads))

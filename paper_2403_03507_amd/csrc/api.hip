@@ -686,6 +686,13 @@ galore_status galore_join(galore_ctx* ctx) {
   return join_all(ctx);
 }
 
+galore_status galore_get_stream(const galore_ctx* ctx, int32_t which, void** out_stream) {
+  if (!ctx || !out_stream) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx or out_stream is NULL");
+  if (which < 0 || which > 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "which must be 0 or 1");
+  *out_stream = ctx->aux[which];
+  return GALORE_OK;
+}
+
 galore_status galore_profile_start(galore_ctx* ctx) {
   if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
   for (ProfRecord& r : ctx->records) { ctx->event_pool.push_back(r.begin); ctx->event_pool.push_back(r.end); }

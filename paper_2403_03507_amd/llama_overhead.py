@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Overhead of per-layer GaLore updates on a LLaMA-shaped decoder stack (Sec. 4.3 / Sec. 5.5 of
+arXiv 2403.03507 report the end-to-end cost of the method on top of forward + backward).
+
+A stack of decoder blocks (RMSNorm, causal self-attention without biases, SwiGLU MLP; random
+weights, random hidden states as input; embedding and LM head left out) runs forward + backward
+  (a) alone, gradients dropped;
+  (b) with `hooks.PerLayerGaLore`: each block's 7 matrices are stepped by the library as soon as
+      their gradients exist;
+  (c) with torch's fused AdamW on the same matrices after the backward pass, for scale.
+Prints ONE JSON line with tokens/s of each and the overhead of (b) over (a).
+
+    python -m paper_2403_03507_amd.llama_overhead --d 4096 --f 11008 --heads 32 --layers 8 --rank 1024
+"""
+import argparse
+import json
+import os
+import sys
+
+import torch
+import torch.nn.functional as F
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+from paper_2403_03507_amd.hooks import PerLayerGaLore  # noqa: E402
+
+
+class RMSNorm(torch.nn.Module):
+    def __init__(self, d, dtype):
+        super().__init__()
+        self.weight = torch.nn.Parameter(torch.ones(d, dtype=dtype, device="cuda"))
+
+    def forward(self, x):
+        v = x.float()
+        return (v * torch.rsqrt(v.pow(2).mean(-1, keepdim=True) + 1e-6)).to(x.dtype) * self.weight
+
+
+class DecoderBlock(torch.nn.Module):
+    def __init__(self, d, f, heads, dtype):
+        super().__init__()
+        lin = lambda i, o: torch.nn.Linear(i, o, bias=False, dtype=dtype, device="cuda")
+        self.heads = heads
+        self.n1, self.n2 = RMSNorm(d, dtype), RMSNorm(d, dtype)
+        self.q, self.k, self.v, self.o = lin(d, d), lin(d, d), lin(d, d), lin(d, d)
+        self.gate, self.up, self.down = lin(d, f), lin(d, f), lin(f, d)
+
+    def matrices(self):
+        return [m.weight for m in (self.q, self.k, self.v, self.o, self.gate, self.up, self.down)]
+
+    def forward(self, x):
+        b, s, d = x.shape
+        h = self.n1(x)
+        split = lambda t: t.view(b, s, self.heads, d // self.heads).transpose(1, 2)
+        a = F.scaled_dot_product_attention(split(self.q(h)), split(self.k(h)), split(self.v(h)), is_causal=True)
+        x = x + self.o(a.transpose(1, 2).reshape(b, s, d))
+        h = self.n2(x)
+        return x + self.down(F.silu(self.gate(h)) * self.up(h))
+
+
+def timed(fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--d", type=int, default=4096)
+    ap.add_argument("--f", type=int, default=11008)
+    ap.add_argument("--heads", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=8)
+    ap.add_argument("--rank", type=int, default=1024)
+    ap.add_argument("--batch", type=int, default=4)
+    ap.add_argument("--seq", type=int, default=2048)
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--moments", choices=["f32", "q8"], default="f32")
+    args = ap.parse_args(argv)
+    torch.cuda.set_device(0)
+    dtype = torch.bfloat16
+    torch.manual_seed(0)
+    blocks = torch.nn.ModuleList([DecoderBlock(args.d, args.f, args.heads, dtype) for _ in range(args.layers)])
+    for p in blocks.parameters():
+        if p.dim() == 2:
+            torch.nn.init.normal_(p, std=0.02)
+    x = torch.randn(args.batch, args.seq, args.d, device="cuda").to(dtype)
+    tokens = args.batch * args.seq
+
+    def fwd_bwd():
+        h = x
+        for blk in blocks:
+            h = blk(h)
+        h.float().pow(2).mean().backward()
+
+    def plain():
+        fwd_bwd()
+        for p in blocks.parameters():
+            p.grad = None
+
+    ms_plain = timed(plain, args.reps)
+
+    mats = [p for blk in blocks for p in blk.matrices()]
+    adamw = torch.optim.AdamW(mats, lr=1e-4, fused=True)
+
+    def with_adamw():
+        fwd_bwd()
+        adamw.step()
+        for p in blocks.parameters():
+            p.grad = None
+
+    ms_adamw = timed(with_adamw, args.reps)
+    del adamw
+
+    drv = PerLayerGaLore([blk.matrices() for blk in blocks], args.rank, 1e-4, overlap_calls=True, update_gap=200,
+                         refresh_iters=4, moments=args.moments)
+    # the first step refreshes every projector; time it apart
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fwd_bwd(); drv.finish()
+    e1.record(); torch.cuda.synchronize()
+    ms_first = e0.elapsed_time(e1)
+
+    def with_galore():
+        fwd_bwd()
+        drv.finish()
+        for p in blocks.parameters():
+            p.grad = None   # the norm weights (not GaLore matrices)
+
+    ms_galore = timed(with_galore, args.reps)
+    drv.close()
+    out = {
+        "what": "forward + backward of a LLaMA-shaped decoder stack, with and without per-layer GaLore updates",
+        "config": {"d": args.d, "f": args.f, "heads": args.heads, "layers": args.layers, "rank": args.rank, "tokens": tokens,
+                   "dtype": "bf16", "moments": args.moments},
+        "ms_forward_backward": ms_plain, "ms_with_galore": ms_galore, "ms_with_fused_adamw": ms_adamw,
+        "ms_first_step_with_refresh": ms_first,
+        "tokens_per_s_forward_backward": tokens / ms_plain * 1e3,
+        "tokens_per_s_with_galore": tokens / ms_galore * 1e3,
+        "tokens_per_s_with_fused_adamw": tokens / ms_adamw * 1e3,
+        "galore_overhead": ms_galore / ms_plain - 1.0,
+        "adamw_overhead": ms_adamw / ms_plain - 1.0,
+    }
+    print(json.dumps(out))
+    return out
+
+
+if __name__ == "__main__":
+    main()
