@@ -80,8 +80,8 @@ typedef struct {
  *                      256 consecutive elements of a row (max |m| and max v of the block).
  * m code: sign | 4 exponent bits e | 3 mantissa bits f, magnitude (1 + f/8) 2^(e-15) for e > 0,
  * (f/8) 2^-14 for e = 0; v code: 5 exponent bits | 3 mantissa bits, (1 + f/8) 2^(e-31) and
- * (f/8) 2^-30; value = magnitude * scale; quantisation rounds |x| / scale to the nearest
- * magnitude, ties to the even mantissa field.  Needs cols of m to be a multiple of 256
+ * (f/8) 2^-30; value = magnitude * scale; quantisation rounds min(|x| * (1 / scale), 1) to the
+ * nearest magnitude, ties to the even mantissa field.  Needs cols of m to be a multiple of 256
  * (GALORE_ERR_UNIMPLEMENTED otherwise).  With fp32 moments m_scale and v_scale are ignored
  * (data may be NULL). */
 typedef struct {

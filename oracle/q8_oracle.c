@@ -20,8 +20,9 @@
  *   V code    5 exponent bits e, 3 mantissa bits f (no sign):
  *               e > 0: (1 + f/8) 2^(e-31);   e = 0: (f/8) 2^-30.   Largest used: e = 31, f = 0, i.e. 1.
  *   Decode    value = magnitude * scale, one fp32 multiplication.
- *   Encode    y = |x| / scale as ONE fp32 division (0 when scale = 0); the code is the table entry
- *             NEAREST to y; of two equally near entries the one with the even mantissa field wins.
+ *   Encode    y = min(|x| * (1 / scale), 1): ONE fp32 division per block for the reciprocal, ONE fp32
+ *             multiplication per element (0 when scale = 0); the code is the table entry NEAREST to
+ *             y; of two equally near entries the one with the even mantissa field wins.
  *             Written here as a search over the table, not as bit manipulation.
  *   Step      per element, all in fp32, each operation rounded once, in this order:
  *               m = fma(beta1, m_old, (1-beta1) * g)
@@ -72,14 +73,18 @@ static int q8_nearest(double y, int ebits) {
 
 uint8_t oracle_q8_encode_m(float x, float scale) {
   if (scale == 0.0f || x == 0.0f) return 0;
-  const float y = fabsf(x) / scale; /* one fp32 division */
+  const float inv = 1.0f / scale;   /* one fp32 division (the same for every element of a block) */
+  float y = fabsf(x) * inv;         /* one fp32 multiplication */
+  if (y > 1.0f) y = 1.0f;           /* |x| <= scale, but the rounded reciprocal can overshoot by an ulp */
   const int mag = q8_nearest((double)y, 4);
   return (uint8_t)((x < 0.0f ? 0x80 : 0) | mag);
 }
 
 uint8_t oracle_q8_encode_v(float x, float scale) {
   if (scale == 0.0f || x <= 0.0f) return 0;
-  const float y = x / scale;
+  const float inv = 1.0f / scale;
+  float y = x * inv;
+  if (y > 1.0f) y = 1.0f;
   return (uint8_t)q8_nearest((double)y, 5);
 }
 

@@ -5,8 +5,8 @@
 //   * first moment  : sign | 4 exponent bits e | 3 mantissa bits f, magnitude (1 + f/8) 2^(e-15)
 //                     for e > 0 and (f/8) 2^-14 for e = 0, times the scale (largest used: 1);
 //   * second moment : 5 exponent bits | 3 mantissa bits, (1 + f/8) 2^(e-31) / (f/8) 2^-30;
-//   * decode = magnitude * scale; encode = round |x| / scale to the nearest magnitude, ties to
-//     the even mantissa field.
+//   * decode = magnitude * scale; encode = round min(|x| * (1 / scale), 1) to the nearest magnitude
+//     (one reciprocal per block, one multiplication per element), ties to the even mantissa field.
 // One pass: decode, update in fp32 (every operation rounded once, fused multiply-adds where
 // written), form N from the unquantised new moments, take the block maxima over the wavefront,
 // encode.  One wavefront owns one block (4 elements per lane), so the maxima are wavefront
@@ -112,11 +112,13 @@ __global__ __launch_bounds__(256) void adam_q8_group_kernel(const AdamQ8Group gr
       amax = wave_max(amax);
       vmax = wave_max(vmax);
       unsigned om = 0u, ov = 0u;
+      const float inv_m = amax != 0.f ? 1.0f / amax : 0.f;   // one correctly rounded division per block
+      const float inv_v = vmax != 0.f ? 1.0f / vmax : 0.f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         unsigned bm = 0u, bv = 0u;
-        if (amax != 0.f && m[e] != 0.f) bm = (m[e] < 0.f ? 0x80u : 0u) | q8_encode_magnitude<4>(fabsf(m[e]) / amax);
-        if (vmax != 0.f && v[e] > 0.f) bv = q8_encode_magnitude<5>(v[e] / vmax);
+        if (amax != 0.f && m[e] != 0.f) bm = (m[e] < 0.f ? 0x80u : 0u) | q8_encode_magnitude<4>(fminf(fabsf(m[e]) * inv_m, 1.0f));
+        if (vmax != 0.f && v[e] > 0.f) bv = q8_encode_magnitude<5>(fminf(v[e] * inv_v, 1.0f));
         om |= bm << (8 * e);
         ov |= bv << (8 * e);
       }
