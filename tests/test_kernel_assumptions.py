@@ -1,0 +1,50 @@
+"""Build-time assumptions of the hand-scheduled GEMM, checked on the compiler's own assembly output
+of this repository's source (no GPU needed).
+
+The weight-update kernel lets its early W prefetch stay in flight across one barrier with
+`s_waitcnt vmcnt(8)`: that is only right if the compiler emits exactly 8 vector-memory loads for
+the 8 prefetched slices, after the tile loads of the same K step.  A compiler that merged, split
+or moved those loads would silently break the wait count; this test would catch it."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+from conftest import ROOT
+
+HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_early_weight_prefetch_is_exactly_eight_loads(tmp_path):
+    src = os.path.join(ROOT, "paper_2403_03507_amd", "csrc", "gemm_bf16.hip")
+    out = str(tmp_path / "gemm_bf16.s")
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", out, src],
+                          stderr=subprocess.DEVNULL)
+    text = open(out).read()
+    kernels = re.findall(r"^(_ZN6galore14gemm_dl_kernelILb1ELb[01]ELNS_8EpilogueE1E\w+):[^\n]*\n(.*?)\.end_amdhsa_kernel", text, flags=re.S | re.M)
+    assert len(kernels) == 2                                   # (K,X) and (K,K) weight-update kernels
+    for name, body in kernels:
+        ops = []
+        for line in body.split("\n"):
+            t = line.split(";")[0].strip()
+            if t.startswith("global_load_lds"):
+                ops.append("T")                                 # tile load (direct to LDS)
+            elif t.startswith("global_load"):
+                ops.append("W")                                 # load into registers: the W prefetch
+            elif t.startswith("global_store") or t.startswith("global_atomic"):
+                ops.append("S")
+            elif t.startswith("s_waitcnt") and "vmcnt(8)" in t:
+                ops.append("8")
+            elif t.startswith("s_barrier"):
+                ops.append("B")
+        seq = "".join(ops)
+        first = seq.index("8")                                  # the hand-written wait; the compiler's own waits
+        assert seq[first + 1] == "B", name                      # for the prefetched registers come later, in the epilogue
+        before = seq[:first]
+        # the last memory operations before the wait: 8 tile loads of the step, then exactly 8 register loads
+        assert before.endswith("T" * 8 + "W" * 8), (name, before[-40:])
+        assert "S" not in before[before.rindex("B"):], name     # and no store in between
