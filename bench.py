@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
-                    help="f32: the BASELINE configuration; q8: 8-bit block-wise moments (reported under its own metric name)")
+                    help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")

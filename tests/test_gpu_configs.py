@@ -1,4 +1,4 @@
-"""Step parity on one layer of each smaller BASELINE stack (130M, 350M, 1B shapes and gradient
+"""Step parity on one layer of each smaller LLaMA stack of the paper (130M, 350M, 1B shapes and gradient
 recipes), bf16 W/G, fp32 M/V.  The projector is a seeded orthonormal block rounded to bf16 (the
 oracle's own SVD at these sizes takes minutes; the refresh is gated separately), both sides get the
 same bits.  The 1B shapes include n = 5461: odd, so rows are not even 4-byte aligned and the GEMMs
