@@ -74,10 +74,17 @@ template <class T, bool KCONTIG, int BX, int BK, int NT, bool ALIGNED> struct Op
         if (o < olim && i < ilim) v = *reinterpret_cast<const uint4*>(base + (size_t)o * ld + i);
       } else {
         if (o < olim) {
-          T tmp[VEC];
+          const T* src = base + (size_t)o * ld + i;
+          if (i + VEC <= ilim) {
+            // whole 16-byte piece inside the row, but only element-aligned: memcpy lets the compiler
+            // pick the widest access the target allows at that alignment
+            __builtin_memcpy(&v, src, sizeof(uint4));
+          } else {
+            T tmp[VEC];
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) tmp[e] = (i + e < ilim) ? base[(size_t)o * ld + i + e] : T(0);
-          v = *reinterpret_cast<const uint4*>(tmp);
+            for (int e = 0; e < VEC; ++e) tmp[e] = (i + e < ilim) ? src[e] : T(0);
+            v = *reinterpret_cast<const uint4*>(tmp);
+          }
         }
       }
       regs[it] = v;
