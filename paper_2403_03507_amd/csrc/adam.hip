@@ -66,6 +66,11 @@ __global__ __launch_bounds__(256) void adam_group_kernel(const AdamGroup grp) {
 // its contraction index contiguous in memory.  One block per 64 x 64 tile: R, M, V are read and
 // M, V written row-wise with 16-byte vectors, N goes through a padded LDS tile and leaves
 // column-wise, again as 16-byte vectors.  Ragged or unaligned tiles take an element-wise path.
+// 16-byte access to four floats that are only 4-byte aligned (rows of odd length): the compiler picks
+// the widest access the target allows at that alignment
+__device__ __forceinline__ f32x4 load4(const float* p) { f32x4 v; __builtin_memcpy(&v, p, sizeof v); return v; }
+__device__ __forceinline__ void store4(float* p, f32x4 v) { __builtin_memcpy(p, &v, sizeof v); }
+
 template <class TN>
 __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGroup grp) {
   constexpr int TS = 64;
@@ -81,7 +86,7 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
   float* __restrict__ M = pr.M;
   float* __restrict__ V = pr.V;
   TN* __restrict__ N = static_cast<TN*>(pr.N);
-  const bool aligned = (cols % 4 == 0) && (rows % VEC == 0);
+  const bool aligned = rows % VEC == 0;  // rows of N^T stay 16-byte aligned; R, M, V rows may be of any length
   for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
     const int i0 = (t / tiles_c) * TS, j0 = (t % tiles_c) * TS;
     const bool full = aligned && i0 + TS <= rows && j0 + TS <= cols;
@@ -90,17 +95,17 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
       for (int ps = 0; ps < 4; ++ps) {
         const int i = ps * 16 + (threadIdx.x >> 4), j = (threadIdx.x & 15) * 4;
         const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
-        const f32x4 g = *reinterpret_cast<const f32x4*>(R + idx);
-        f32x4 m = *reinterpret_cast<const f32x4*>(M + idx);
-        f32x4 v = *reinterpret_cast<const f32x4*>(V + idx);
+        const f32x4 g = load4(R + idx);
+        f32x4 m = load4(M + idx);
+        f32x4 v = load4(V + idx);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           float me = m[e], ve = v[e];
           tile[j + e][i] = (TN)adam_entry(g[e], me, ve, beta1, beta2, eps, ic1, ic2);
           m[e] = me; v[e] = ve;
         }
-        *reinterpret_cast<f32x4*>(M + idx) = m;
-        *reinterpret_cast<f32x4*>(V + idx) = v;
+        store4(M + idx, m);
+        store4(V + idx, v);
       }
       __syncthreads();
       constexpr int LPR = TS / VEC;        // lanes per output row
