@@ -13,20 +13,42 @@ using CfgDefault = TileCfg<128, 128, 32, 2, 2>;
 // 128x128 tiles (more LDS and L2 traffic per flop).
 using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;  // 8 waves of 128 x 64, two 64 KB stages
 
+// A group is split by what each problem allows: problems that meet the large-tile kernel's
+// alignment rules go there together, the rest to the general kernel (aligned and element-aligned
+// problems apart), so one odd-shaped tensor does not drag its whole group onto the slow path.
 template <class T, bool AK, bool BKC, Epilogue EPI>
 inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
+  GemmGroup dl{}, al{}, un{};
+  for (int i = 0; i < g.count; ++i) {
+    GemmGroup one{};
+    one.count = 1;
+    one.p[0] = g.p[i];
+    bool to_dl = false;
+    if constexpr (std::is_same<T, __bf16>::value) to_dl = group_fits_dl(one, AK, BKC, EPI, CfgDl::BK);
+    GemmGroup& dst = to_dl ? dl : (group_is_aligned<T>(one, AK, BKC) ? al : un);
+    dst.p[dst.count++] = g.p[i];
+  }
   if constexpr (std::is_same<T, __bf16>::value) {
-    if (group_fits_dl(g, AK, BKC, EPI, CfgDl::BK)) {
-      plan_tiles<CfgDl>(g);
-      if (g.total_tiles == 0) return hipSuccess;
-      return launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(g, stream);
+    if (dl.count > 0) {
+      plan_tiles<CfgDl>(dl);
+      if (dl.total_tiles > 0) {
+        hipError_t e = launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(dl, stream);
+        if (e != hipSuccess) return e;
+      }
     }
   }
-  plan_tiles<CfgDefault>(g);
-  if (g.total_tiles == 0) return hipSuccess;
-  if (group_is_aligned<T>(g, AK, BKC))
-    return launch_gemm_instance<T, AK, BKC, true, EPI, CfgDefault>(g, stream);
-  return launch_gemm_instance<T, AK, BKC, false, EPI, CfgDefault>(g, stream);
+  if (al.count > 0) {
+    plan_tiles<CfgDefault>(al);
+    if (al.total_tiles > 0) {
+      hipError_t e = launch_gemm_instance<T, AK, BKC, true, EPI, CfgDefault>(al, stream);
+      if (e != hipSuccess) return e;
+    }
+  }
+  if (un.count > 0) {
+    plan_tiles<CfgDefault>(un);
+    if (un.total_tiles > 0) return launch_gemm_instance<T, AK, BKC, false, EPI, CfgDefault>(un, stream);
+  }
+  return hipSuccess;
 }
 
 // The layout / epilogue combinations the library uses:
