@@ -26,9 +26,9 @@ PEAK_HBM_GBS = 8000.0
 # runs of paper_2403_03507_amd/traffic_probe.py, calibrated with a 1 GiB copy (see
 # profiles/step_llama7b_hbm_traffic.md).  Reported as roofline.traffic; null for other shapes.
 MEASURED_TRAFFIC_BYTES_7B = {
-    "project_left": 581.3e6 + 157.6e6,
+    "project_left": 590.0e6 + 157.6e6,
     "project_right": 205.7e6 + 45.1e6,
-    "back": 1131.5e6 + 404.8e6,
+    "back": 1090.4e6 + 404.8e6,
     "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
 }
 

@@ -29,6 +29,7 @@ template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_> struct DlC
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
 };
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
@@ -77,12 +78,19 @@ template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
   // that the compiler does not see an LDS write it would fence every later LDS read against
   // (it would wait for ALL outstanding loads, the prefetched tile included); ordering against
   // the fragment reads is provided by the vmcnt waits and the barrier of the main loop.
-  __device__ __forceinline__ void issue(const void* src, unsigned lds_tile, int wave) const {
+  // STREAM marks the loads non-temporal: for an operand whose panels are used once by the
+  // workgroups that share them and not again soon, so that they do not displace the other
+  // operand's panels (which the XCD needs again in its next round) from L2.
+  template <bool STREAM> __device__ __forceinline__ void issue(const void* src, unsigned lds_tile, int wave) const {
 #pragma unroll
     for (int it = 0; it < PER_WAVE; ++it) {
       const unsigned dst = __builtin_amdgcn_readfirstlane(lds_tile + (wave + it * NW) * 1024);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(dst), "v"(voff[it]), "s"(src) : "memory");
+      if (STREAM)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                     :: "s"(dst), "v"(voff[it]), "s"(src) : "memory");
+      else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(dst), "v"(voff[it]), "s"(src) : "memory");
     }
   }
 
@@ -127,6 +135,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   using BOp = DlOperand<BKC, BN, BK, NW>;
   constexpr int STAGE_BYTES = AOp::TILE_BYTES + BOp::TILE_BYTES;
   constexpr int RING_BYTES = S * STAGE_BYTES;
+  // Measured on the 7B shapes: streaming G in the LEFT projection (its panels are shared by the
+  // four tile rows of a band at the same time and never needed again) -2.7 %; streaming the B
+  // panels of the weight update +9 % (slower), G of the RIGHT projection no change.
+  constexpr bool STREAM_A = false;
+  constexpr bool STREAM_B = EPI == Epilogue::StoreF32 && AK && !BKC;
   static_assert(S == 2, "the cross-tile stream is written for a two-stage ring");
   static_assert(WN == 64 || WN == 128, "the strip epilogue covers 8 rows with one or two passes of the wave");
   constexpr int PITCH = WN + 8;           // floats; 4 PITCH = 32 (mod 64) spreads the two half-waves over the banks
@@ -188,8 +201,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   const unsigned lds0 = (unsigned)(uintptr_t)smem_dl;
   auto issue_step = [&](int kt, int stage) {
     const unsigned st = lds0 + stage * STAGE_BYTES;
-    opa.issue(a_src + kt * a_step, st, wave);
-    opb.issue(b_src + kt * b_step, st + AOp::TILE_BYTES, wave);
+    opa.template issue<STREAM_A>(a_src + kt * a_step, st, wave);
+    opb.template issue<STREAM_B>(b_src + kt * b_step, st + AOp::TILE_BYTES, wave);
   };
 
   // epilogue geometry: a strip is 8 rows x WN columns of the wave's tile (accumulator registers
@@ -253,7 +266,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
               const int row = row0 + 32 * i + 8 * q + RPP * ps;
-              wpre[i][q][ps] = *reinterpret_cast<const bf16x8*>(W + (size_t)(row < M ? row : M - 1) * ldc + colc);
+              // W is read once and written once per step: non-temporal accesses keep it from
+              // displacing the operand panels that the XCD's other workgroups still need in L2
+              wpre[i][q][ps] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(
+                                   W + (size_t)(row < M ? row : M - 1) * ldc + colc)));
             }
         }
     };
@@ -373,7 +389,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
               o[e] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e] - pr.s1 * lo[e]);
               o[e + 4] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e + 4] - pr.s1 * hi[e]);
             }
-            *reinterpret_cast<bf16x8*>(W + (size_t)row * ldc + col) = o;
+            __builtin_nontemporal_store(__builtin_bit_cast(i32x4, o), reinterpret_cast<i32x4*>(W + (size_t)row * ldc + col));
           } else {
             float* C = static_cast<float*>(pr.C);
             float* dst = C + (size_t)row * ldc + col;
