@@ -51,6 +51,7 @@ struct RefreshTensor {
   float* vclean; // round_up(r, 32) x k: reflectors as plain vectors (unit diagonal, zeros above, scaled), transposed
   float* tmat;   // (r / 32 macro panels) x 32 x 32: triangular factors T of the compact WY form
   float* tpart;  // 8 x 32 x 32: shares of V^T V of the macro panel being prepared
+  float* wpart;  // (r / 32 + 1) x 4 x 32 x 32: shares of w = x V^T, per block of 32 target rows and slice of positions
   float* lambda; // r
   int32_t* order;// r : order[i] = output column of eigenvector i
   int32_t* sweep_flag;  // kJacobiSweeps + 1 : sweep s rotated something
@@ -67,7 +68,7 @@ struct RefreshGroup {
 };
 
 struct Layout {
-  size_t C, Q, Z, Bw, Jt, S, tau, vscale, vclean, tmat, tpart, lambda, order, sweep_flag, total;
+  size_t C, Q, Z, Bw, Jt, S, tau, vscale, vclean, tmat, tpart, wpart, lambda, order, sweep_flag, total;
 };
 
 Layout layout_for(int64_t k, int64_t r) {
@@ -85,6 +86,7 @@ Layout layout_for(int64_t k, int64_t r) {
   L.vclean = take((size_t)((r + 31) / 32 * 32) * k * 4);
   L.tmat = take((size_t)((r + 31) / 32) * 1024 * 4);
   L.tpart = take((size_t)8 * 1024 * 4);
+  L.wpart = take((size_t)((r + 31) / 32 + 1) * 4 * 1024 * 4);
   L.lambda = take((size_t)r * 4);
   L.order = take((size_t)r * 4);
   L.sweep_flag = take((size_t)(kJacobiSweeps + 1) * 4);
@@ -489,27 +491,33 @@ __global__ __launch_bounds__(64) void wy_tfactor_kernel(const RefreshGroup grp, 
   }
 }
 
-// Apply macro panel J0 to 32 columns of the target (rows c0 .. c0+31 of the transposed storage),
-// positions >= J0:  x <- x - V Tf^T (V^T x)  with Tf = T when factoring (Q_p^T x) and T^T when
-// forming Q (Q_p x);  in row form w = x V^T, y = w Tf, x -= y V.
-__global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
-                                                        int target_is_q, int backward) {
+// Apply macro panel J0 to the target (rows col_begin .. col_end-1 of the transposed storage), positions
+// >= J0:  x <- x - V Tf^T (V^T x)  with Tf = T when factoring (Q_p^T x) and T^T when forming Q (Q_p x);
+// in row form w = x V^T, y = w Tf, x -= y V.  Two launches over a grid of (32 target rows) x (slice of
+// the positions) x (tensor), so that late macro panels, which have few target rows left, still fill the
+// chip, and no workgroup has to pull more than a few hundred KB through its CU's L2 port:
+//   wy_project_kernel  this slice's share of w (32 x 32) into wpart;
+//   wy_update_kernel   w = sum of the shares, y = w Tf, then x -= y V on this slice of the positions.
+constexpr int kWYApplySlices = 4;
+__device__ __forceinline__ void wy_slice(int J0, int k, int s, int& p_begin, int& p_end) {
+  const int units = (k - J0 + 63) >> 6;  // slices are whole 64-position chunks (one wave trip of the update)
+  const int per = (units + kWYApplySlices - 1) / kWYApplySlices;
+  p_begin = J0 + 64 * per * s;
+  p_end = min(k, p_begin + 64 * per);
+}
+
+__global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
+                                                          int target_is_q) {
   __shared__ float stage[16 * 256];
-  __shared__ float Wm[kWY * (kWY + 1)];
-  __shared__ float Ym[kWY * (kWY + 1)];
-  __shared__ float Tf[kWY * (kWY + 1)];
-  const RefreshTensor& t = grp.t[blockIdx.y];
+  const RefreshTensor& t = grp.t[blockIdx.z];
   const int k = t.k;
-  float* __restrict__ X = target_is_q ? t.Q : t.Z;
+  const float* __restrict__ X = target_is_q ? t.Q : t.Z;
   const float* __restrict__ V = t.vclean + (size_t)J0 * k;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c0 = col_begin + kWY * blockIdx.x;
-  {
-    const float* T = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
-    const int i = tid >> 5, j = tid & 31;
-    Tf[i * (kWY + 1) + j] = backward ? T[j * kWY + i] : T[i * kWY + j];
-  }
-  // w = x V^T: block (I0 target rows, Jb reflectors) over a quarter of the positions per wave
+  int p_begin, p_end;
+  wy_slice(J0, k, blockIdx.y, p_begin, p_end);
+  // block (I0 target rows, Jb reflectors) over a quarter of the slice per wave
   {
     const int I0 = (wave & 1) * 16, Jb = ((wave >> 1) & 1) * 16, kq = wave >> 2;
     const int i = lane & 15, g = lane >> 4;
@@ -517,7 +525,8 @@ __global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, 
     const bool xok = xr < col_end;
     const float* arow = X + (size_t)(xok ? xr : col_begin) * k;
     const float* brow = V + (size_t)(Jb + i) * k;
-    const wf4 acc = gram_partial(arow, xok, brow, true, J0, k, kq, g);
+    wf4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (p_begin < p_end) acc = gram_partial(arow, xok, brow, true, p_begin, p_end, kq, g);
 #pragma unroll
     for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];
   }
@@ -528,6 +537,31 @@ __global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, 
     float sum = 0.f;
 #pragma unroll
     for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    t.wpart[((size_t)blockIdx.x * kWYApplySlices + blockIdx.y) * (kWY * kWY) + tid] = sum;  // entry (i, j)
+  }
+}
+
+__global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
+                                                         int target_is_q, int backward) {
+  __shared__ float Wm[kWY * (kWY + 1)];
+  __shared__ float Ym[kWY * (kWY + 1)];
+  __shared__ float Tf[kWY * (kWY + 1)];
+  const RefreshTensor& t = grp.t[blockIdx.z];
+  const int k = t.k;
+  float* __restrict__ X = target_is_q ? t.Q : t.Z;
+  const float* __restrict__ V = t.vclean + (size_t)J0 * k;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c0 = col_begin + kWY * blockIdx.x;
+  int p_begin, p_end;
+  wy_slice(J0, k, blockIdx.y, p_begin, p_end);
+  if (p_begin >= p_end) return;  // uniform
+  {
+    const float* T = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
+    const int i = tid >> 5, j = tid & 31;
+    Tf[i * (kWY + 1) + j] = backward ? T[j * kWY + i] : T[i * kWY + j];
+    float sum = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < kWYApplySlices; ++sl) sum += t.wpart[((size_t)blockIdx.x * kWYApplySlices + sl) * (kWY * kWY) + tid];
     Wm[i * (kWY + 1) + j] = sum;
   }
   __syncthreads();
@@ -539,7 +573,7 @@ __global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, 
     Ym[i * (kWY + 1) + j] = y;
   }
   __syncthreads();
-  // x -= y V, 16 positions per wave at a time: acc starts as x, A = -y, B = V
+  // x -= y V on this slice: acc starts as x, A = -y, B = V
   {
     const int i = lane & 15, g = lane >> 4;
     float ya[2][8];
@@ -554,31 +588,38 @@ __global__ __launch_bounds__(1024) void wy_apply_kernel(const RefreshGroup grp, 
         xrow[h][v] = xr < col_end ? xr : -1;
       }
     }
-    // two chunks of 16 positions per trip, all loads of a trip issued before its MFMAs
-    for (int n0 = J0 + 32 * wave; n0 < k; n0 += 512) {
-      float b[2][8];
-      wf4 acc[2][2];
+    // 64 positions per trip: lane (i, g) owns positions pos0 .. pos0 + 3 (one 16-byte access per row),
+    // position pos0 + c belongs to MFMA column block c, so block c holds positions {n0 + 4 n + c}.
+    // All loads of a trip are issued before its MFMAs.
+    for (int n0 = p_begin + 64 * wave; n0 < p_end; n0 += 1024) {
+      const int pos0 = n0 + 4 * i;
+      const bool pok = pos0 < p_end;          // slice ends are multiples of 4: a piece is inside or outside as a whole
+      wf4 b[8];
+      wf4 x[2][4];
+      const wf4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const int pos = n0 + 16 * c + i;      // here i indexes the position inside the chunk
+      for (int sidx = 0; sidx < 8; ++sidx) b[sidx] = pok ? *reinterpret_cast<const wf4*>(V + (size_t)(4 * sidx + g) * k + pos0) : zero;
 #pragma unroll
-        for (int sidx = 0; sidx < 8; ++sidx) b[c][sidx] = pos < k ? V[(size_t)(4 * sidx + g) * k + pos] : 0.f;
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int v = 0; v < 4; ++v)
+          x[h][v] = (xrow[h][v] >= 0 && pok) ? *reinterpret_cast<const wf4*>(X + (size_t)xrow[h][v] * k + pos0) : zero;
 #pragma unroll
-          for (int v = 0; v < 4; ++v) acc[c][h][v] = (xrow[h][v] >= 0 && pos < k) ? X[(size_t)xrow[h][v] * k + pos] : 0.f;
-      }
+      for (int h = 0; h < 2; ++h) {
+        wf4 acc[4];
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const int pos = n0 + 16 * c + i;
+        for (int c = 0; c < 4; ++c) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+          for (int v = 0; v < 4; ++v) acc[c][v] = x[h][v][c];
 #pragma unroll
-          for (int sidx = 0; sidx < 8; ++sidx) acc[c][h] = __builtin_amdgcn_mfma_f32_16x16x4f32(ya[h][sidx], b[c][sidx], acc[c][h], 0, 0, 0);
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (xrow[h][v] >= 0 && pos < k) X[(size_t)xrow[h][v] * k + pos] = acc[c][h][v];
+          for (int sidx = 0; sidx < 8; ++sidx) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(ya[h][sidx], b[sidx][c], acc[c], 0, 0, 0);
         }
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (xrow[h][v] >= 0 && pok) {
+            const wf4 o = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+            *reinterpret_cast<wf4*>(X + (size_t)xrow[h][v] * k + pos0) = o;
+          }
       }
     }
   }
@@ -808,27 +849,31 @@ constexpr int kGramB = 16, kGramR2 = 32;
 __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r, const int (&rows)[8], const int (&out_rows)[2][4],
                                                     const float (&rot)[2][8], int wave, int lane) {
   const int j = lane & 15;
-  // two blocks of 16 columns per trip, all loads of a trip issued before its MFMAs
-  for (int n0 = 32 * wave; n0 < r; n0 += 512) {
-    float b[2][8];
+  // 64 columns per trip: lane (j, g) owns columns col0 .. col0 + 3 (one 16-byte access per row), column
+  // col0 + c belongs to MFMA column block c.  r is a multiple of 4, so a piece is inside or outside as
+  // a whole.  All loads of a trip are issued before its MFMAs.
+  const jf4m zero = {0.f, 0.f, 0.f, 0.f};
+  for (int n0 = 64 * wave; n0 < r; n0 += 1024) {
+    const int col0 = n0 + 4 * j;
+    const bool cok = col0 < r;
+    jf4m b[8];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const int col = n0 + 16 * c + j;
+    for (int s = 0; s < 8; ++s) b[s] = (rows[s] >= 0 && cok) ? *reinterpret_cast<const jf4m*>(Y + (size_t)rows[s] * r + col0) : zero;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) b[c][s] = (rows[s] >= 0 && col < r) ? Y[(size_t)rows[s] * r + col] : 0.f;
-    }
+    for (int h = 0; h < 2; ++h) {
+      jf4m acc[4];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const int col = n0 + 16 * c + j;
+      for (int c = 0; c < 4; ++c) {
+        acc[c] = zero;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        jf4m acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(rot[h][s], b[c][s], acc, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-          if (out_rows[h][v] >= 0 && col < r) Y[(size_t)out_rows[h][v] * r + col] = acc[v];
+        for (int s = 0; s < 8; ++s) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(rot[h][s], b[s][c], acc[c], 0, 0, 0);
       }
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (out_rows[h][v] >= 0 && cok) {
+          const jf4m o = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+          *reinterpret_cast<jf4m*>(Y + (size_t)out_rows[h][v] * r + col0) = o;
+        }
     }
   }
 }
@@ -1069,6 +1114,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     t.vclean = reinterpret_cast<float*>(it.ws + L.vclean);
     t.tmat = reinterpret_cast<float*>(it.ws + L.tmat);
     t.tpart = reinterpret_cast<float*>(it.ws + L.tpart);
+    t.wpart = reinterpret_cast<float*>(it.ws + L.wpart);
     t.lambda = reinterpret_cast<float*>(it.ws + L.lambda);
     t.order = reinterpret_cast<int32_t*>(it.ws + L.order);
     t.sweep_flag = reinterpret_cast<int32_t*>(it.ws + L.sweep_flag);
@@ -1141,13 +1187,19 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
           hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, grp, J0, nb32);
           hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(64), 0, stream, grp, J0, nb32);
           const int trailing = r - (J0 + nb32);
-          if (trailing > 0)
-            hipLaunchKernelGGL(wy_apply_kernel, dim3((trailing + kWY - 1) / kWY, n), dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0, 0);
+          if (trailing > 0) {
+            const dim3 grid((trailing + kWY - 1) / kWY, kWYApplySlices, n);
+            hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0);
+            hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0, 0);
+          }
         }
         GALORE_RETURN_IF(hipGetLastError());
         hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
-        for (int J0 = (r - 1) / kWY * kWY; J0 >= 0; J0 -= kWY)
-          hipLaunchKernelGGL(wy_apply_kernel, dim3((r - J0 + kWY - 1) / kWY, n), dim3(1024), 0, stream, grp, J0, J0, r, 1, 1);
+        for (int J0 = (r - 1) / kWY * kWY; J0 >= 0; J0 -= kWY) {
+          const dim3 grid((r - J0 + kWY - 1) / kWY, kWYApplySlices, n);
+          hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, grp, J0, J0, r, 1);
+          hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, grp, J0, J0, r, 1, 1);
+        }
         GALORE_RETURN_IF(hipGetLastError());
         continue;
       }
