@@ -931,13 +931,22 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
 
   // 2. inner sweeps on the Gram matrix
   int cur = 0;
+  // Round 0 of a sweep pairs every block exactly once: there the inner sweep covers all pairs of the
+  // 32 rows (31 rounds), which also rotates the pairs INSIDE each block once per sweep.  The other
+  // rounds only need the 16 x 16 pairs between the two blocks: 16 rounds of (i, 16 + (i + ir) % 16).
+  const bool all_pairs = round == 0;
+  const int inner_rounds = all_pairs ? R2 - 1 : B;
   for (int isw = 0; isw < kGramInnerSweeps; ++isw)
-    for (int ir = 0; ir < R2 - 1; ++ir) {
+    for (int ir = 0; ir < inner_rounds; ++ir) {
       // phase A: every wave derives the rotation of its pair
       int p, q;
-      if (wave == 0) { p = R2 - 1; q = ir; }
-      else { p = (ir + wave) % (R2 - 1); q = (ir + (R2 - 1) - wave) % (R2 - 1); }
-      if (p > q) { const int x = p; p = q; q = x; }
+      if (all_pairs) {
+        if (wave == 0) { p = R2 - 1; q = ir; }
+        else { p = (ir + wave) % (R2 - 1); q = (ir + (R2 - 1) - wave) % (R2 - 1); }
+        if (p > q) { const int x = p; p = q; q = x; }
+      } else {
+        p = wave; q = B + ((wave + ir) & (B - 1));
+      }
       const float* G = Gm[cur];
       const float a = G[p * GP + p], bb = G[q * GP + q], c = G[p * GP + q];
       const bool rot = grow(p) >= 0 && grow(q) >= 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
