@@ -11,6 +11,8 @@
 // written), form N from the unquantised new moments, take the block maxima over the wavefront,
 // encode.  One wavefront owns one block (4 elements per lane), so the maxima are wavefront
 // reductions and nothing but N's transposition needs LDS.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace galore {
@@ -21,36 +23,46 @@ typedef __bf16 q_bf16x4 __attribute__((ext_vector_type(4)));
 
 template <int EBITS> __device__ __forceinline__ float q8_magnitude(unsigned code) {  // code without sign
   constexpr int bias = (1 << EBITS) - 1;
+  // (1 + f/8) 2^(e-bias) = (8 + f) 2^(e-bias-3) for e > 0, (f/8) 2^(1-bias) = f 2^(1-bias-3) for e = 0:
+  // an integer of at most 4 bits scaled by a power of two, exact either way
   const unsigned e = code >> 3, f = code & 7u;
-  if (e == 0) return (float)f * __builtin_ldexpf(1.0f, -(bias + 2));      // (f/8) 2^(1-bias), exact
-  return __uint_as_float(((e - bias + 127u) << 23) | (f << 20));           // (1 + f/8) 2^(e-bias)
+  const unsigned mant = e ? 8u + f : f;
+  const int ex = (int)(e ? e : 1u) - (bias + 3);
+  return __builtin_ldexpf((float)mant, ex);
 }
 
 // y in [0, 1] -> code of the nearest magnitude; round-to-nearest-even on a 3-bit mantissa is
-// exactly "nearest, ties to the even mantissa field", binade changes included
+// exactly "nearest, ties to the even mantissa field", binade changes included.  For a normal
+// magnitude the rounding is one integer addition on the bits of y: adding 0x7FFFF plus the lowest
+// kept bit carries into the kept mantissa bit exactly when the dropped part is above one half, or
+// equal to it with the kept field odd, and a mantissa that rounds up to 8 carries on into the exponent.
 template <int EBITS> __device__ __forceinline__ unsigned q8_encode_magnitude(float y) {
   constexpr int bias = (1 << EBITS) - 1;
   constexpr int emin = 1 - bias;                    // exponent of the smallest normal magnitude
-  if (!(y >= 0x1p-40f)) return 0u;                  // far below half of the smallest step (2^-18 / 2^-34)
   const unsigned bits = __float_as_uint(y);
-  const int exp = (int)(bits >> 23) - 127;
-  if (exp >= emin) {
-    const unsigned mant = bits & 0x7FFFFFu;
-    unsigned f = mant >> 20;
-    const unsigned rem = mant & 0xFFFFFu;
-    if (rem > 0x80000u || (rem == 0x80000u && (f & 1u))) ++f;
-    unsigned e = (unsigned)(exp + bias);
-    if (f == 8u) { f = 0u; ++e; }
-    return (e << 3) | f;
-  }
+  const unsigned kept = (bits + 0x7FFFFu + ((bits >> 20) & 1u)) >> 20;   // (biased exponent << 3) | f after rounding
+  const unsigned normal = kept - ((unsigned)(127 - bias) << 3);           // (e << 3) | f
   // below the smallest normal: uniform steps of 2^(emin-3); 8 steps reach the smallest normal (code 8)
-  return (unsigned)__builtin_rintf(y * __builtin_ldexpf(1.0f, 3 - emin));
+  const unsigned sub = (unsigned)__builtin_rintf(y * __builtin_ldexpf(1.0f, 3 - emin));
+  return y >= __builtin_ldexpf(1.0f, emin) ? normal : sub;   // y < 2^-40 rounds to 0 in the second form
 }
 
+// Maximum over the 64 lanes of a wavefront, every lane gets it.  Data-parallel-primitive moves inside
+// the VALU (quad permutes, row mirrors, row broadcasts) instead of six LDS-crossbar shuffles; lanes a
+// row mask excludes see their own value again.  The maximum does not depend on the order.
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-  return x;
+  auto dpp = [](float v, auto ctrl, auto row_mask) {
+    const int b = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(b, b, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false));
+  };
+  using std::integral_constant;
+  x = fmaxf(x, dpp(x, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{}));   // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp(x, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{}));   // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp(x, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{}));  // row_half_mirror
+  x = fmaxf(x, dpp(x, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{}));  // row_mirror: each row of 16 holds its maximum
+  x = fmaxf(x, dpp(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{}));  // row_bcast15 into rows 1 and 3
+  x = fmaxf(x, dpp(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{}));  // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
 __device__ __forceinline__ void store_n4(float* N, size_t i, q_f32x4 n) { *reinterpret_cast<q_f32x4*>(N + i) = n; }
