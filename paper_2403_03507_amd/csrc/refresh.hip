@@ -35,6 +35,10 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kJacobiSweeps = 10;   // upper bound; sweeps after convergence return at once
 constexpr float kJacobiTol = 1e-5f;  // |b_p.b_q| <= tol |b_p||b_q|: a few times the rounding floor of an fp32 dot of length r
+// A sweep whose largest rotation stayed below this level is the last one (Gram-matrix kernel): inner
+// products of long fp32 rows keep crossing kJacobiTol by rounding alone, so "no rotation at all" is
+// rarely reached although the result has stopped changing.
+constexpr float kJacobiStopTol = 4e-5f;
 constexpr int kNB = 8;               // reflectors per Householder panel
 constexpr int kRPT = 4;              // rows per thread in the panel kernels (1024 threads): k - j0 <= 4096
 constexpr int kSW = 8;               // columns per block in the blocked reflector application
@@ -885,7 +889,8 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
   __shared__ float stage[16 * 256];          // per wave: a 16 x 16 partial Gram block
   __shared__ float alpha[R2], beta[R2];      // per row: new_row = alpha * row + beta * partner row
   __shared__ int partner[R2];
-  __shared__ int rotated;
+  __shared__ int rotated;      // some rotation was applied: Bw and Jt have to be updated
+  __shared__ int significant;  // some rotation was above the stopping level: another sweep is due
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
   if (sweep > 0 && t.sweep_flag[sweep - 1] == 0) return;  // converged
@@ -916,7 +921,7 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
 #pragma unroll
     for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
   }
-  if (tid == 0) rotated = 0;
+  if (tid == 0) { rotated = 0; significant = 0; }
   __syncthreads();
   {
     const int i = tid >> 5, j = tid & 31;
@@ -963,6 +968,7 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
         alpha[p] = cs; beta[p] = -sn; partner[p] = q;
         alpha[q] = cs; beta[q] = sn;  partner[q] = p;
         if (rot) rotated = 1;
+        if (rot && c * c > (kJacobiStopTol * kJacobiStopTol) * a * bb) significant = 1;
       }
       if (rot && lane < R2) {  // rows p, q of the accumulated rotation (only this wave touches them)
         const float uu = Rot[p * GP + lane], vv = Rot[q * GP + lane];
@@ -982,7 +988,7 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
     }
 
   if (rotated == 0) return;  // nothing changed: leave Bw, Jt and the sweep flag alone (uniform)
-  if (tid == 0) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
+  if (tid == 0 && significant) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
 
   // 3. apply the accumulated rotation to the rows of Bw and of Jt
   {
