@@ -11,6 +11,8 @@
  *   - Adam on R with bias correction and N = Mhat / (sqrt(Vhat) + eps)   [Algorithm 2, update block; Eq. for N_t in Sec. 4.2]
  *   - projection back and weight update  W <- W - lr*alpha*P N            [Algorithm 2, last three lines]
  *   - top-r singular vectors of G by one-sided Jacobi (no LAPACK)         [Sec. 3.3, SVD equation for P_t, Q_t; Algorithm 2, refresh branch]
+ *   - the two-sided form of Definition 3.6,  G~ = P rho(P^T G Q) Q^T  with rho = Adam,
+ *     P = [u_1..u_r], Q = [v_1..v_r]                                      [Sec. 3.3, Definition 3.6 and the SVD equation]
  *
  * Matrices are dense row-major double arrays.  OpenMP is used on outermost
  * loops only; there is no blocking, no intrinsics and no library call.
@@ -281,5 +283,63 @@ int oracle_projector(const double* G, int64_t m, int64_t n, int64_t r,
     for (int64_t j = 0; j < n; ++j) Gt[j * m + i] = G[i * n + j];
   int rc = oracle_top_left_singular_vectors(Gt, n, m, r, proj, sigma, tol, max_sweeps);
   free(Gt);
+  return rc;
+}
+
+/* ---------- two-sided projection (Definition 3.6) --------------------------- */
+
+/* R (r x r) = P^T G Q, with P (m x r), G (m x n), Q (n x r): the projected gradient R_t of
+ * Definition 3.6 / Theorem 3.8.  Written as the two plain products above, (P^T G) Q. */
+void oracle_project_two_sided(const double* P, const double* G, const double* Q, double* R,
+                              int64_t m, int64_t n, int64_t r) {
+  double* T = (double*)malloc((size_t)r * n * sizeof(double));
+  oracle_project_left(P, G, T, m, n, r);       /* T = P^T G   (r x n) */
+  oracle_project_right(T, Q, R, r, n, r);      /* R = T Q     (r x r) */
+  free(T);
+}
+
+/* W (m x n) <- (1 - lr*wd) W - lr*alpha * P N Q^T, with N (r x r): G~_t = P_t rho_t(R_t) Q_t^T of
+ * Definition 3.6, scaled by alpha and subtracted as in Algorithm 2 (positive-gradient convention). */
+void oracle_apply_two_sided(double* W, const double* P, const double* N, const double* Q,
+                            int64_t m, int64_t n, int64_t r,
+                            double lr, double alpha, double weight_decay) {
+  double* S = (double*)malloc((size_t)r * n * sizeof(double));   /* S = N Q^T (r x n) */
+  for (int64_t i = 0; i < r; ++i)
+    for (int64_t j = 0; j < n; ++j) {
+      double acc = 0.0;
+      for (int64_t k = 0; k < r; ++k) acc += N[i * r + k] * Q[j * r + k];
+      S[i * n + j] = acc;
+    }
+  oracle_apply_left(W, P, S, m, n, r, lr, alpha, weight_decay);
+  free(S);
+}
+
+/* Both projectors of the SVD equation of Sec. 3.3: P = [u_1..u_r] (m x r), Q = [v_1..v_r] (n x r)
+ * of G = U S V^T.  The vectors of the SHORT side come from the Jacobi routine above with their
+ * canonical signs (they are the one-sided projector of Algorithm 2); each vector of the long side
+ * is the one the decomposition pairs with it, v_i = G^T u_i / s_i (or u_i = G v_i / s_i), so that
+ * sum_i s_i u_i v_i^T is the leading part of G.  Needs s_r > 0 (returns -2 otherwise: the partner
+ * vector is then not determined by G).  sigma: min(m, n) values.  Returns the sweeps used or -1. */
+int oracle_projector_pair(const double* G, int64_t m, int64_t n, int64_t r,
+                          double* P, double* Q, double* sigma, double tol, int max_sweeps) {
+  const int left = m <= n;
+  double* S = left ? P : Q;                       /* short side: k x r */
+  double* L = left ? Q : P;                       /* long side:  l x r */
+  const int64_t l = left ? n : m;
+  const int rc = oracle_projector(G, m, n, r, S, sigma, tol, max_sweeps);
+  if (rc < 0) return rc;
+  for (int64_t c = 0; c < r; ++c) {
+    double nrm2 = 0.0;
+    for (int64_t j = 0; j < l; ++j) {
+      double acc = 0.0;
+      if (left) { for (int64_t i = 0; i < m; ++i) acc += G[i * n + j] * P[i * r + c]; }   /* (G^T u_c)[j] */
+      else      { for (int64_t i = 0; i < n; ++i) acc += G[j * n + i] * Q[i * r + c]; }   /* (G v_c)[j]   */
+      L[j * r + c] = acc;
+      nrm2 += acc * acc;
+    }
+    const double nrm = sqrt(nrm2);   /* = s_c */
+    if (!(nrm > 0.0)) return -2;
+    for (int64_t j = 0; j < l; ++j) L[j * r + c] /= nrm;
+  }
   return rc;
 }

@@ -67,6 +67,10 @@ def lib():
         L.oracle_top_left_singular_vectors.restype = ctypes.c_int
         L.oracle_projector.argtypes = [_dp, _i64, _i64, _i64, _dp, _dp, _f64, ctypes.c_int]
         L.oracle_projector.restype = ctypes.c_int
+        L.oracle_project_two_sided.argtypes = [_dp, _dp, _dp, _dp, _i64, _i64, _i64]
+        L.oracle_apply_two_sided.argtypes = [_dp, _dp, _dp, _dp, _i64, _i64, _i64, _f64, _f64, _f64]
+        L.oracle_projector_pair.argtypes = [_dp, _i64, _i64, _i64, _dp, _dp, _dp, _f64, ctypes.c_int]
+        L.oracle_projector_pair.restype = ctypes.c_int
     return _lib
 
 
@@ -197,6 +201,82 @@ def projector(G, r, tol=1e-12, max_sweeps=60):
     if sweeps < 0:
         raise RuntimeError("Jacobi SVD did not converge")
     return proj, s
+
+
+def project_two_sided(P, G, Q):
+    """R (r x r) = P^T G Q  (Definition 3.6)."""
+    P, G, Q = _c(P), _c(G), _c(Q)
+    (m, n), r = G.shape, P.shape[1]
+    assert P.shape == (m, r) and Q.shape == (n, r)
+    R = np.empty((r, r))
+    lib().oracle_project_two_sided(_p(P), _p(G), _p(Q), _p(R), m, n, r)
+    return R
+
+
+def apply_two_sided(W, P, N, Q, lr, alpha, weight_decay=0.0):
+    """In place W <- (1 - lr*wd) W - lr*alpha * P N Q^T  (Definition 3.6, N r x r)."""
+    P, N, Q = _c(P), _c(N), _c(Q)
+    (m, n), r = W.shape, P.shape[1]
+    assert P.shape == (m, r) and Q.shape == (n, r) and N.shape == (r, r)
+    lib().oracle_apply_two_sided(_p(W), _p(P), _p(N), _p(Q), m, n, r, lr, alpha, weight_decay)
+    return W
+
+
+def projector_pair(G, r, tol=1e-12, max_sweeps=60):
+    """P = [u_1..u_r], Q = [v_1..v_r] of G = U S V^T (Sec. 3.3), paired signs, plus the singular values."""
+    G = _c(G)
+    m, n = G.shape
+    P, Q, s = np.empty((m, r)), np.empty((n, r)), np.empty(min(m, n))
+    rc = lib().oracle_projector_pair(_p(G), m, n, r, _p(P), _p(Q), _p(s), tol, max_sweeps)
+    if rc == -2:
+        raise RuntimeError("singular value r is zero: the right vector is not determined")
+    if rc < 0:
+        raise RuntimeError("Jacobi SVD did not converge")
+    return P, Q, s
+
+
+class GaLoreTensorTwoSided:
+    """One weight matrix under the two-sided rule of Definition 3.6 with rho = Adam (the update block of
+    Algorithm 2 applied to the r x r matrix R = P^T G Q); fp64 arithmetic, storage-dtype state."""
+
+    def __init__(self, W, rank, update_gap=200, scale=0.25, beta1=0.9, beta2=0.999,
+                 eps=1e-8, weight_decay=0.0, dtype="f32", auto_refresh=True):
+        self.dtype = dtype
+        self.W = round_storage(W, dtype)
+        self.m, self.n = self.W.shape
+        self.r = int(rank)
+        assert 1 <= self.r <= min(self.m, self.n)
+        self.T = int(update_gap)
+        self.alpha, self.beta1, self.beta2 = float(scale), float(beta1), float(beta2)
+        self.eps, self.wd = float(eps), float(weight_decay)
+        self.auto_refresh = auto_refresh
+        self.M = np.zeros((self.r, self.r))
+        self.V = np.zeros((self.r, self.r))
+        self.P = self.Q = self.sigma = None
+        self.t = 0
+        self.last_R = self.last_N = None
+
+    def refresh(self, G):
+        P, Q, s = projector_pair(G, self.r)
+        self.P, self.Q, self.sigma = round_storage(P, self.dtype), round_storage(Q, self.dtype), s
+        return self.P, self.Q
+
+    def set_projectors(self, P, Q):
+        self.P, self.Q = round_storage(P, self.dtype), round_storage(Q, self.dtype)
+
+    def step(self, G, lr):
+        G = round_storage(G, self.dtype)
+        if self.auto_refresh and self.t % self.T == 0:
+            self.refresh(G)
+        R = project_two_sided(self.P, G, self.Q)
+        N = adam(R, self.M, self.V, self.beta1, self.beta2, self.eps, self.t + 1)
+        self.last_R, self.last_N = R, N
+        apply_two_sided(self.W, self.P, N, self.Q, lr, self.alpha, self.wd)
+        self.W = round_storage(self.W, self.dtype)
+        self.M = round_storage(self.M, "f32")
+        self.V = round_storage(self.V, "f32")
+        self.t += 1
+        return self.W
 
 
 class GaLoreTensor:
