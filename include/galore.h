@@ -231,6 +231,42 @@ galore_status galore_project_back(const galore_tensor* proj, const galore_tensor
                                   const galore_tensor* W, float lr, float scale,
                                   float weight_decay, void* hip_stream);
 
+/* ---- Two-sided projection (Sec. 3.3, Definition 3.6) ----
+ * The general rule the paper states before it drops one projector for memory (Sec. 4.2):
+ *     G~ = P rho(P^T G Q) Q^T,   P = [u_1..u_r] (m x r),  Q = [v_1..v_r] (n x r)  of  G = U S V^T,
+ * with rho = the Adam map of Algorithm 2's update block on the r x r matrix R = P^T G Q:
+ *     W <- (1 - lr*weight_decay) W - lr*scale * P N Q^T.
+ * State per tensor: mr + nr + 2 r^2 elements.  One tensor per call, no context: the caller keeps
+ * the step count t (0-based, as in galore_get_step) and clears M, V before the first step.
+ * All tensors are BORROWED device memory, row-major; p, q have W's dtype, m, v are fp32, r x r, dense.
+ * The calls enqueue on hip_stream and return; errors as for the other calls (galore_last_error(NULL)). */
+typedef struct {
+  galore_tensor p;   /* m x r */
+  galore_tensor q;   /* n x r */
+  galore_tensor m;   /* r x r, fp32, ld == r */
+  galore_tensor v;   /* r x r, fp32, ld == r */
+} galore_two_sided_state;
+
+/* Bytes of device workspace (256-byte aligned) the two calls below need for a weight of W's shape
+ * and dtype; uses hp->rank. */
+galore_status galore_two_sided_workspace_bytes(const galore_hparams* hp, const galore_tensor* W, size_t* out_bytes);
+
+/* One step: R = P^T G Q, Adam on R with bias correction for step k = t + 1, weight update in the
+ * epilogue of the last product (the m x n update is never stored).  With hp->auto_refresh and
+ * t a multiple of hp->update_gap, the projectors are first recomputed from this G (the refresh test
+ * of Algorithm 2).  Uses hp->scale, beta1, beta2, eps, weight_decay. */
+galore_status galore_two_sided_step(const galore_hparams* hp, const galore_tensor* W, const galore_tensor* G,
+                                    const galore_two_sided_state* S, int64_t t, float lr,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Both projectors from G (SVD equation of Sec. 3.3).  The projector of the short side is the one
+ * galore_refresh_subspace computes (canonical signs); each vector of the other side is the one the
+ * decomposition pairs with it, v_i = G^T u_i / s_i (u_i = G v_i / s_i), formed as a unit-length row
+ * of P^T G (column of G Q).  Uses hp->rank, refresh_iters, seed.  M, V are not touched. */
+galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_tensor* G,
+                                       const galore_two_sided_state* S,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- Instrumentation (measurement only, no part of the method) ----
  * Between galore_profile_start and galore_profile_stop every kernel group that galore_step or
  * galore_refresh_subspace enqueues is bracketed by a pair of HIP events on the context's

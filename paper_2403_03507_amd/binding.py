@@ -29,6 +29,10 @@ class galore_state(ctypes.Structure):
                 ("m_scale", galore_tensor), ("v_scale", galore_tensor)]
 
 
+class galore_two_sided_state(ctypes.Structure):
+    _fields_ = [("p", galore_tensor), ("q", galore_tensor), ("m", galore_tensor), ("v", galore_tensor)]
+
+
 class galore_hparams(ctypes.Structure):
     _fields_ = [("rank", ctypes.c_int32), ("update_gap", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -46,7 +50,8 @@ EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "gal
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
-           "galore_set_call_overlap", "galore_join", "galore_get_stream"]
+           "galore_set_call_overlap", "galore_join", "galore_get_stream",
+           "galore_two_sided_workspace_bytes", "galore_two_sided_step", "galore_two_sided_refresh"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
 _lib = None
@@ -82,6 +87,10 @@ def lib():
         L.galore_set_call_overlap.argtypes = [vp, i32]
         L.galore_join.argtypes = [vp]
         L.galore_get_stream.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_void_p)]
+        tsp = ctypes.POINTER(galore_two_sided_state)
+        L.galore_two_sided_workspace_bytes.argtypes = [hp, tp, ctypes.POINTER(ctypes.c_size_t)]
+        L.galore_two_sided_step.argtypes = [hp, tp, tp, tsp, i64, f32, vp, ctypes.c_size_t, vp]
+        L.galore_two_sided_refresh.argtypes = [hp, tp, tsp, vp, ctypes.c_size_t, vp]
         L.galore_profile_start.argtypes = [vp]
         L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
@@ -212,6 +221,48 @@ def galore_profile_stop(ctx):
     cnt = (ctypes.c_int64 * n)()
     _check(lib().galore_profile_stop(ctx, ms, cnt), ctx)
     return {STAGES[i]: (ms[i], cnt[i]) for i in range(n)}
+
+
+def galore_two_sided_workspace_bytes(hp, w_desc):
+    out = ctypes.c_size_t(0)
+    _check(lib().galore_two_sided_workspace_bytes(ctypes.byref(hp), ctypes.byref(w_desc), ctypes.byref(out)))
+    return out.value
+
+
+def galore_two_sided_step(hp, W, G, state, t, lr, workspace):
+    _check(lib().galore_two_sided_step(ctypes.byref(hp), ctypes.byref(desc(W)), ctypes.byref(desc(G)), ctypes.byref(state),
+                                       int(t), lr, workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def galore_two_sided_refresh(hp, G, state, workspace):
+    _check(lib().galore_two_sided_refresh(ctypes.byref(hp), ctypes.byref(desc(G)), ctypes.byref(state),
+                                          workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+class GaLoreTwoSided:
+    """One weight matrix under the two-sided rule (Definition 3.6): owns P, Q, the r x r moments and the
+    workspace (torch memory) and keeps the step count; all arithmetic happens in the library."""
+
+    def __init__(self, weight, rank, device="cuda", **hparams):
+        m, n = weight.shape
+        self.hp = make_hparams(rank, **hparams)
+        self.P = torch.zeros(m, rank, dtype=weight.dtype, device=device)
+        self.Q = torch.zeros(n, rank, dtype=weight.dtype, device=device)
+        self.M = torch.zeros(rank, rank, dtype=torch.float32, device=device)
+        self.V = torch.zeros(rank, rank, dtype=torch.float32, device=device)
+        nbytes = galore_two_sided_workspace_bytes(self.hp, shape_desc(m, n, weight.dtype))
+        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        self.t = 0
+
+    def state(self):
+        return galore_two_sided_state(desc(self.P), desc(self.Q), desc(self.M), desc(self.V))
+
+    def refresh(self, grad):
+        galore_two_sided_refresh(self.hp, grad, self.state(), self.workspace)
+
+    def step(self, weight, grad, lr):
+        galore_two_sided_step(self.hp, weight, grad, self.state(), self.t, lr, self.workspace)
+        self.t += 1
 
 
 class GaLore:

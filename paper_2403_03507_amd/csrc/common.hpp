@@ -111,5 +111,9 @@ hipError_t launch_transpose_group(const TransposeGroup& g, DType dt, hipStream_t
 
 // ---- small utilities -----------------------------------------------------------------------
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
+// dst (rows x cols, leading dimension ldd, dtype dt) <- src (dense fp32), rounded to nearest even
+hipError_t launch_cast_rows(const float* src, void* dst, int rows, int cols, int ldd, DType dt, hipStream_t stream);
+// the same with every row scaled to unit Euclidean length (a zero row stays zero)
+hipError_t launch_normalize_rows(const float* src, void* dst, int rows, int cols, int ldd, DType dt, hipStream_t stream);
 
 }  // namespace galore

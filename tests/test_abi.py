@@ -157,3 +157,42 @@ def test_init_rejects_malformed_8bit_moment_state():
     # 8-bit codes are a moment format only
     wq = [gb.shape_desc(8, 512, gb.GALORE_U8)]
     assert _status(gb.galore_workspace_bytes, hp, wq) == 3
+
+
+def _two_sided_call(hp, w, g, st, ws_ptr, ws_bytes, t=0):
+    L = gb.lib()
+    gb._check(L.galore_two_sided_step(ctypes.byref(hp), ctypes.byref(w) if w is not None else None,
+                                      ctypes.byref(g) if g is not None else None, ctypes.byref(st), t, 1e-3,
+                                      ws_ptr, ws_bytes, None))
+
+
+def test_two_sided_validation_happens_before_any_device_work():
+    hp = _hp(rank=4, auto_refresh=False)
+    m, n, r = 8, 16, 4
+    w = gb.galore_tensor(4096, m, n, n, gb.GALORE_F32)
+    g = gb.galore_tensor(4096, m, n, n, gb.GALORE_F32)
+
+    def state():
+        return gb.galore_two_sided_state(gb.galore_tensor(4096, m, r, r, gb.GALORE_F32), gb.galore_tensor(4096, n, r, r, gb.GALORE_F32),
+                                         gb.galore_tensor(4096, r, r, r, gb.GALORE_F32), gb.galore_tensor(4096, r, r, r, gb.GALORE_F32))
+    need = gb.galore_two_sided_workspace_bytes(hp, gb.shape_desc(m, n, torch.float32))
+    assert need % 256 == 0 and need >= (r * m + 2 * r * n + 2 * r * r + n * r) * 4
+    assert _status(gb.galore_two_sided_workspace_bytes, _hp(rank=9), gb.shape_desc(m, n, torch.float32)) == 4
+    assert _status(_two_sided_call, hp, w, None, state(), 4096, need) == 1                  # G NULL
+    assert _status(_two_sided_call, hp, w, g, state(), 0, need) == 6                         # workspace NULL
+    assert _status(_two_sided_call, hp, w, g, state(), 4096 + 8, need) == 5                  # misaligned
+    assert _status(_two_sided_call, hp, w, g, state(), 4096, need - 256) == 6                # too small
+    assert _status(_two_sided_call, hp, w, g, state(), 4096, need, t=-1) == 1
+    bad = gb.galore_tensor(4096, m, n + 1, n + 1, gb.GALORE_F32)
+    assert _status(_two_sided_call, hp, w, bad, state(), 4096, need) == 2                   # G shape
+    bad = gb.galore_tensor(4096, m, n, n, gb.GALORE_BF16)
+    assert _status(_two_sided_call, hp, w, bad, state(), 4096, need) == 3                   # G dtype
+    s = state(); s.q.rows = m
+    assert _status(_two_sided_call, hp, w, g, s, 4096, need) == 7                            # Q is cols(W) x rank
+    s = state(); s.p.dtype = gb.GALORE_BF16
+    assert _status(_two_sided_call, hp, w, g, s, 4096, need) == 3
+    s = state(); s.m.dtype = gb.GALORE_BF16
+    assert _status(_two_sided_call, hp, w, g, s, 4096, need) == 3                            # moments are fp32
+    s = state(); s.v.cols = r + 1; s.v.ld = r + 1
+    assert _status(_two_sided_call, hp, w, g, s, 4096, need) == 7                            # moments are rank x rank
+    assert _status(_two_sided_call, _hp(rank=9, auto_refresh=False), w, g, state(), 4096, need) == 4
