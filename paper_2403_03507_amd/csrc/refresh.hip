@@ -461,13 +461,17 @@ __global__ __launch_bounds__(1024) void wy_gram_kernel(const RefreshGroup grp, i
   }
 }
 
-// One workgroup of 64 lanes per tensor: S = sum of the slices' shares, then T column by column;
-// lane i owns row i of T in registers (the masked update keeps register indices static).
-__global__ __launch_bounds__(64) void wy_tfactor_kernel(const RefreshGroup grp, int J0, int nb) {
+// One workgroup per tensor: S = sum of the slices' shares (one entry per thread, so the shares arrive in
+// one memory round trip), then the first 32 lanes build T column by column; lane i owns row i of T in
+// registers.
+__global__ __launch_bounds__(1024) void wy_tfactor_kernel(const RefreshGroup grp, int J0, int nb) {
   __shared__ float Sm[kWY * (kWY + 1)];
+  __shared__ float taus[kWY];   // fetched once: a global load inside the column loop would cost its latency 32 times
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int lane = threadIdx.x;
-  for (int e = lane; e < kWY * kWY; e += 64) {
+  if (lane < kWY) taus[lane] = lane < nb ? t.tau[J0 + lane] : 0.f;
+  {
+    const int e = lane;   // 1024 threads, 32 x 32 entries
     float sum = 0.f;
 #pragma unroll
     for (int sl = 0; sl < kWYSlices; ++sl) sum += t.tpart[sl * (kWY * kWY) + e];
@@ -479,15 +483,14 @@ __global__ __launch_bounds__(64) void wy_tfactor_kernel(const RefreshGroup grp, 
     float trow[kWY];
 #pragma unroll
     for (int j = 0; j < kWY; ++j) trow[j] = 0.f;
-#pragma unroll 1
+    // fully unrolled: every register index is static and column j only touches entries l < j
+#pragma unroll
     for (int j = 0; j < kWY; ++j) {
-      const float tau = j < nb ? t.tau[J0 + j] : 0.f;
+      const float tau = taus[j];
       float acc = 0.f;
 #pragma unroll
-      for (int l = 0; l < kWY; ++l) acc += trow[l] * Sm[l * (kWY + 1) + j];  // trow[l] = 0 unless i <= l < j
-      const float val = i == j ? tau : (i < j ? -tau * acc : 0.f);
-#pragma unroll
-      for (int jj = 0; jj < kWY; ++jj) trow[jj] = jj == j ? val : trow[jj];
+      for (int l = 0; l < j; ++l) acc += trow[l] * Sm[l * (kWY + 1) + j];  // trow[l] = 0 unless i <= l
+      trow[j] = i == j ? tau : (i < j ? -tau * acc : 0.f);
     }
     float* out = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
 #pragma unroll
@@ -1200,7 +1203,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
                                  j0, nb, j0 + nb, 0, 0, J0 + nb32);
           }
           hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, grp, J0, nb32);
-          hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(64), 0, stream, grp, J0, nb32);
+          hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(kWY * kWY), 0, stream, grp, J0, nb32);
           const int trailing = r - (J0 + nb32);
           if (trailing > 0) {
             const dim3 grid((trailing + kWY - 1) / kWY, kWYApplySlices, n);
