@@ -299,9 +299,14 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
 // Apply the nb reflectors of panel j0 (stored in Z) to columns col_begin + kSW blockIdx.x + (0..kSW-1)
 // of the target (Z itself while factoring, Q while forming the orthogonal factor), rows >= j0,
 // in forward order (H_nb-1 ... H_0 X: factoring) or reverse order (H_0 ... H_nb-1 X: forming Q).
+// With factor_next (factoring only), workgroup 0 - whose columns are the next panel - goes on to factor
+// them while it still holds them in registers, exactly as householder_panel_kernel would: one launch and
+// one trip of the panel through memory less per panel.
 __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const RefreshGroup grp, int j0, int nb, int col_begin,
-                                                                       int target_is_q, int reverse, int col_end) {
+                                                                       int target_is_q, int reverse, int col_end, int factor_next) {
+  static_assert(kSW == kNB, "the fused factorisation treats a workgroup's columns as one panel");
   __shared__ float red[17 * kSW];
+  __shared__ float bc[kNB + 1];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int k = t.k;
   const float* __restrict__ Zv = t.Z;
@@ -345,6 +350,54 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
       const float tv = tau * v[s][ii];
 #pragma unroll
       for (int c = 0; c < kSW; ++c) x[s][c] -= tv * w[c];
+    }
+  }
+  if (factor_next && blockIdx.x == 0) {
+    // columns c0 .. c0 + nbn - 1 are the next panel; thread tid still owns rows j0 + tid + 1024 s
+    const int nbn = col_end - c0 < kNB ? col_end - c0 : kNB;
+#pragma unroll
+    for (int i = 0; i < kNB; ++i) {
+      if (i >= nbn) break;
+      const int j = c0 + i;
+      float d[kNB];
+#pragma unroll
+      for (int c = 0; c < kNB; ++c) {
+        float a = 0.f;
+        if (c >= i) {
+#pragma unroll
+          for (int s = 0; s < kRPT; ++s)
+            if (j0 + tid + 1024 * s > j) a += x[s][i] * x[s][c];
+        }
+        d[c] = a;
+      }
+      if (tid == j - j0) {  // owner of row j (j - j0 < 2 kNB) publishes that row of the panel
+#pragma unroll
+        for (int c = 0; c < kNB; ++c) bc[c] = x[0][c];
+      }
+      block_sum_vec<kNB>(d, red);  // its barriers also publish bc
+      const float x0 = bc[i];
+      const float sigma = d[i];
+      float tau = 0.f, vs = 0.f;
+      if (sigma != 0.f) {
+        const float beta = -copysignf(sqrtf(x0 * x0 + sigma), x0);
+        tau = (beta - x0) / beta;
+        vs = 1.0f / (x0 - beta);
+      }
+      if (tid == 0) { t.tau[j] = tau; t.vscale[j] = vs; }
+      if (tau != 0.f) {
+#pragma unroll
+        for (int c = 0; c < kNB; ++c) {
+          if (c <= i) continue;
+          const float tw = tau * (bc[c] + vs * d[c]);
+#pragma unroll
+          for (int s = 0; s < kRPT; ++s) {
+            const int row = j0 + tid + 1024 * s;
+            if (row == j) x[s][c] -= tw;
+            else if (row > j) x[s][c] -= tw * vs * x[s][i];
+          }
+        }
+      }
+      __syncthreads();  // bc is rewritten in the next round
     }
   }
 #pragma unroll
@@ -1196,11 +1249,13 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
           const int nb32 = r - J0 < kWY ? r - J0 : kWY;
           for (int j0 = J0; j0 < J0 + nb32; j0 += kNB) {
             const int nb = J0 + nb32 - j0 < kNB ? J0 + nb32 - j0 : kNB;
-            hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
+            // the first panel of a macro panel has its own launch; the others are factored by workgroup 0
+            // of the previous panel's update, which holds their columns in registers anyway
+            if (j0 == J0) hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
             const int inner = J0 + nb32 - (j0 + nb);
             if (inner > 0)
               hipLaunchKernelGGL(householder_block_apply_kernel, dim3((inner + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
-                                 j0, nb, j0 + nb, 0, 0, J0 + nb32);
+                                 j0, nb, j0 + nb, 0, 0, J0 + nb32, 1);
           }
           hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, grp, J0, nb32);
           hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(kWY * kWY), 0, stream, grp, J0, nb32);
@@ -1227,7 +1282,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
         const int ncols = r - (j0 + nb);
         if (ncols > 0)
           hipLaunchKernelGGL(householder_block_apply_kernel, dim3((ncols + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
-                             j0, nb, j0 + nb, 0, 0, r);
+                             j0, nb, j0 + nb, 0, 0, r, 0);
       }
       GALORE_RETURN_IF(hipGetLastError());
       hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
@@ -1235,7 +1290,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
       for (int j0 = last; j0 >= 0; j0 -= kNB) {
         const int nb = r - j0 < kNB ? r - j0 : kNB;
         hipLaunchKernelGGL(householder_block_apply_kernel, dim3((r - j0 + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
-                           j0, nb, j0, 1, 1, r);
+                           j0, nb, j0, 1, 1, r, 0);
       }
       GALORE_RETURN_IF(hipGetLastError());
     } else {
