@@ -5,7 +5,7 @@ A "step" is one pass of the whole hot path (project, low-rank Adam, project back
 subspace refresh falls on step 0 and is timed apart) over every GaLore matrix of a synthetic
 LLaMA-7B-shaped stack (32 layers x {4x 4096x4096, 2x 4096x11008, 11008x4096}, bf16 W/G, fp32
 M/V, r = 1024), called one layer at a time in backward order, the way a per-layer weight update
-during back-propagation calls it; consecutive calls overlap on the library's two streams, which
+during back-propagation calls it; consecutive calls overlap on the library's streams, which
 are joined into the caller's stream once per step (galore_join), when the next forward pass
 needs the weights.  Prints ONE JSON line.
 """
@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
+    ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="overlapped calls: calls in flight (library streams used)")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")
@@ -89,9 +90,11 @@ def main():
     del srcs
     torch.cuda.synchronize()
 
-    opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments)
+    # one call's workspace per call in flight: overlapped calls then overlap their subspace refreshes as well
+    opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
+                    workspace_factor=args.in_flight)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
-    overlap = not args.join_every_call and args.lanes > 1
+    overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
     gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
@@ -110,11 +113,9 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1)
 
-    # step 0: t mod T == 0 for every tensor, so it carries the subspace refresh
-    gb.galore_profile_start(opt.ctx)
+    # step 0: t mod T == 0 for every tensor, so it carries the subspace refresh (in the default schedule
+    # the refreshes of consecutive calls overlap like the steps do)
     first_ms = timed(lambda: one_step(0))
-    prof0 = gb.galore_profile_stop(opt.ctx)
-    refresh_ms = prof0["refresh"][0]
     for w in range(1, max(args.warmup, 1)):
         one_step(w)
     K = args.steps
@@ -131,6 +132,13 @@ def main():
     gb.galore_profile_start(opt.ctx)
     prof_total_ms = timed(lambda: [one_step(base + 2 * K + i) for i in range(K)])
     prof = gb.galore_profile_stop(opt.ctx)
+    # one more refresh step, serial and bracketed by events: the refresh of one call on its own
+    for i in range(len(W)):
+        opt.set_step(i, 0)
+    gb.galore_profile_start(opt.ctx)
+    one_step(0)
+    torch.cuda.synchronize()
+    refresh_serial_ms = gb.galore_profile_stop(opt.ctx)["refresh"][0]
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     gb.galore_set_call_overlap(opt.ctx, overlap)
 
@@ -199,14 +207,16 @@ def main():
                                "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype,
                                                                                    "fp32" if args.moments == "f32" else "8-bit", r, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
-                   "schedule": "consecutive calls overlap on two library streams, one join per step" if overlap else
+                   "schedule": "consecutive calls overlap on %d library streams, one join per step" % overlap if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "stages": per_stage,
         "ms_per_step_serial": serial_ms,
         "ms_per_step_serial_with_events": prof_total_ms / K,
-        "refresh": {"ms_total_step0": refresh_ms, "ms_per_layer_set": refresh_ms / L, "step0_ms": first_ms},
+        # step 0 = refresh + step in the timed schedule; the serial figure is the sum of the refresh launches alone
+        "refresh": {"step0_ms": first_ms, "ms_per_layer_set": (first_ms - ms_per_step) / L,
+                    "ms_per_layer_set_serial": refresh_serial_ms / L},
         "step_flops": 4.0 * sum(m * n for m, n in shapes) * r * L,
         "step_tflops": 4.0 * sum(m * n for m, n in shapes) * r * L / (ms_per_step * 1e-3) / 1e12,
     }

@@ -159,26 +159,30 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
  * context's stream.  Results do not depend on the setting. */
 galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
 
-/* Overlap of consecutive calls (off by default).  When on, every galore_step call runs as ONE
- * chain (all its tensors grouped in each kernel launch) on one of two library-owned streams of
- * default priority, alternating from call to call.  The stream waits for the context's stream at
- * the start of the call (so gradients produced there are ready) but is NOT joined back into it at
- * the end: the bandwidth-bound Adam pass and the GEMM tails of one call overlap with the GEMMs
- * of the next one (per-layer calls of one optimizer step).  Call c uses half (c mod 2) of the
- * workspace, so it runs this way only if its tensors fit half of it; otherwise, and whenever a
- * tensor of the call is still in flight on the other stream or a subspace refresh is due, the
- * library joins first and proceeds as without overlap.  The caller must call galore_join()
- * before work on the context's stream (or the host) reads or writes W, M, V or the projectors of
- * tensors passed since the last join, and must not overwrite their G buffers before it.
- * galore_set_concurrency does not apply to overlapped calls.  Results do not depend on the
- * setting.  Turning it off joins. */
+/* Overlap of consecutive calls (off by default; on = 0 off, 1 or 2 = two calls in flight, 3 =
+ * three).  When on, every galore_step call runs as ONE chain (all its tensors grouped in each
+ * kernel launch) on one of `on` library-owned streams of default priority, taking turns from call
+ * to call.  The stream waits for the context's stream at the start of the call (so gradients
+ * produced there are ready) but is NOT joined back into it at the end: the bandwidth-bound Adam
+ * pass and the GEMM tails of one call overlap with the GEMMs of the next one (per-layer calls of
+ * one optimizer step), and so do the many short launches of the subspace refreshes of consecutive
+ * calls.  Call c uses share (c mod on) of the workspace, one of `on` equal parts, so its step runs
+ * this way only if the transients of its tensors fit one share, and a refresh that is due only if
+ * its working set fits one share (a workspace of `on` times galore_workspace_bytes always
+ * suffices); otherwise, and whenever a tensor of the call is still in flight on another
+ * stream, the library joins first and proceeds as without overlap.  The caller must call
+ * galore_join() before work on the context's stream (or the host) reads or writes W, M, V or the
+ * projectors of tensors passed since the last join, and must not overwrite their G buffers before
+ * it.  galore_set_concurrency does not apply to overlapped calls.  Results do not depend on the
+ * setting.  Turning it off, or changing the number of calls in flight, joins.
+ * Errors: GALORE_ERR_INVALID_ARG for on outside 0 ... 3. */
 galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on);
 
 /* Make the context's stream wait for everything the library streams hold (no host wait).
  * A no-op when nothing is pending. */
 galore_status galore_join(galore_ctx* ctx);
 
-/* The two library-owned HIP streams (which = 0, 1), for callers whose allocator must know which
+/* The three library-owned HIP streams (which = 0, 1, 2), for callers whose allocator must know which
  * streams still read a gradient buffer it is about to recycle (with overlapped calls the library
  * reads G on these streams after galore_step has returned).  The streams stay owned by the
  * library and die with the context. */

@@ -197,7 +197,7 @@ def galore_set_concurrency(ctx, lanes):
 
 
 def galore_set_call_overlap(ctx, on):
-    _check(lib().galore_set_call_overlap(ctx, 1 if on else 0), ctx)
+    _check(lib().galore_set_call_overlap(ctx, int(on)), ctx)  # False/0 off, True/1/2 two calls in flight, 3 three
 
 
 def galore_join(ctx):
@@ -269,8 +269,10 @@ class GaLore:
     """Owns the device memory of a tensor list's optimizer state (allocated with torch) and a
     library context bound to torch's current stream.  All arithmetic happens in the library."""
 
-    def __init__(self, weights, rank, device="cuda", workspace_bytes=None, moments="f32", **hparams):
-        """moments: "f32" (Algorithm 2 as printed) or "q8" (8-bit codes + one fp32 scale per 256 elements)."""
+    def __init__(self, weights, rank, device="cuda", workspace_bytes=None, moments="f32", workspace_factor=1, **hparams):
+        """moments: "f32" (Algorithm 2 as printed) or "q8" (8-bit codes + one fp32 scale per 256 elements).
+        workspace_factor: multiples of galore_workspace_bytes to allocate when workspace_bytes is not given;
+        with as many multiples as calls in flight, overlapped calls (set_call_overlap) also overlap their subspace refreshes."""
         assert moments in ("f32", "q8")
         self.moments = moments
         self.hp = make_hparams(rank, **hparams)
@@ -291,7 +293,7 @@ class GaLore:
                 self.V_scale.append(torch.empty(shape[0], shape[1] // 256, dtype=torch.float32, device=device))
         w_descs = [shape_desc(m, n, dt) for (m, n), dt in zip(self.shapes, self.dtypes)]
         if workspace_bytes is None:
-            workspace_bytes = galore_workspace_bytes(self.hp, w_descs)
+            workspace_bytes = int(workspace_factor) * galore_workspace_bytes(self.hp, w_descs)
         self.workspace = torch.empty(max(workspace_bytes, 256), dtype=torch.uint8, device=device)
         none = galore_tensor(None, 0, 0, 0, GALORE_F32)
         states = [galore_state(desc(p), desc(m), desc(v), desc(pt),
@@ -310,8 +312,8 @@ class GaLore:
         galore_join(self.ctx)
 
     def library_streams(self):
-        """The library's two streams as torch streams (for Tensor.record_stream)."""
-        return [torch.cuda.ExternalStream(galore_get_stream(self.ctx, i)) for i in range(2)]
+        """The library's three streams as torch streams (for Tensor.record_stream)."""
+        return [torch.cuda.ExternalStream(galore_get_stream(self.ctx, i)) for i in range(3)]
 
     def refresh(self, grads, first=0):
         galore_refresh_subspace(self.ctx, [desc(g) for g in grads], first, len(grads))

@@ -40,6 +40,8 @@ struct ProfRecord {
   int stage;
 };
 
+constexpr int kLibStreams = 3;  // library-owned streams per context
+
 struct galore_ctx {
   galore_hparams hp;
   std::vector<TensorInfo> tensors;
@@ -54,16 +56,17 @@ struct galore_ctx {
   // `lanes` independent chains (project -> Adam -> project back) that run on the caller's
   // stream and on library-owned streams (default priority), forked and joined with events.
   int lanes = 3;
-  hipStream_t aux[2] = {nullptr, nullptr};
+  hipStream_t aux[kLibStreams] = {};
   hipEvent_t fork_ev = nullptr;
-  hipEvent_t join_ev[2] = {nullptr, nullptr};
+  hipEvent_t join_ev[kLibStreams] = {};
   // Overlap of consecutive calls (galore_set_call_overlap): every call (chunk) runs as ONE chain on
-  // one of the two library streams, alternating, and the context's stream is not made to wait
-  // until galore_join.  The chunk on stream h uses half h of the workspace, so stream order
-  // alone protects the workspace.
+  // one of the first `slots` library streams, taking turns, and the context's stream is not made to
+  // wait until galore_join.  The chunk on stream h uses share h of the workspace (one of `slots`
+  // equal parts), so stream order alone protects the workspace.
   bool overlap_calls = false;
+  int slots = 2;
   bool unjoined = false;          // library streams hold work the context's stream has not waited for
-  int parity = 0;
+  int parity = 0;                 // the library stream (and workspace share) the next overlapped call takes
   std::vector<char> in_flight;    // per tensor: 0, or 1 + the library stream its last chain ran on
 };
 
@@ -282,7 +285,7 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
 // Make the context's stream wait for everything the library streams hold.
 galore_status join_all(galore_ctx* ctx) {
   galore_status st = GALORE_OK;
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < kLibStreams; ++c) {
     if (!ctx->aux[c] || !ctx->join_ev[c]) continue;
     hipError_t e = hipEventRecord(ctx->join_ev[c], ctx->aux[c]);
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_ev[c], 0);
@@ -293,7 +296,13 @@ galore_status join_all(galore_ctx* ctx) {
   return st;
 }
 
-size_t workspace_half(const galore_ctx* ctx) { return (ctx->ws_bytes / 2) & ~(size_t)255; }
+// the part of the workspace one overlapped call may use
+size_t workspace_share(const galore_ctx* ctx) { return (ctx->ws_bytes / (size_t)ctx->slots) & ~(size_t)255; }
+bool library_streams_ready(const galore_ctx* ctx) {
+  for (int c = 0; c < kLibStreams; ++c)
+    if (!ctx->aux[c] || !ctx->join_ev[c]) return false;
+  return ctx->fork_ev != nullptr;
+}
 
 // One chunk of the step: carve the workspace, split the tensors into chains of similar cost and
 // run the chains concurrently.  Chains touch disjoint tensors and disjoint workspace regions.
@@ -304,7 +313,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
     const TensorInfo& ti = ctx->tensors[it.tensor];
     need += align_up((size_t)r * ti.ldim * 4) + align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
   }
-  const bool overlap = ctx->overlap_calls && ctx->aux[0] && ctx->aux[1] && ctx->fork_ev && need <= workspace_half(ctx);
+  const bool overlap = ctx->overlap_calls && library_streams_ready(ctx) && need <= workspace_share(ctx);
   if (ctx->unjoined) {
     // Order everything first when this chunk cannot run on a library stream, or when one of its
     // tensors is still in flight on the OTHER library stream.
@@ -315,7 +324,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
       if (s) return s;
     }
   }
-  size_t off = overlap ? (size_t)ctx->parity * workspace_half(ctx) : 0;
+  size_t off = overlap ? (size_t)ctx->parity * workspace_share(ctx) : 0;
   for (StepItem& it : items) {
     const TensorInfo& ti = ctx->tensors[it.tensor];
     it.R = reinterpret_cast<float*>(ctx->ws + off);
@@ -331,12 +340,12 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
     const galore_status st = run_chain(ctx, items, lr, ctx->aux[h]);
     for (const StepItem& it : items) ctx->in_flight[it.tensor] = (char)(1 + h);
     ctx->unjoined = true;
-    ctx->parity ^= 1;
+    ctx->parity = (ctx->parity + 1) % ctx->slots;
     if (st != GALORE_OK) (void)join_all(ctx);  // keep the context's stream ordered after a failed launch
     return st;
   }
   int lanes = ctx->lanes;
-  if (lanes > 1 && (!ctx->aux[0] || !ctx->aux[1] || !ctx->fork_ev)) lanes = 1;
+  if (lanes > 1 && !library_streams_ready(ctx)) lanes = 1;
   if ((int)items.size() < 2) lanes = 1;
   if (lanes <= 1) return run_chain(ctx, items, lr, ctx->stream);
 
@@ -382,8 +391,10 @@ galore_status check_step_tensor(galore_ctx* ctx, const TensorInfo& ti, const gal
   return GALORE_OK;
 }
 
-galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first, const std::vector<int>& local) {
-  // local: indices i (relative to `first`) of tensors to refresh, in order.
+galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first, const std::vector<int>& local,
+                          hipStream_t stream, unsigned char* ws, size_t ws_bytes) {
+  // local: indices i (relative to `first`) of tensors to refresh, in order; [ws, ws + ws_bytes) is the
+  // part of the workspace this refresh may use, `stream` the stream it runs on.
   size_t pos = 0;
   while (pos < local.size()) {
     std::vector<RefreshItem> chunk;
@@ -393,21 +404,21 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
       const int i = local[pos];
       TensorInfo& ti = ctx->tensors[first + i];
       const size_t need = refresh_workspace_bytes(ti.kdim, ctx->hp.rank);
-      if (!chunk.empty() && used + need > ctx->ws_bytes) break;
+      if (!chunk.empty() && used + need > ws_bytes) break;
       RefreshItem it{};
       it.G = G[i].data; it.ldg = G[i].ld; it.rows = ti.rows; it.cols = ti.cols;
       it.dt = ti.dt;
       it.proj = ti.st.proj.data; it.ldp = ti.st.proj.ld;
       it.proj_t = ti.st.proj_t.data; it.ldpt = ti.st.proj_t.ld;
-      it.ws = ctx->ws + used;
+      it.ws = ws + used;
       it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
       chunk.push_back(it);
       chunk_tensors.push_back(first + i);
       used += need;
       ++pos;
     }
-    ProfScope prof(ctx, GALORE_STAGE_REFRESH, true);
-    hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, ctx->stream);
+    ProfScope prof(ctx, GALORE_STAGE_REFRESH, true, stream);
+    hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
     for (int idx : chunk_tensors) ctx->tensors[idx].proj_t_valid = true;  // the refresh writes proj and proj_t
   }
@@ -535,7 +546,7 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
   ctx->in_flight.assign(ctx->tensors.size(), 0);
   {
     hipError_t e = hipSuccess;
-    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+    for (int i = 0; i < kLibStreams && e == hipSuccess; ++i) {
       e = hipStreamCreateWithFlags(&ctx->aux[i], hipStreamNonBlocking);
       if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->join_ev[i], hipEventDisableTiming);
     }
@@ -585,16 +596,35 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
     for (int i = 0; i < count; ++i)
       if (ctx->tensors[first + i].t % ctx->hp.update_gap == 0) due.push_back(i);
     if (!due.empty()) {
-      if (ctx->unjoined) {  // the refresh runs on the context's stream and uses the whole workspace
+      size_t rneed = 0;
+      for (int i : due) rneed += refresh_workspace_bytes(ctx->tensors[first + i].kdim, ctx->hp.rank);
+      const int h = ctx->parity;
+      // With overlapping calls the refresh runs where this call's step will run: on library stream h,
+      // in share h of the workspace (the step's transients follow there on the same stream), if it fits.
+      const bool on_library_stream = ctx->overlap_calls && library_streams_ready(ctx) &&
+                                     (int)due.size() <= kMaxGroup && rneed <= workspace_share(ctx);
+      bool clash = !on_library_stream;  // otherwise: the context's stream and the whole workspace
+      for (int i : due) clash = clash || (ctx->in_flight[first + i] != 0 && ctx->in_flight[first + i] != 1 + h);
+      if (ctx->unjoined && clash) {
         galore_status s = join_all(ctx);
         if (s) return s;
       }
-      galore_status s = run_refresh(ctx, G, first, due);
-      if (s) return s;
+      if (on_library_stream) {
+        hipError_t e = hipEventRecord(ctx->fork_ev, ctx->stream);  // the gradients are ready on the context's stream
+        if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux[h], ctx->fork_ev, 0);
+        if (e != hipSuccess) return hip_fail(ctx, e, "forking streams");
+        for (int i : due) ctx->in_flight[first + i] = (char)(1 + h);
+        ctx->unjoined = true;
+        galore_status s = run_refresh(ctx, G, first, due, ctx->aux[h], ctx->ws + (size_t)h * workspace_share(ctx), workspace_share(ctx));
+        if (s) { (void)join_all(ctx); return s; }
+      } else {
+        galore_status s = run_refresh(ctx, G, first, due, ctx->stream, ctx->ws, ctx->ws_bytes);
+        if (s) return s;
+      }
     }
   }
-  // with overlapping calls a chunk has to fit half of the workspace
-  const size_t limit = ctx->overlap_calls ? workspace_half(ctx) : ctx->ws_bytes;
+  // with overlapping calls a chunk has to fit one call's share of the workspace
+  const size_t limit = ctx->overlap_calls ? workspace_share(ctx) : ctx->ws_bytes;
   int pos = 0;
   while (pos < count) {
     std::vector<StepItem> items;
@@ -631,7 +661,7 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
     galore_status s = join_all(ctx);
     if (s) return s;
   }
-  return run_refresh(ctx, G, first, all);
+  return run_refresh(ctx, G, first, all, ctx->stream, ctx->ws, ctx->ws_bytes);
 }
 
 galore_status galore_get_step(const galore_ctx* ctx, int32_t tensor, int64_t* t) {
@@ -658,7 +688,7 @@ void galore_destroy(galore_ctx* ctx) {
   if (!ctx) return;
   for (ProfRecord& r : ctx->records) { (void)hipEventDestroy(r.begin); (void)hipEventDestroy(r.end); }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < kLibStreams; ++i) {
     if (ctx->aux[i]) { (void)hipStreamSynchronize(ctx->aux[i]); (void)hipStreamDestroy(ctx->aux[i]); }
     if (ctx->join_ev[i]) (void)hipEventDestroy(ctx->join_ev[i]);
   }
@@ -675,8 +705,15 @@ galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes) {
 
 galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on) {
   if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  if (on < 0 || on > kLibStreams) return fail(ctx, GALORE_ERR_INVALID_ARG, "on must be 0 ... %d", kLibStreams);
+  const int slots = on <= 2 ? 2 : on;
+  // turning it off, or changing how the workspace is divided, orders everything first
+  if (ctx->unjoined && (on == 0 || slots != ctx->slots)) {
+    galore_status s = join_all(ctx);
+    if (s) return s;
+  }
   ctx->overlap_calls = on != 0;
-  if (!ctx->overlap_calls && ctx->unjoined) return join_all(ctx);
+  if (slots != ctx->slots) { ctx->slots = slots; ctx->parity = 0; }
   return GALORE_OK;
 }
 
@@ -688,7 +725,7 @@ galore_status galore_join(galore_ctx* ctx) {
 
 galore_status galore_get_stream(const galore_ctx* ctx, int32_t which, void** out_stream) {
   if (!ctx || !out_stream) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx or out_stream is NULL");
-  if (which < 0 || which > 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "which must be 0 or 1");
+  if (which < 0 || which >= kLibStreams) return fail(nullptr, GALORE_ERR_INVALID_ARG, "which must be 0 ... %d", kLibStreams - 1);
   *out_stream = ctx->aux[which];
   return GALORE_OK;
 }

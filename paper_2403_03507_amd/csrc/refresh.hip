@@ -65,6 +65,11 @@ struct RefreshTensor {
   uint64_t seed;
 };
 
+// The kernels of the long launch sequences (QR panels, Jacobi rounds: about two thousand launches per
+// refresh) read this table from device memory through a pointer; the few one-off kernels take it by
+// value.  By value every launch would put 2.3 KB into the runtime's kernel-argument ring, whose few MB
+// then hold only some hundred launches: the host thread ends up waiting for the GPU launch by launch
+// for the whole refresh instead of running ahead of it.
 struct RefreshGroup {
   int32_t count;
   int32_t r;
@@ -72,7 +77,7 @@ struct RefreshGroup {
 };
 
 struct Layout {
-  size_t C, Q, Z, Bw, Jt, S, tau, vscale, vclean, tmat, tpart, wpart, lambda, order, sweep_flag, total;
+  size_t C, Q, Z, Bw, Jt, S, tau, vscale, vclean, tmat, tpart, wpart, lambda, order, sweep_flag, group, total;
 };
 
 Layout layout_for(int64_t k, int64_t r) {
@@ -94,8 +99,17 @@ Layout layout_for(int64_t k, int64_t r) {
   L.lambda = take((size_t)r * 4);
   L.order = take((size_t)r * 4);
   L.sweep_flag = take((size_t)(kJacobiSweeps + 1) * 4);
+  L.group = take(sizeof(RefreshGroup));  // the descriptor table of the group this tensor leads
   L.total = off;
   return L;
+}
+
+// Copy the descriptor table into device memory (one launch per refresh).
+__global__ __launch_bounds__(256) void upload_group_kernel(const RefreshGroup grp, RefreshGroup* dst) {
+  static_assert(sizeof(RefreshGroup) % 4 == 0, "copied as 32-bit words");
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(&grp);
+  uint32_t* out = reinterpret_cast<uint32_t*>(dst);
+  for (int i = threadIdx.x; i < (int)(sizeof(RefreshGroup) / 4); i += blockDim.x) out[i] = src[i];
 }
 
 // ---- counter-based Gaussian start block ----------------------------------------------------
@@ -158,8 +172,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // COMPUTE: derive tau_j and vscale_j from column j first (factoring; target == Z, col_begin = j + 1)
 // and let block 0 publish them; otherwise read them (forming Q).
 template <bool COMPUTE>
-__global__ __launch_bounds__(1024) void householder_strip_kernel(const RefreshGroup grp, int j, int col_begin,
+__global__ __launch_bounds__(1024) void householder_strip_kernel(const RefreshGroup* __restrict__ gp, int j, int col_begin,
                                                                  int target_is_q) {
+  const RefreshGroup& grp = *gp;
   __shared__ float red1[16];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r, k = t.k;
@@ -226,7 +241,8 @@ __device__ __forceinline__ void block_sum_vec(float (&v)[NV], float* red) {
 
 // Factor columns [j0, j0 + nb) of Z below row j0: LAPACK-style reflectors, column j keeps the
 // unscaled vector below its diagonal, tau_j and the scale 1 / (x0 - beta) go to side arrays.
-__global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGroup grp, int j0, int nb) {
+__global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGroup* __restrict__ gp, int j0, int nb) {
+  const RefreshGroup& grp = *gp;
   __shared__ float red[17 * kNB];
   __shared__ float bc[kNB + 1];
   const RefreshTensor& t = grp.t[blockIdx.y];
@@ -302,8 +318,9 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
 // With factor_next (factoring only), workgroup 0 - whose columns are the next panel - goes on to factor
 // them while it still holds them in registers, exactly as householder_panel_kernel would: one launch and
 // one trip of the panel through memory less per panel.
-__global__ __launch_bounds__(1024) void householder_block_apply_kernel(const RefreshGroup grp, int j0, int nb, int col_begin,
+__global__ __launch_bounds__(1024) void householder_block_apply_kernel(const RefreshGroup* __restrict__ gp, int j0, int nb, int col_begin,
                                                                        int target_is_q, int reverse, int col_end, int factor_next) {
+  const RefreshGroup& grp = *gp;
   static_assert(kSW == kNB, "the fused factorisation treats a workgroup's columns as one panel");
   __shared__ float red[17 * kSW];
   __shared__ float bc[kNB + 1];
@@ -467,7 +484,8 @@ constexpr int kWY = 32;
 // vectors into vclean (rows beyond nb are zero) and form this slice's share of S = V^T V on the
 // matrix cores (left in tpart; wy_tfactor_kernel adds the shares).
 constexpr int kWYSlices = 8;
-__global__ __launch_bounds__(1024) void wy_gram_kernel(const RefreshGroup grp, int J0, int nb) {
+__global__ __launch_bounds__(1024) void wy_gram_kernel(const RefreshGroup* __restrict__ gp, int J0, int nb) {
+  const RefreshGroup& grp = *gp;
   __shared__ float stage[16 * 256];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int k = t.k;
@@ -517,7 +535,8 @@ __global__ __launch_bounds__(1024) void wy_gram_kernel(const RefreshGroup grp, i
 // One workgroup per tensor: S = sum of the slices' shares (one entry per thread, so the shares arrive in
 // one memory round trip), then the first 32 lanes build T column by column; lane i owns row i of T in
 // registers.
-__global__ __launch_bounds__(1024) void wy_tfactor_kernel(const RefreshGroup grp, int J0, int nb) {
+__global__ __launch_bounds__(1024) void wy_tfactor_kernel(const RefreshGroup* __restrict__ gp, int J0, int nb) {
+  const RefreshGroup& grp = *gp;
   __shared__ float Sm[kWY * (kWY + 1)];
   __shared__ float taus[kWY];   // fetched once: a global load inside the column loop would cost its latency 32 times
   const RefreshTensor& t = grp.t[blockIdx.y];
@@ -566,8 +585,9 @@ __device__ __forceinline__ void wy_slice(int J0, int k, int s, int& p_begin, int
   p_end = min(k, p_begin + 64 * per);
 }
 
-__global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
+__global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup* __restrict__ gp, int J0, int col_begin, int col_end,
                                                           int target_is_q) {
+  const RefreshGroup& grp = *gp;
   __shared__ float stage[16 * 256];
   const RefreshTensor& t = grp.t[blockIdx.z];
   const int k = t.k;
@@ -601,8 +621,9 @@ __global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup grp
   }
 }
 
-__global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup grp, int J0, int col_begin, int col_end,
+__global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup* __restrict__ gp, int J0, int col_begin, int col_end,
                                                          int target_is_q, int backward) {
+  const RefreshGroup& grp = *gp;
   __shared__ float Wm[kWY * (kWY + 1)];
   __shared__ float Ym[kWY * (kWY + 1)];
   __shared__ float Tf[kWY * (kWY + 1)];
@@ -686,7 +707,8 @@ __global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup grp,
 }
 
 // which 0: Qt <- [I_r 0] (r x k);  which 1: Jt <- I_r and the sweep flags <- 0
-__global__ __launch_bounds__(256) void identity_fill_kernel(const RefreshGroup grp, int which) {
+__global__ __launch_bounds__(256) void identity_fill_kernel(const RefreshGroup* __restrict__ gp, int which) {
+  const RefreshGroup& grp = *gp;
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
   if (which == 1 && blockIdx.x == 0 && threadIdx.x <= kJacobiSweeps) t.sweep_flag[threadIdx.x] = 0;
@@ -701,7 +723,8 @@ __global__ __launch_bounds__(256) void identity_fill_kernel(const RefreshGroup g
 // ---- one-sided Jacobi on the rows of Bw ----------------------------------------------------------
 // Round `round` of a round-robin tournament over n = r (+1 if odd) players: pair s = 0 is
 // (n-1, round); pair s > 0 is ((round + s) mod (n-1), (round - s) mod (n-1)).
-__global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup grp, int round, int n, int sweep) {
+__global__ __launch_bounds__(256) void jacobi_round_kernel(const RefreshGroup* __restrict__ gp, int round, int n, int sweep) {
+  const RefreshGroup& grp = *gp;
   __shared__ float red[3][4];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int r = grp.r;
@@ -763,7 +786,8 @@ constexpr int kJacobiMaxR = 1280;  // longest row the register-resident inner lo
 typedef float jf4 __attribute__((ext_vector_type(4)));
 
 template <int B>  // rows per block (16 or 8); 2B rows are orthogonalised against each other
-__global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshGroup grp, int round, int nplayers, int sweep) {
+__global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshGroup* __restrict__ gp, int round, int nplayers, int sweep) {
+  const RefreshGroup& grp = *gp;
   constexpr int R2 = 2 * B;
   extern __shared__ __align__(16) float jsm[];
   const RefreshTensor& t = grp.t[blockIdx.y];
@@ -938,7 +962,8 @@ __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r
   }
 }
 
-__global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGroup grp, int round, int nplayers, int sweep) {
+__global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGroup* __restrict__ gp, int round, int nplayers, int sweep) {
+  const RefreshGroup& grp = *gp;
   constexpr int B = kGramB, R2 = kGramR2, GP = R2 + 1;
   __shared__ float Gm[2][R2 * GP];
   __shared__ float Rot[R2 * GP];             // Rot[i][k]: new row i = sum_k Rot[i][k] old row k
@@ -1196,6 +1221,14 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     kmax = k > kmax ? k : kmax;
   }
 
+  RefreshGroup* dgrp;
+  {
+    const RefreshItem& lead = items[0];
+    dgrp = reinterpret_cast<RefreshGroup*>(lead.ws + layout_for(lead.rows <= lead.cols ? lead.rows : lead.cols, r).group);
+    hipLaunchKernelGGL(upload_group_kernel, dim3(1), dim3(256), 0, stream, grp, dgrp);
+    GALORE_RETURN_IF(hipGetLastError());
+  }
+
   // Gram matrix of the short side, split by (dtype, orientation).
   for (int dti = 0; dti < 2; ++dti)
     for (int left = 1; left >= 0; --left) {
@@ -1251,45 +1284,45 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
             const int nb = J0 + nb32 - j0 < kNB ? J0 + nb32 - j0 : kNB;
             // the first panel of a macro panel has its own launch; the others are factored by workgroup 0
             // of the previous panel's update, which holds their columns in registers anyway
-            if (j0 == J0) hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
+            if (j0 == J0) hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, dgrp, j0, nb);
             const int inner = J0 + nb32 - (j0 + nb);
             if (inner > 0)
-              hipLaunchKernelGGL(householder_block_apply_kernel, dim3((inner + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+              hipLaunchKernelGGL(householder_block_apply_kernel, dim3((inner + kSW - 1) / kSW, n), dim3(1024), 0, stream, dgrp,
                                  j0, nb, j0 + nb, 0, 0, J0 + nb32, 1);
           }
-          hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, grp, J0, nb32);
-          hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(kWY * kWY), 0, stream, grp, J0, nb32);
+          hipLaunchKernelGGL(wy_gram_kernel, dim3(kWYSlices, n), dim3(1024), 0, stream, dgrp, J0, nb32);
+          hipLaunchKernelGGL(wy_tfactor_kernel, dim3(1, n), dim3(kWY * kWY), 0, stream, dgrp, J0, nb32);
           const int trailing = r - (J0 + nb32);
           if (trailing > 0) {
             const dim3 grid((trailing + kWY - 1) / kWY, kWYApplySlices, n);
-            hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0);
-            hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, grp, J0, J0 + nb32, r, 0, 0);
+            hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0 + nb32, r, 0);
+            hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0 + nb32, r, 0, 0);
           }
         }
         GALORE_RETURN_IF(hipGetLastError());
-        hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+        hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, dgrp, 0);
         for (int J0 = (r - 1) / kWY * kWY; J0 >= 0; J0 -= kWY) {
           const dim3 grid((r - J0 + kWY - 1) / kWY, kWYApplySlices, n);
-          hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, grp, J0, J0, r, 1);
-          hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, grp, J0, J0, r, 1, 1);
+          hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0, r, 1);
+          hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0, r, 1, 1);
         }
         GALORE_RETURN_IF(hipGetLastError());
         continue;
       }
       for (int j0 = 0; j0 < r; j0 += kNB) {
         const int nb = r - j0 < kNB ? r - j0 : kNB;
-        hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, grp, j0, nb);
+        hipLaunchKernelGGL(householder_panel_kernel, dim3(1, n), dim3(1024), 0, stream, dgrp, j0, nb);
         const int ncols = r - (j0 + nb);
         if (ncols > 0)
-          hipLaunchKernelGGL(householder_block_apply_kernel, dim3((ncols + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+          hipLaunchKernelGGL(householder_block_apply_kernel, dim3((ncols + kSW - 1) / kSW, n), dim3(1024), 0, stream, dgrp,
                              j0, nb, j0 + nb, 0, 0, r, 0);
       }
       GALORE_RETURN_IF(hipGetLastError());
-      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, dgrp, 0);
       const int last = (r - 1) / kNB * kNB;
       for (int j0 = last; j0 >= 0; j0 -= kNB) {
         const int nb = r - j0 < kNB ? r - j0 : kNB;
-        hipLaunchKernelGGL(householder_block_apply_kernel, dim3((r - j0 + kSW - 1) / kSW, n), dim3(1024), 0, stream, grp,
+        hipLaunchKernelGGL(householder_block_apply_kernel, dim3((r - j0 + kSW - 1) / kSW, n), dim3(1024), 0, stream, dgrp,
                            j0, nb, j0, 1, 1, r, 0);
       }
       GALORE_RETURN_IF(hipGetLastError());
@@ -1298,13 +1331,13 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
       for (int j = 0; j < r; ++j) {
         const int ncols = r - (j + 1);
         const dim3 grid(ncols > 0 ? (ncols + 31) / 32 : 1, n);
-        hipLaunchKernelGGL(householder_strip_kernel<true>, grid, dim3(1024), 0, stream, grp, j, j + 1, 0);
+        hipLaunchKernelGGL(householder_strip_kernel<true>, grid, dim3(1024), 0, stream, dgrp, j, j + 1, 0);
       }
       GALORE_RETURN_IF(hipGetLastError());
-      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, grp, 0);
+      hipLaunchKernelGGL(identity_fill_kernel, fill_grid, dim3(256), 0, stream, dgrp, 0);
       for (int j = r - 1; j >= 0; --j) {
         const dim3 grid((r - j + 31) / 32, n);
-        hipLaunchKernelGGL(householder_strip_kernel<false>, grid, dim3(1024), 0, stream, grp, j, j, 1);
+        hipLaunchKernelGGL(householder_strip_kernel<false>, grid, dim3(1024), 0, stream, dgrp, j, j, 1);
       }
       GALORE_RETURN_IF(hipGetLastError());
     }
@@ -1313,7 +1346,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
   // Rayleigh-Ritz
   GALORE_RETURN_IF(gemm_f32(0));
   GALORE_RETURN_IF(gemm_f32(1));
-  hipLaunchKernelGGL(identity_fill_kernel, dim3(blocks_for((int64_t)r * r, 256 * 8, 1024), n), dim3(256), 0, stream, grp, 1);
+  hipLaunchKernelGGL(identity_fill_kernel, dim3(blocks_for((int64_t)r * r, 256 * 8, 1024), n), dim3(256), 0, stream, dgrp, 1);
   // rows per block so that two blocks of whole rows (plus the 2b x 2b rotation product) fit in LDS
   int jb = 0;
   for (int cand : {16, 8})
@@ -1336,16 +1369,16 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
         if (use_gram)
-          hipLaunchKernelGGL(jacobi_gram_round_kernel, dim3(players / 2, n), dim3(1024), 0, stream, grp, round, players, sweep);
+          hipLaunchKernelGGL(jacobi_gram_round_kernel, dim3(players / 2, n), dim3(1024), 0, stream, dgrp, round, players, sweep);
         else if (jb == 16)
-          hipLaunchKernelGGL(jacobi_block_round_kernel<16>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
+          hipLaunchKernelGGL(jacobi_block_round_kernel<16>, dim3(players / 2, n), dim3(1024), smem, stream, dgrp, round, players, sweep);
         else
-          hipLaunchKernelGGL(jacobi_block_round_kernel<8>, dim3(players / 2, n), dim3(1024), smem, stream, grp, round, players, sweep);
+          hipLaunchKernelGGL(jacobi_block_round_kernel<8>, dim3(players / 2, n), dim3(1024), smem, stream, dgrp, round, players, sweep);
   } else if (r > 1) {  // rows too long for LDS: one launch per round of row pairs
     const int players = (r % 2 == 0) ? r : r + 1;
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
-        hipLaunchKernelGGL(jacobi_round_kernel, dim3(players / 2, n), dim3(256), 0, stream, grp, round, players, sweep);
+        hipLaunchKernelGGL(jacobi_round_kernel, dim3(players / 2, n), dim3(256), 0, stream, dgrp, round, players, sweep);
   }
   GALORE_RETURN_IF(hipGetLastError());
   hipLaunchKernelGGL(ritz_values_kernel, dim3(r, n), dim3(256), 0, stream, grp);

@@ -17,7 +17,9 @@ from . import binding as gb
 class PerLayerGaLore:
     def __init__(self, layers, rank, lr, overlap_calls=True, **kwargs):
         """layers: list of lists of 2-D parameters (one inner list per transformer block, in the order
-        the library should see them).  kwargs go to `binding.GaLore` (update_gap, scale, moments, ...)."""
+        the library should see them).  overlap_calls: False, True (two calls in flight) or 3 (three; pass
+        workspace_factor=3 too, so that refreshes overlap as well).  kwargs go to `binding.GaLore`
+        (update_gap, scale, moments, workspace_factor, ...)."""
         self.layers = [list(l) for l in layers]
         self.flat = [p for l in self.layers for p in l]
         for p in self.flat:

@@ -199,14 +199,26 @@ def _run_layers(overlap, update_gap, steps=4, workspace_factor=2, repeat_layer=F
     return out
 
 
-@pytest.mark.parametrize("update_gap", [1000, 2])
-def test_overlapped_calls_match_joined_calls_bitwise(update_gap):
-    # Overlapping consecutive calls only changes stream placement and which workspace half a call
-    # uses; a refresh falling due in the middle (update_gap = 2) forces a join inside the library.
+@pytest.mark.parametrize("update_gap,workspace_factor,in_flight", [(1000, 2, 2), (2, 2, 2), (2, 1, 2), (2, 3, 3), (1000, 3, 3), (2, 1, 3)])
+def test_overlapped_calls_match_joined_calls_bitwise(update_gap, workspace_factor, in_flight):
+    # Overlapping consecutive calls only changes stream placement and which share of the workspace a
+    # call uses.  A refresh falling due (step 0; with update_gap = 2 also in the middle) runs on the
+    # call's library stream when it fits one share (factor = calls in flight) and forces a join inside
+    # the library when it does not (factor 1).
     a = _run_layers(False, update_gap)
-    b = _run_layers(True, update_gap)
+    b = _run_layers(in_flight, update_gap, workspace_factor=workspace_factor)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+def test_call_overlap_rejects_more_streams_than_the_library_owns():
+    W = [wl.make_weight(64, 96, 1, "f32").cuda()]
+    opt = gb.GaLore(W, 8)
+    with pytest.raises(gb.GaloreError):
+        opt.set_call_overlap(4)
+    opt.set_call_overlap(3)
+    opt.set_call_overlap(0)
+    opt.close()
 
 
 def test_overlapped_calls_same_tensors_twice_and_small_workspace():
