@@ -107,6 +107,15 @@ typedef struct {
   int32_t auto_refresh;  /* 1: galore_step refreshes the projector itself when t mod T == 0;
                             0: the caller owns the projector contents (writes state.proj or
                                calls galore_refresh_subspace) */
+  int32_t refresh_warm_iters; /* 0: every refresh starts from the seeded Gaussian block and runs
+                            refresh_iters iterations.  > 0 (needs auto_refresh = 1): a tensor whose
+                            projector was written by an earlier refresh of this context starts the
+                            iteration from that projector and runs this many iterations instead
+                            (this build's option, not the paper's, which calls an exact SVD: the
+                            iteration converges to the same top-r vectors from any start of full
+                            rank, and needs fewer rounds when the gradients of consecutive refreshes
+                            span nearby subspaces); galore_set_step makes the tensor's next refresh
+                            a cold one again.  >= 0 */
   uint64_t seed;         /* seed of the Gaussian start block of the first refresh */
 } galore_hparams;
 

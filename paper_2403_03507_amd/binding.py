@@ -37,7 +37,7 @@ class galore_hparams(ctypes.Structure):
     _fields_ = [("rank", ctypes.c_int32), ("update_gap", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
                 ("weight_decay", ctypes.c_float), ("refresh_iters", ctypes.c_int32),
-                ("auto_refresh", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+                ("auto_refresh", ctypes.c_int32), ("refresh_warm_iters", ctypes.c_int32), ("seed", ctypes.c_uint64)]
 
 
 class GaloreError(RuntimeError):
@@ -124,9 +124,9 @@ def _stream():
 
 
 def make_hparams(rank, update_gap=200, scale=0.25, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
-                 refresh_iters=6, auto_refresh=True, seed=0):
+                 refresh_iters=6, auto_refresh=True, seed=0, refresh_warm_iters=0):
     return galore_hparams(rank, update_gap, scale, beta1, beta2, eps, weight_decay, refresh_iters,
-                          1 if auto_refresh else 0, seed)
+                          1 if auto_refresh else 0, refresh_warm_iters, seed)
 
 
 # ---- the C calls, same names -------------------------------------------------------------------

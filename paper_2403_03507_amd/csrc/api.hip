@@ -30,6 +30,7 @@ struct TensorInfo {
   galore_state st;
   int64_t t;
   bool proj_t_valid;  // state.proj_t mirrors state.proj (only trusted when the library owns the projector)
+  bool refreshed;     // the projector in state.proj_t was written by a refresh of this context
   bool q8;            // moments stored as 8-bit codes with block scales
 };
 
@@ -104,6 +105,7 @@ galore_status check_hparams(galore_ctx* ctx, const galore_hparams* hp) {
   if (!(hp->eps >= 0.f) || !std::isfinite(hp->scale) || !(hp->weight_decay >= 0.f))
     return fail(ctx, GALORE_ERR_INVALID_ARG, "eps / scale / weight_decay out of range");
   if (hp->refresh_iters < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_iters %d < 1", hp->refresh_iters);
+  if (hp->refresh_warm_iters < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_warm_iters %d < 0", hp->refresh_warm_iters);
   return GALORE_OK;
 }
 
@@ -395,32 +397,44 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
                           hipStream_t stream, unsigned char* ws, size_t ws_bytes) {
   // local: indices i (relative to `first`) of tensors to refresh, in order; [ws, ws + ws_bytes) is the
   // part of the workspace this refresh may use, `stream` the stream it runs on.
-  size_t pos = 0;
-  while (pos < local.size()) {
-    std::vector<RefreshItem> chunk;
-    std::vector<int> chunk_tensors;
-    size_t used = 0;
-    while (pos < local.size() && (int)chunk.size() < kMaxGroup) {
-      const int i = local[pos];
-      TensorInfo& ti = ctx->tensors[first + i];
-      const size_t need = refresh_workspace_bytes(ti.kdim, ctx->hp.rank);
-      if (!chunk.empty() && used + need > ws_bytes) break;
-      RefreshItem it{};
-      it.G = G[i].data; it.ldg = G[i].ld; it.rows = ti.rows; it.cols = ti.cols;
-      it.dt = ti.dt;
-      it.proj = ti.st.proj.data; it.ldp = ti.st.proj.ld;
-      it.proj_t = ti.st.proj_t.data; it.ldpt = ti.st.proj_t.ld;
-      it.ws = ws + used;
-      it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
-      chunk.push_back(it);
-      chunk_tensors.push_back(first + i);
-      used += need;
-      ++pos;
+  // Tensors that start from their previous projector (see galore_hparams::refresh_warm_iters) run a
+  // different number of iterations than those that start from the Gaussian block: two passes.
+  const bool warm_allowed = ctx->hp.refresh_warm_iters > 0 && ctx->hp.auto_refresh;
+  std::vector<int> lists[2];  // decided before anything runs: a cold refresh marks its tensors refreshed
+  for (int i : local) lists[warm_allowed && ctx->tensors[first + i].refreshed ? 1 : 0].push_back(i);
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool warm = pass == 1;
+    const std::vector<int>& todo = lists[pass];
+    size_t pos = 0;
+    while (pos < todo.size()) {
+      std::vector<RefreshItem> chunk;
+      std::vector<int> chunk_tensors;
+      size_t used = 0;
+      while (pos < todo.size() && (int)chunk.size() < kMaxGroup) {
+        const int i = todo[pos];
+        TensorInfo& ti = ctx->tensors[first + i];
+        const size_t need = refresh_workspace_bytes(ti.kdim, ctx->hp.rank);
+        if (!chunk.empty() && used + need > ws_bytes) break;
+        RefreshItem it{};
+        it.G = G[i].data; it.ldg = G[i].ld; it.rows = ti.rows; it.cols = ti.cols;
+        it.dt = ti.dt;
+        it.proj = ti.st.proj.data; it.ldp = ti.st.proj.ld;
+        it.proj_t = ti.st.proj_t.data; it.ldpt = ti.st.proj_t.ld;
+        it.ws = ws + used;
+        it.seed = ctx->hp.seed + 0x9E3779B97F4A7C15ull * (uint64_t)(first + i + 1);
+        chunk.push_back(it);
+        chunk_tensors.push_back(first + i);
+        used += need;
+        ++pos;
+      }
+      ProfScope prof(ctx, GALORE_STAGE_REFRESH, true, stream);
+      hipError_t e = refresh_group(chunk, ctx->hp.rank, warm ? ctx->hp.refresh_warm_iters : ctx->hp.refresh_iters, warm, stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
+      for (int idx : chunk_tensors) {
+        ctx->tensors[idx].proj_t_valid = true;  // the refresh writes proj and proj_t
+        ctx->tensors[idx].refreshed = true;
+      }
     }
-    ProfScope prof(ctx, GALORE_STAGE_REFRESH, true, stream);
-    hipError_t e = refresh_group(chunk, ctx->hp.rank, ctx->hp.refresh_iters, stream);
-    if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
-    for (int idx : chunk_tensors) ctx->tensors[idx].proj_t_valid = true;  // the refresh writes proj and proj_t
   }
   return GALORE_OK;
 }
@@ -503,6 +517,7 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
       return fail(nullptr, GALORE_ERR_SHAPE, "S[%d].proj_t must be %lld x %lld", i, (long long)r, (long long)ti.kdim);
     if ((DType)pt.dtype != ti.dt) return fail(nullptr, GALORE_ERR_DTYPE, "S[%d].proj_t dtype must equal the weight dtype", i);
     ti.proj_t_valid = false;
+    ti.refreshed = false;
     const int64_t mr = ti.left ? r : ti.rows, mc = ti.left ? ti.cols : r;
     const galore_tensor* mv[2] = {&S[i].m, &S[i].v};
     ti.q8 = S[i].m.dtype == GALORE_U8 || S[i].v.dtype == GALORE_U8;
@@ -679,6 +694,7 @@ galore_status galore_set_step(galore_ctx* ctx, int32_t tensor, int64_t t) {
   if (t < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "step counter must be >= 0");
   ctx->tensors[tensor].t = t;
   ctx->tensors[tensor].proj_t_valid = false;  // a resumed projector was written by the caller
+  ctx->tensors[tensor].refreshed = false;
   return GALORE_OK;
 }
 
@@ -1085,7 +1101,7 @@ galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_te
   it.ldpt = left ? m : n;
   it.ws = ws + L.rws;
   it.seed = hp->seed + 0x9E3779B97F4A7C15ull;
-  hipError_t e = refresh_group(std::vector<RefreshItem>{it}, r, hp->refresh_iters, stream);
+  hipError_t e = refresh_group(std::vector<RefreshItem>{it}, r, hp->refresh_iters, /*warm_start=*/false, stream);
   if (e != hipSuccess) return hip_fail(nullptr, e, "subspace refresh");
   if (left) {
     // rows of P^T G are s_i v_i^T: unit length makes them Q^T

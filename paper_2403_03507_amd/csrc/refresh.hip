@@ -63,6 +63,8 @@ struct RefreshTensor {
   int32_t k;
   int32_t ldpt;
   uint64_t seed;
+  int32_t proj_is_bf16;  // dtype of proj_t
+  int32_t pad_;
 };
 
 // The kernels of the long launch sequences (QR panels, Jacobi rounds: about two thousand launches per
@@ -129,6 +131,18 @@ __global__ __launch_bounds__(256) void gaussian_fill_kernel(const RefreshGroup g
     const float u1 = (float)((h >> 40) + 1) * (1.0f / 16777216.0f);  // (0, 1]
     const float u2 = (float)(h & 0xFFFFFF) * (1.0f / 16777216.0f);   // [0, 1)
     t.Q[i] = sqrtf(-2.0f * logf(u1)) * cosf(6.28318530718f * u2);
+  }
+}
+
+// Warm start: the iteration block is the previous projector, Qt <- proj_t widened to fp32.
+__global__ __launch_bounds__(256) void projector_start_kernel(const RefreshGroup grp) {
+  const RefreshTensor& t = grp.t[blockIdx.y];
+  const int64_t count = (int64_t)t.k * grp.r;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const int64_t row = i / t.k, col = i - row * t.k;
+    const int64_t src = row * t.ldpt + col;
+    t.Q[i] = t.proj_is_bf16 ? (float)static_cast<const __bf16*>(t.proj_t)[src] : static_cast<const float*>(t.proj_t)[src];
   }
 }
 
@@ -1185,7 +1199,7 @@ inline unsigned blocks_for(int64_t count, int per_block, unsigned cap) {
 
 size_t refresh_workspace_bytes(int64_t kdim, int64_t r) { return layout_for(kdim, r).total; }
 
-hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, hipStream_t stream) {
+hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, hipStream_t stream) {
   const int n = (int)items.size();
   if (n == 0) return hipSuccess;
   if (n > kMaxGroup) return hipErrorInvalidValue;
@@ -1218,6 +1232,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     t.k = (int32_t)k;
     t.ldpt = (int32_t)it.ldpt;
     t.seed = it.seed;
+    t.proj_is_bf16 = it.dt == DType::BF16;
     kmax = k > kmax ? k : kmax;
   }
 
@@ -1248,7 +1263,8 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     }
 
   const dim3 fill_grid(blocks_for(kmax * r, 256 * 8, 1024), n);
-  hipLaunchKernelGGL(gaussian_fill_kernel, fill_grid, dim3(256), 0, stream, grp);
+  if (warm_start) hipLaunchKernelGGL(projector_start_kernel, fill_grid, dim3(256), 0, stream, grp);
+  else hipLaunchKernelGGL(gaussian_fill_kernel, fill_grid, dim3(256), 0, stream, grp);
   GALORE_RETURN_IF(hipGetLastError());
 
   auto gemm_f32 = [&](int which) -> hipError_t {

@@ -22,7 +22,9 @@ struct RefreshItem {
 // matrices, reflector data).
 size_t refresh_workspace_bytes(int64_t kdim, int64_t r);
 
-// Recompute the projectors of up to kMaxGroup tensors with grouped launches on `stream`.
-hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, hipStream_t stream);
+// Recompute the projectors of up to kMaxGroup tensors with grouped launches on `stream`: `iters`
+// rounds of orthogonal iteration from the seeded Gaussian block, or, with `warm_start`, from what
+// proj_t holds on entry (a previous projector of the same tensor; must have full rank).
+hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, hipStream_t stream);
 
 }  // namespace galore

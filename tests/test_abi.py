@@ -59,6 +59,7 @@ def test_workspace_bytes_formula_and_errors():
     assert _status(gb.galore_workspace_bytes, _hp(update_gap=0), w) == 1
     assert _status(gb.galore_workspace_bytes, _hp(beta1=1.0), w) == 1
     assert _status(gb.galore_workspace_bytes, _hp(refresh_iters=0), w) == 1
+    assert _status(gb.galore_workspace_bytes, _hp(refresh_warm_iters=-1), w) == 1
     bad = [gb.galore_tensor(None, 8, 16, 12, 0)]                               # ld < cols
     assert _status(gb.galore_workspace_bytes, _hp(), bad) == 2
     bad = [gb.galore_tensor(None, 8, 16, 16, 7)]                               # unknown dtype

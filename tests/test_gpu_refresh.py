@@ -192,3 +192,72 @@ def test_auto_refresh_cadence_and_update_geometry():
                 P0, _ = orc.projector(to64(G[i]), r)
                 assert _proj_dist(P, P0) <= 1e-3
     opt.close()
+
+
+@pytest.mark.parametrize("shape,dtype", [((256, 688), "f32"), ((688, 256), "f32"), ((256, 688), "bf16")])
+def test_warm_started_refresh_same_subspace(shape, dtype):
+    # refresh_warm_iters: from the second refresh of a tensor on, the iteration starts from the previous
+    # projector.  The source keeps its singular factors and draws fresh noise every step (which
+    # tilts the last singular directions by about sigma_noise / sigma_r ~ 0.2), and a round shrinks the
+    # error by (sigma_{r+1} / sigma_r)^2 <= 1/16: three rounds from the old projector land where the
+    # oracle's exact SVD of the new gradient does, to the gate of the cold refresh.
+    m, n = shape
+    r, T = 48, 2
+    src = wl.GradientSource(m, n, 71, "gapped", dtype=dtype, gap_rank=r)
+    W = [wl.make_weight(m, n, 72, dtype).cuda()]
+    opt = gb.GaLore(W, r, update_gap=T, refresh_iters=8, refresh_warm_iters=3, auto_refresh=True)
+    for step in range(5):
+        G = src.grad(step).cuda()
+        opt.step(W, [G], 1e-3)
+        torch.cuda.synchronize()
+        if step % T == 0:
+            P0, _ = orc.projector(to64(G), r)
+            P = to64(opt.proj[0])
+            if dtype == "f32":
+                assert _proj_dist(P, P0) <= 1e-3, step
+                assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
+            else:
+                assert _proj_dist(P, orc.round_storage(P0, "bf16")) <= 2e-2, step
+            np.testing.assert_array_equal(to64(opt.proj_t[0]), P.T)
+    opt.close()
+
+
+def test_warm_started_refresh_reaches_an_unrelated_subspace():
+    # The start block only sets the speed: with as many rounds as a cold start gets, a projector of a
+    # gradient with other singular factors is reached from the old one just as well.
+    m, n, r, T = 256, 688, 48, 1
+    a = wl.GradientSource(m, n, 73, "gapped", dtype="f32", gap_rank=r)
+    b = wl.GradientSource(m, n, 74, "gapped", dtype="f32", gap_rank=r)
+    W = [wl.make_weight(m, n, 75, "f32").cuda()]
+    opt = gb.GaLore(W, r, update_gap=T, refresh_iters=8, refresh_warm_iters=8, auto_refresh=True)
+    opt.step(W, [a.grad(0).cuda()], 1e-3)
+    Gb = b.grad(1).cuda()
+    opt.step(W, [Gb], 1e-3)
+    torch.cuda.synchronize()
+    P0, _ = orc.projector(to64(Gb), r)
+    assert _proj_dist(to64(opt.proj[0]), P0) <= 1e-3
+    opt.close()
+
+
+def test_warm_start_only_after_an_own_refresh_and_not_after_set_step():
+    # First refresh, explicit refreshes of a caller-owned projector and the refresh after
+    # galore_set_step (a resumed projector is the caller's) are cold: bit-identical to a context
+    # that never warm-starts.
+    m, n, r, T = 256, 688, 32, 2
+    src = wl.GradientSource(m, n, 76, "gapped", dtype="bf16", gap_rank=r)
+
+    def run(warm_iters):
+        W = [wl.make_weight(m, n, 77, "bf16").cuda()]
+        opt = gb.GaLore(W, r, update_gap=T, refresh_iters=4, refresh_warm_iters=warm_iters, auto_refresh=True)
+        opt.step(W, [src.grad(0).cuda()], 1e-3)      # t = 0: cold in both
+        first = opt.proj[0].clone()
+        opt.step(W, [src.grad(1).cuda()], 1e-3)
+        opt.set_step(0, 2)                           # resume at a refresh step
+        opt.step(W, [src.grad(2).cuda()], 1e-3)      # cold again
+        torch.cuda.synchronize()
+        out = (first, opt.proj[0].clone(), W[0].clone())
+        opt.close()
+        return out
+
+    for x, y in zip(run(0), run(1)):
+        assert torch.equal(x, y)
