@@ -115,8 +115,9 @@ def main(argv=None):
     ms_adamw = timed(with_adamw, args.reps)
     del adamw
 
-    drv = PerLayerGaLore([blk.matrices() for blk in blocks], args.rank, 1e-4, overlap_calls=True, update_gap=200,
-                         refresh_iters=4, moments=args.moments)
+    # three calls in flight, and a workspace share for each so that the refreshes of the first step overlap too
+    drv = PerLayerGaLore([blk.matrices() for blk in blocks], args.rank, 1e-4, overlap_calls=3, update_gap=200,
+                         refresh_iters=4, moments=args.moments, workspace_factor=3)
     # the first step refreshes every projector; time it apart
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
