@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
     ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="overlapped calls: calls in flight (library streams used)")
+    ap.add_argument("--layers-per-call", type=int, default=1, choices=[1, 2],
+                    help="layers handed to one galore_step call (the small stacks fill the chip better with 2)")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")
@@ -92,16 +94,21 @@ def main():
 
     # one call's workspace per call in flight: overlapped calls then overlap their subspace refreshes as well
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
-                    workspace_factor=args.in_flight)
+                    workspace_factor=args.in_flight * args.layers_per_call)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
     gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
+    LPC = args.layers_per_call
+    call_w = {l: [x for k in range(l, min(l + LPC, L)) for x in w_descs[k]] for l in range(0, L, LPC)}
+    # the layers of one call take consecutive gradient sets of the pool
+    call_g = [{l: [x for k in range(l, min(l + LPC, L)) for x in g_descs[(s + k - l) % POOL]] for l in range(0, L, LPC)}
+              for s in range(POOL)]
 
     def one_step(step_index):
-        for l in reversed(range(L)):  # backward order, one layer per call
-            gb.galore_step(opt.ctx, w_descs[l], g_descs[(l + step_index) % POOL], n_per_layer * l, n_per_layer, lr)
+        for l in reversed(range(0, L, LPC)):  # backward order, one layer (or LPC layers) per call
+            gb.galore_step(opt.ctx, call_w[l], call_g[(l // LPC + step_index) % POOL][l], n_per_layer * l, len(call_w[l]), lr)
         gb.galore_join(opt.ctx)  # the next forward pass needs the weights: one join per step
 
     def timed(fn):
@@ -147,6 +154,8 @@ def main():
     right = [(m, n) for (m, n) in shapes if m > n]
     flops = {"project_left": sum(2.0 * m * n * r for m, n in left), "project_right": sum(2.0 * m * n * r for m, n in right)}
     flops["back"] = flops["project_left"] + flops["project_right"]
+    if L % LPC == 0:  # a launch covers the tensors of LPC layers
+        flops = {k: v * LPC for k, v in flops.items()}
     sN = 2 if dtype == "bf16" else 4
     if args.moments == "q8":  # read R and two code bytes, write two code bytes and N; four scale accesses per 256 elements
         adam_bytes = sum(r * max(m, n) * (4 + 4 + sN + 16.0 / 256) for m, n in shapes)
@@ -167,7 +176,7 @@ def main():
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
-        roofline["traffic"] = MEASURED_TRAFFIC_BYTES_7B[dominant]
+        roofline["traffic"] = MEASURED_TRAFFIC_BYTES_7B[dominant] * (LPC if L % LPC == 0 else 1)
         roofline["traffic_unit"] = "bytes per launch (L2 fetch + write-back counters; cache hits in the 256 MB MALL are included)"
     per_stage = {}
     for k in gemm_stages:
@@ -203,9 +212,10 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, %s M/V, r=%d, per-layer calls in "
+        "config": {"workload": "%s: %d layers x {4x %dx%d, 2x %dx%d, %dx%d}, %s W/G, %s M/V, r=%d, %s calls in "
                                "backward order, gradient pool of %d layer sets" % (args.config, L, d, d, d, f, f, d, dtype,
-                                                                                   "fp32" if args.moments == "f32" else "8-bit", r, POOL),
+                                                                                   "fp32" if args.moments == "f32" else "8-bit", r,
+                                                                                   "per-layer" if LPC == 1 else "%d-layer" % LPC, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
                    "schedule": "consecutive calls overlap on %d library streams, one join per step" % overlap if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},
