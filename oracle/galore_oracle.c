@@ -23,6 +23,7 @@
  * LAPACK SVD.  Decoupled weight decay is not defined by the paper: its only
  * pin is a hand calculation ("parity unpinned" beyond weight_decay = 0).
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -185,7 +186,12 @@ void oracle_apply_right(double* W, const double* N, const double* Q,
  * Pairs are visited in round-robin tournament order so the disjoint pairs of
  * one round can be rotated in parallel; a sweep is p-1 (or p) rounds covering
  * every pair once.  Iteration stops after a sweep in which every pair already
- * satisfied |b_i.b_j| <= tol |b_i| |b_j|.
+ * satisfied |b_i.b_j| <= tol |b_i| |b_j|.  A row whose norm has fallen to
+ * rounding level of the whole matrix (<= eps max(p,q) |A|_F) belongs to a zero
+ * singular value: its direction is rounding noise that every rotation with a
+ * large row renews, so the relative test can never settle for it and it is
+ * left alone, as an exactly zero row is.  Its singular vector is arbitrary
+ * within the null space; the accumulated J stays orthogonal either way.
  *
  * U_r: p x r row-major.  sigma: p values, descending.  Returns the number of
  * sweeps used, or -1 if max_sweeps was reached without convergence. */
@@ -196,6 +202,11 @@ int oracle_top_left_singular_vectors(const double* A, int64_t p, int64_t q, int6
   double* T = (double*)calloc((size_t)p * p, sizeof(double)); /* J^T */
   memcpy(B, A, (size_t)p * q * sizeof(double));
   for (int64_t i = 0; i < p; ++i) T[i * p + i] = 1.0;
+
+  double fro2 = 0.0;
+  for (int64_t i = 0; i < p * q; ++i) fro2 += A[i] * A[i];
+  const double zero_norm = DBL_EPSILON * (double)(p > q ? p : q) * sqrt(fro2);
+  const double zero2 = zero_norm * zero_norm; /* squared norm at or below which a row counts as zero */
 
   const int64_t np = (p % 2 == 0) ? p : p + 1; /* players; index p is a bye when p is odd */
   int64_t* seat = (int64_t*)malloc((size_t)np * sizeof(int64_t));
@@ -214,7 +225,7 @@ int oracle_top_left_singular_vectors(const double* A, int64_t p, int64_t q, int6
         double* bj = B + j * q;
         double a = 0.0, b = 0.0, c = 0.0;
         for (int64_t k = 0; k < q; ++k) { a += bi[k] * bi[k]; b += bj[k] * bj[k]; c += bi[k] * bj[k]; }
-        if (a == 0.0 || b == 0.0) continue;
+        if (a <= zero2 || b <= zero2) continue;
         if (fabs(c) <= tol * sqrt(a) * sqrt(b)) continue;
         ++rotations;
         const double zeta = (b - a) / (2.0 * c);
@@ -318,7 +329,8 @@ void oracle_apply_two_sided(double* W, const double* P, const double* N, const d
  * of G = U S V^T.  The vectors of the SHORT side come from the Jacobi routine above with their
  * canonical signs (they are the one-sided projector of Algorithm 2); each vector of the long side
  * is the one the decomposition pairs with it, v_i = G^T u_i / s_i (or u_i = G v_i / s_i), so that
- * sum_i s_i u_i v_i^T is the leading part of G.  Needs s_r > 0 (returns -2 otherwise: the partner
+ * sum_i s_i u_i v_i^T is the leading part of G.  Needs s_r > 0, i.e. above the rounding level
+ * eps max(m,n) |G|_F that the Jacobi routine treats as zero (returns -2 otherwise: the partner
  * vector is then not determined by G).  sigma: min(m, n) values.  Returns the sweeps used or -1. */
 int oracle_projector_pair(const double* G, int64_t m, int64_t n, int64_t r,
                           double* P, double* Q, double* sigma, double tol, int max_sweeps) {
@@ -328,6 +340,9 @@ int oracle_projector_pair(const double* G, int64_t m, int64_t n, int64_t r,
   const int64_t l = left ? n : m;
   const int rc = oracle_projector(G, m, n, r, S, sigma, tol, max_sweeps);
   if (rc < 0) return rc;
+  double fro2 = 0.0;
+  for (int64_t i = 0; i < m * n; ++i) fro2 += G[i] * G[i];
+  const double zero_norm = DBL_EPSILON * (double)(m > n ? m : n) * sqrt(fro2);
   for (int64_t c = 0; c < r; ++c) {
     double nrm2 = 0.0;
     for (int64_t j = 0; j < l; ++j) {
@@ -338,7 +353,7 @@ int oracle_projector_pair(const double* G, int64_t m, int64_t n, int64_t r,
       nrm2 += acc * acc;
     }
     const double nrm = sqrt(nrm2);   /* = s_c */
-    if (!(nrm > 0.0)) return -2;
+    if (!(nrm > zero_norm)) return -2;
     for (int64_t j = 0; j < l; ++j) L[j * r + c] /= nrm;
   }
   return rc;

@@ -94,6 +94,37 @@ def test_rank_deficient_input():
     np.testing.assert_allclose(P @ (P.T @ A), A, atol=1e-10)
 
 
+def _degenerate(m, n):
+    rng = np.random.default_rng(6)
+    cases = {"zero": np.zeros((m, n)), "rank2": rng.standard_normal((m, 2)) @ rng.standard_normal((2, n)),
+             "constant": np.ones((m, n))}
+    z = rng.standard_normal((m, n)); z[:, n // 3:] = 0.0
+    cases["zero_columns"] = z          # rank n // 3 < m: a null space on the short side
+    z = rng.standard_normal((m, n)); z[m // 3:] = 0.0
+    cases["zero_rows"] = z
+    z = np.zeros((m, n)); z[3, 7] = 2.0
+    cases["single_entry"] = z
+    return cases
+
+
+@pytest.mark.parametrize("name", ["zero", "rank2", "constant", "zero_columns", "zero_rows", "single_entry"])
+@pytest.mark.parametrize("shape", [(40, 90), (90, 40)])
+def test_null_spaces_against_lapack(name, shape):
+    # Matrices with a null space on the short side: rows that belong to zero singular values hold
+    # rounding noise, which the stopping rule has to leave alone (it used to rotate them for ever).
+    # Singular values against LAPACK's; the vectors of a null space are arbitrary, so for them only
+    # orthonormality and the captured energy (Eckart-Young: sum of the r largest sigma^2) are fixed.
+    m, n = shape
+    G = _degenerate(m, n)[name]
+    r = 12
+    P, sig = orc.projector(G, r)
+    sv = np.linalg.svd(G, compute_uv=False)
+    np.testing.assert_allclose(sig[:len(sv)], sv, atol=1e-12 * max(sv[0], 1.0))
+    assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-12
+    captured = np.linalg.norm(P.T @ G if m <= n else G @ P) ** 2
+    np.testing.assert_allclose(captured, np.sum(sv[:r] ** 2), rtol=1e-10, atol=1e-300)
+
+
 def test_transposed_input_swaps_sides():
     rng = np.random.default_rng(5)
     G = rng.standard_normal((7, 11))
