@@ -1177,7 +1177,10 @@ __global__ __launch_bounds__(256) void finalize_projector_kernel(const RefreshGr
     }
     __syncthreads();
   }
-  const float sgn = z[besti[0]] < 0.f ? -1.f : 1.f;
+  // No entry compares greater than the start value when all of them are NaN (a gradient with
+  // non-finite entries): the index is still the sentinel then, and row 0 serves as well as any.
+  const int pick = besti[0] < k ? besti[0] : 0;
+  const float sgn = z[pick] < 0.f ? -1.f : 1.f;
   T* P = static_cast<T*>(t.proj_t) + (size_t)c * t.ldpt;
   for (int row = threadIdx.x; row < k; row += 256) P[row] = (T)(sgn * z[row]);
 }
