@@ -24,8 +24,10 @@ def dev(a, dtype, device="cuda"):
 
 
 def strided(t, pad):
-    """Copy of t living inside a wider buffer, so its leading dimension is cols + pad."""
-    buf = torch.zeros(t.shape[0], t.shape[1] + pad, dtype=t.dtype, device=t.device)
+    """Copy of t living inside a wider buffer, so its leading dimension is cols + pad.  The pad holds
+    NaN (floating dtypes): a kernel that lets anything beyond a row's end into a result shows up."""
+    fill = float("nan") if t.dtype.is_floating_point else 0
+    buf = torch.full((t.shape[0], t.shape[1] + pad), fill, dtype=t.dtype, device=t.device)
     view = buf[:, : t.shape[1]]
     view.copy_(t)
     return view

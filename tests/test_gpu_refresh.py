@@ -338,3 +338,29 @@ def test_non_finite_and_overflowing_gradients_leave_the_library_usable():
         ref = P0 if dt == torch.float32 else orc.round_storage(P0, "bf16")
         assert _proj_dist(P, ref) <= (1e-3 if dt == torch.float32 else 2e-2)
         opt.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,pad", [((200, 328), 8), ((328, 200), 8), ((200, 328), 3), ((328, 200), 3),
+                                       ((130, 257), 7), ((257, 130), 6)])
+def test_gradient_with_padded_rows(shape, pad, dtype):
+    # G as a view into a wider buffer (row stride = cols + pad): rows that stay 16-byte aligned
+    # (pads 8, 7, 6 for these widths) or only element-aligned (pad 3).  The pad holds NaN, so a
+    # kernel that let anything beyond a row's end into a sum would show.
+    m, n = shape
+    r = 24
+    G = wl.GradientSource(m, n, 91, "gapped", dtype=dtype, gap_rank=r).grad(0)
+    P0, _ = orc.projector(to64(G), r)
+    buf = torch.full((m, n + pad), float("nan"), dtype=G.dtype, device="cuda")
+    Gd = buf[:, :n]
+    Gd.copy_(G)
+    opt = gb.GaLore([G.cuda()], r, refresh_iters=8, auto_refresh=False)
+    opt.refresh([Gd])
+    torch.cuda.synchronize()
+    P = to64(opt.proj[0])
+    assert np.isfinite(P).all()
+    if dtype == "f32":
+        assert _proj_dist(P, P0) <= 1e-3
+    else:
+        assert _proj_dist(P, orc.round_storage(P0, "bf16")) <= 2e-2
+    opt.close()
