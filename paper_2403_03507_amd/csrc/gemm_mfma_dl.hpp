@@ -457,6 +457,9 @@ inline bool group_fits_dl(const GemmGroup& g, bool ak, bool bk, Epilogue epi, in
     if (p.K % bk_step != 0 || p.K < bk_step) return false;
     if (p.M < 8 || p.N < 8 || p.N % 8 != 0) return false;
     if ((reinterpret_cast<uintptr_t>(p.C) & 15) || p.ldc % c_vec != 0) return false;
+    // the tile loads address an operand with 32-bit byte offsets from its first element
+    const uint64_t a_outer = ak ? (uint64_t)p.M : (uint64_t)p.K, b_outer = bk ? (uint64_t)p.N : (uint64_t)p.K;
+    if (a_outer * (uint64_t)p.lda * 2 > 0xFFFFFFFFull || b_outer * (uint64_t)p.ldb * 2 > 0xFFFFFFFFull) return false;
   }
   return true;
 }

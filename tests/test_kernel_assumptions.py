@@ -48,3 +48,37 @@ def test_early_weight_prefetch_is_exactly_eight_loads(tmp_path):
         # the last memory operations before the wait: 8 tile loads of the step, then exactly 8 register loads
         assert before.endswith("T" * 8 + "W" * 8), (name, before[-40:])
         assert "S" not in before[before.rindex("B"):], name     # and no store in between
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
+def test_large_tile_kernel_refuses_operands_beyond_its_32_bit_offsets(tmp_path):
+    # The large-tile GEMM addresses an operand with 32-bit byte offsets from its first element, so the
+    # host has to route operands of 4 GiB or more to the general kernel (64-bit offsets).  Host code only.
+    src = tmp_path / "fits.hip"
+    src.write_text(r'''
+#include "gemm_mfma_dl.hpp"
+#include <cstdio>
+using namespace galore;
+static GemmGroup one(int M, int N, int K, int lda, int ldb) {
+  GemmGroup g{}; g.count = 1;
+  GemmProblem& p = g.p[0];
+  p.A = reinterpret_cast<const void*>(0x1000); p.B = reinterpret_cast<const void*>(0x2000); p.C = reinterpret_cast<void*>(0x3000);
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = N;
+  return g;
+}
+int main() {
+  // A as [M][K], B as [N][K], both contiguous along K
+  printf("%d", (int)group_fits_dl(one(4096, 4096, 1024, 1024, 1024), true, true, Epilogue::ApplyW));          // ordinary
+  printf("%d", (int)group_fits_dl(one(1 << 20, 4096, 1024, 2048, 1024), true, true, Epilogue::ApplyW));       // A: 2^20 x 2048 x 2 B = 4 GiB
+  printf("%d", (int)group_fits_dl(one((1 << 20) - 1, 4096, 1024, 2048, 1024), true, true, Epilogue::ApplyW));  // just under
+  printf("%d", (int)group_fits_dl(one(4096, 1 << 21, 1024, 1024, 1024), true, true, Epilogue::ApplyW));       // B: 4 GiB
+  // B as [K][N]: K rows of ldb elements
+  printf("%d\n", (int)group_fits_dl(one(1024, 8192, 1 << 18, 1 << 18, 8192), true, false, Epilogue::StoreF32)); // B: 2^18 x 8192 x 2 B = 4 GiB
+  return 0;
+}
+''')
+    exe = str(tmp_path / "fits")
+    inc = os.path.join(ROOT, "paper_2403_03507_amd", "csrc")
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O1", "-std=c++17", "-I", inc, "-Xclang", "-target-feature",
+                           "-Xclang", "-packed-fp32-ops", "-o", exe, str(src)], stderr=subprocess.DEVNULL)
+    assert subprocess.check_output([exe]).decode().strip() == "10100"
