@@ -364,3 +364,24 @@ def test_gradient_with_padded_rows(shape, pad, dtype):
     else:
         assert _proj_dist(P, orc.round_storage(P0, "bf16")) <= 2e-2
     opt.close()
+
+
+@pytest.mark.parametrize("shape,dtype", [((512, 1376), "f32"), ((1376, 512), "f32"), ((512, 1376), "bf16"), ((544, 600), "f32")])
+def test_short_side_of_512_and_more_uses_split_bf16_products(shape, dtype):
+    # From a short side of 512 (multiple of 32) on, Zt = Qt C runs on the bf16 matrix cores with
+    # both operands split three ways, which has to be as accurate as the fp32 product it replaces:
+    # the gap of these gradients (sigma_r / sigma_1 = 1/20, 1/400 in the Gram matrix) leaves no room
+    # for a product that is good to 2^-16 only (two-way split) under the 1e-3 gate.
+    m, n = shape
+    r = 64
+    G = wl.GradientSource(m, n, 95, "gapped", dtype=dtype, gap_rank=r).grad(0)
+    P0, sig = orc.projector(to64(G), r)
+    opt = _refresh([G], r, iters=8)
+    P = to64(opt.proj[0])
+    if dtype == "f32":
+        assert _proj_dist(P, P0) <= 1e-3
+        assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
+        np.testing.assert_allclose(np.sum(P * P0, axis=0), 1.0, atol=1e-4)
+    else:
+        assert _proj_dist(P, orc.round_storage(P0, "bf16")) <= 2e-2
+    opt.close()
