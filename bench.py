@@ -101,10 +101,11 @@ def main():
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
     LPC = args.layers_per_call
-    call_w = {l: [x for k in range(l, min(l + LPC, L)) for x in w_descs[k]] for l in range(0, L, LPC)}
+    # argument arrays are marshalled once: weights and pooled gradients stay where they are
+    call_w = {l: gb.tensor_array(x for k in range(l, min(l + LPC, L)) for x in w_descs[k]) for l in range(0, L, LPC)}
     # the layers of one call take consecutive gradient sets of the pool
-    call_g = [{l: [x for k in range(l, min(l + LPC, L)) for x in g_descs[(s + k - l) % POOL]] for l in range(0, L, LPC)}
-              for s in range(POOL)]
+    call_g = [{l: gb.tensor_array(x for k in range(l, min(l + LPC, L)) for x in g_descs[(s + k - l) % POOL])
+               for l in range(0, L, LPC)} for s in range(POOL)]
 
     def one_step(step_index):
         for l in reversed(range(0, L, LPC)):  # backward order, one layer (or LPC layers) per call

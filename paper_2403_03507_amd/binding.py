@@ -116,7 +116,15 @@ def shape_desc(rows, cols, dtype, ld=None, data=None):
 
 
 def _arr(items, typ):
+    if isinstance(items, ctypes.Array) and items._type_ is typ:
+        return items      # marshalled once by the caller (tensor_array): per-layer calls of small stacks are host-bound
     return (typ * len(items))(*items)
+
+
+def tensor_array(descs):
+    """A C array of galore_tensor for the list arguments of galore_step / galore_refresh_subspace, built once
+    and reused while the tensors stay where they are."""
+    return _arr(list(descs), galore_tensor)
 
 
 def _stream():
