@@ -35,6 +35,8 @@ class PerLayerGaLore:
         # with overlapped calls the library reads a gradient on its own streams after the hook has
         # returned: the caching allocator is told so before the gradient is dropped
         self._lib_streams = self.opt.library_streams() if overlap_calls else []
+        # the weights stay where they are: their argument arrays are marshalled once
+        self._w_arrays = [gb.tensor_array(gb.desc(p.data) for p in l) for l in self.layers]
         self._ready = [0] * len(self.layers)
         self._handles = []
         for li, l in enumerate(self.layers):
@@ -54,7 +56,7 @@ class PerLayerGaLore:
         grads = [p.grad for p in params]
         for p, g in zip(params, grads):
             assert g is not None and g.dtype == p.dtype and g.is_contiguous()
-        self.opt.step([p.data for p in params], grads, self.lr, first=self.first[li])
+        gb.galore_step(self.opt.ctx, self._w_arrays[li], [gb.desc(g) for g in grads], self.first[li], len(params), self.lr)
         for g in grads:
             for st in self._lib_streams:
                 g.record_stream(st)
