@@ -162,7 +162,10 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
  * formed in fp32: entries of G beyond about 1e17 in magnitude overflow it, and such a gradient,
  * like one with inf or NaN entries, yields a projector (and, in galore_step, moments and weights)
  * with non-finite entries; no error is reported and no kernel misbehaves, the caller is
- * expected to skip steps whose gradients are not finite. */
+ * expected to skip steps whose gradients are not finite.
+ * Environment: GALORE_REFRESH_FP32_PRODUCTS=1 (read once per process) makes the iteration's
+ * products Qt C run on the fp32 matrix cores instead of as split-bf16 products of the same
+ * accuracy; it exists for comparison and changes workspace needs, so set it before the first call. */
 galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, int32_t first,
                                       int32_t count);
 
