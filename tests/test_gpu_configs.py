@@ -42,3 +42,40 @@ def test_one_layer_two_steps(cfg):
             assert relF(to64(opt.M[i]), o.M) <= 1e-5, (cfg, step, i)
             assert relF(to64(opt.V[i]), o.V) <= 1e-5, (cfg, step, i)
     opt.close()
+
+
+def test_llama130m_layer_one_refresh_period_of_200_steps():
+    # One layer of the 130M stack over a whole refresh period (T = 200: the projector of step 0 serves all
+    # 200 steps), as the paper's runs do between two refreshes.  Parity protocol for a projector that
+    # several answers satisfy: the oracle is handed the bits of the device's projector, then both run
+    # 200 steps on the same gradients; W, M, V are compared along the way, so rounding differences that
+    # accumulate (bf16 weights move by 0 or 1 ulp per step) would show.
+    c = wl.CONFIGS["llama130m"]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    r, dtype, lr = c["rank"], c["dtype"], f32(1e-3)
+    srcs = wl.make_sources("llama130m", seed=13, device="cpu", layers=1)
+    W0 = [wl.make_weight(m, n, 170 + i, dtype) for i, (m, n) in enumerate(shapes)]
+    Wd = [w.cuda() for w in W0]
+    opt = gb.GaLore(Wd, r, update_gap=200, refresh_iters=4, auto_refresh=True)
+    oracles = [orc.GaLoreTensor(to64(W0[i]), r, update_gap=200, scale=f32(0.25), beta1=f32(0.9), beta2=f32(0.999),
+                                eps=f32(1e-8), dtype=dtype, auto_refresh=False) for i in range(len(shapes))]
+    worst = {}
+    for step in range(200):
+        G = [s.grad(step) for s in srcs]
+        opt.step(Wd, [g.cuda() for g in G], lr)
+        if step == 0:
+            torch.cuda.synchronize()
+            for i, o in enumerate(oracles):
+                o.set_projector(to64(opt.proj[i]))
+        for i, o in enumerate(oracles):
+            o.step(to64(G[i]), lr)
+        if step in (0, 9, 49, 99, 199):
+            torch.cuda.synchronize()
+            for i, o in enumerate(oracles):
+                e = (relF(to64(Wd[i]), o.W), relF(to64(opt.M[i]), o.M), relF(to64(opt.V[i]), o.V))
+                worst[step] = tuple(max(a, b) for a, b in zip(worst.get(step, (0, 0, 0)), e))
+                assert e[0] <= TOL[dtype] and e[1] <= 1e-5 and e[2] <= 1e-5, (step, i, e)
+    print("worst relF (W, M, V) by step:", worst)
+    for i in range(len(shapes)):
+        assert opt.get_step(i) == 200
+    opt.close()
