@@ -428,7 +428,8 @@ galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first
         ++pos;
       }
       ProfScope prof(ctx, GALORE_STAGE_REFRESH, true, stream);
-      hipError_t e = refresh_group(chunk, ctx->hp.rank, warm ? ctx->hp.refresh_warm_iters : ctx->hp.refresh_iters, warm, stream);
+      hipError_t e = refresh_group(chunk, ctx->hp.rank, warm ? ctx->hp.refresh_warm_iters : ctx->hp.refresh_iters, warm,
+                                   /*crowded=*/stream != ctx->stream, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "subspace refresh");
       for (int idx : chunk_tensors) {
         ctx->tensors[idx].proj_t_valid = true;  // the refresh writes proj and proj_t
@@ -1101,7 +1102,7 @@ galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_te
   it.ldpt = left ? m : n;
   it.ws = ws + L.rws;
   it.seed = hp->seed + 0x9E3779B97F4A7C15ull;
-  hipError_t e = refresh_group(std::vector<RefreshItem>{it}, r, hp->refresh_iters, /*warm_start=*/false, stream);
+  hipError_t e = refresh_group(std::vector<RefreshItem>{it}, r, hp->refresh_iters, /*warm_start=*/false, /*crowded=*/false, stream);
   if (e != hipSuccess) return hip_fail(nullptr, e, "subspace refresh");
   if (left) {
     // rows of P^T G are s_i v_i^T: unit length makes them Q^T

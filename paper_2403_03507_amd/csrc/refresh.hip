@@ -1008,13 +1008,13 @@ constexpr int kGramB = 16, kGramR2 = 32;
 // for lane (i = lane % 16, g = lane / 16).  A wave owns whole columns, so it reads all 32 inputs
 // of a column before it writes any.
 __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r, const int (&rows)[8], const int (&out_rows)[2][4],
-                                                    const float (&rot)[2][8], int wave, int lane) {
+                                                    const float (&rot)[2][8], int wave, int lane, int nwaves) {
   const int j = lane & 15;
   // 64 columns per trip: lane (j, g) owns columns col0 .. col0 + 3 (one 16-byte access per row), column
   // col0 + c belongs to MFMA column block c.  r is a multiple of 4, so a piece is inside or outside as
   // a whole.  All loads of a trip are issued before its MFMAs.
   const jf4m zero = {0.f, 0.f, 0.f, 0.f};
-  for (int n0 = 64 * wave; n0 < r; n0 += 1024) {
+  for (int n0 = 64 * wave; n0 < r; n0 += 64 * nwaves) {
     const int col0 = n0 + 4 * j;
     const bool cok = col0 < r;
     jf4m b[8];
@@ -1039,9 +1039,18 @@ __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r
   }
 }
 
-__global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGroup* __restrict__ gp, int round, int nplayers, int sweep) {
+// NW = wavefronts per workgroup.  The work is laid out in 16 shares (one rotation per share and inner
+// round, one Gram entry per thread of 1024); a wavefront takes 16 / NW of them, one after the other, and
+// 16 / NW workgroups fit a CU (<= 128 registers per lane).  The round is a chain of dependent LDS
+// round trips, so fewer wavefronts cost little: per 7B layer set a refresh alone takes 84.0 / 84.2 /
+// 90.6 ms with NW = 16 / 8 / 4, while with three refreshes in flight (the launches of this kernel then
+// outnumber the CUs, and the memory phases of one workgroup overlap with the inner rounds of its
+// neighbours on the CU) it takes 53.3 / 50.8 / 48.9 ms.  Hence 8 alone and 4 when crowded.
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(const RefreshGroup* __restrict__ gp, int round, int nplayers, int sweep) {
   const RefreshGroup& grp = *gp;
   constexpr int B = kGramB, R2 = kGramR2, GP = R2 + 1;
+  constexpr int VW = 16 / NW;  // shares ("virtual wavefronts") per wavefront
   __shared__ float Gm[2][R2 * GP];
   __shared__ float Rot[R2 * GP];             // Rot[i][k]: new row i = sum_k Rot[i][k] old row k
   __shared__ float stage[16 * 256];          // per wave: a 16 x 16 partial Gram block
@@ -1069,20 +1078,24 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
   // 1. Gram matrix: wave w computes the 16 x 16 block (I0, J0) over a quarter of the columns.  MFMA
   // operand lane (i = lane % 16, g = lane / 16) supplies k = 4 g + (0..3) of every 16 columns, the
   // same for A and B, so one 16-byte load feeds four MFMAs.
-  {
-    const int I0 = (wave & 1) * 16, J0 = ((wave >> 1) & 1) * 16, kq = wave >> 2;
+#pragma unroll
+  for (int sh = 0; sh < VW; ++sh) {
+    const int vw = wave + NW * sh;
+    const int I0 = (vw & 1) * 16, J0 = ((vw >> 1) & 1) * 16, kq = vw >> 2;
     const int i = lane & 15, g = lane >> 4;
     const int ga = grow(I0 + i), gb = grow(J0 + i);
     const float* arow = t.Bw + (size_t)(ga >= 0 ? ga : 0) * r;
     const float* brow = t.Bw + (size_t)(gb >= 0 ? gb : 0) * r;
     const jf4m acc = gram_partial(arow, ga >= 0, brow, gb >= 0, 0, r, kq, g);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
+    for (int v = 0; v < 4; ++v) stage[vw * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
   }
   if (tid == 0) { rotated = 0; significant = 0; }
   __syncthreads();
-  {
-    const int i = tid >> 5, j = tid & 31;
+#pragma unroll
+  for (int sh = 0; sh < VW; ++sh) {
+    const int vt = tid + 64 * NW * sh;
+    const int i = vt >> 5, j = vt & 31;
     const int blk = (i >> 4) | ((j >> 4) << 1);
     float sum = 0.f;
 #pragma unroll
@@ -1101,16 +1114,19 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
   const int inner_rounds = all_pairs ? R2 - 1 : B;
   for (int isw = 0; isw < kGramInnerSweeps; ++isw)
     for (int ir = 0; ir < inner_rounds; ++ir) {
-      // phase A: every wave derives the rotation of its pair
+      // phase A: every (virtual) wave derives the rotation of its pair
+      const float* G = Gm[cur];
+#pragma unroll
+      for (int sh = 0; sh < VW; ++sh) {
+      const int vw = wave + NW * sh;
       int p, q;
       if (all_pairs) {
-        if (wave == 0) { p = R2 - 1; q = ir; }
-        else { p = (ir + wave) % (R2 - 1); q = (ir + (R2 - 1) - wave) % (R2 - 1); }
+        if (vw == 0) { p = R2 - 1; q = ir; }
+        else { p = (ir + vw) % (R2 - 1); q = (ir + (R2 - 1) - vw) % (R2 - 1); }
         if (p > q) { const int x = p; p = q; q = x; }
       } else {
-        p = wave; q = B + ((wave + ir) & (B - 1));
+        p = vw; q = B + ((vw + ir) & (B - 1));
       }
-      const float* G = Gm[cur];
       const float a = G[p * GP + p], bb = G[q * GP + q], c = G[p * GP + q];
       const bool rot = grow(p) >= 0 && grow(q) >= 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
       float cs = 1.f, sn = 0.f;
@@ -1133,10 +1149,13 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
         Rot[p * GP + lane] = cs * uu - sn * vv;
         Rot[q * GP + lane] = sn * uu + cs * vv;
       }
+      }
       __syncthreads();
       // phase B: G <- J^T G J for the 16 disjoint rotations of this round
-      {
-        const int i = tid >> 5, j = tid & 31;
+#pragma unroll
+      for (int sh = 0; sh < VW; ++sh) {
+        const int vt = tid + 64 * NW * sh;
+        const int i = vt >> 5, j = vt & 31;
         const int pi = partner[i], pj = partner[j];
         const float ai = alpha[i], bi2 = beta[i], aj = alpha[j], bj2 = beta[j];
         Gm[cur ^ 1][i * GP + j] = ai * (aj * G[i * GP + j] + bj2 * G[i * GP + pj]) + bi2 * (aj * G[pi * GP + j] + bj2 * G[pi * GP + pj]);
@@ -1163,8 +1182,8 @@ __global__ __launch_bounds__(1024) void jacobi_gram_round_kernel(const RefreshGr
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int v = 0; v < 4; ++v) out_rows[h][v] = grow(16 * h + 4 * g + v);
-    gram_apply_rotation(t.Bw, r, rows, out_rows, rot, wave, lane);
-    gram_apply_rotation(t.Jt, r, rows, out_rows, rot, wave, lane);
+    gram_apply_rotation(t.Bw, r, rows, out_rows, rot, wave, lane, NW);
+    gram_apply_rotation(t.Jt, r, rows, out_rows, rot, wave, lane, NW);
   }
 }
 
@@ -1265,7 +1284,7 @@ inline unsigned blocks_for(int64_t count, int per_block, unsigned cap) {
 
 size_t refresh_workspace_bytes(int64_t kdim, int64_t r) { return layout_for(kdim, r).total; }
 
-hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, hipStream_t stream) {
+hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, bool crowded, hipStream_t stream) {
   const int n = (int)items.size();
   if (n == 0) return hipSuccess;
   if (n > kMaxGroup) return hipErrorInvalidValue;
@@ -1479,7 +1498,8 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
       for (int round = 0; round < players - 1; ++round)
         if (use_gram)
-          hipLaunchKernelGGL(jacobi_gram_round_kernel, dim3(players / 2, n), dim3(1024), 0, stream, dgrp, round, players, sweep);
+          if (crowded) hipLaunchKernelGGL(jacobi_gram_round_kernel<4>, dim3(players / 2, n), dim3(256), 0, stream, dgrp, round, players, sweep);
+          else hipLaunchKernelGGL(jacobi_gram_round_kernel<8>, dim3(players / 2, n), dim3(512), 0, stream, dgrp, round, players, sweep);
         else if (jb == 16)
           hipLaunchKernelGGL(jacobi_block_round_kernel<16>, dim3(players / 2, n), dim3(1024), smem, stream, dgrp, round, players, sweep);
         else

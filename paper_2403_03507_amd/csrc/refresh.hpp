@@ -25,6 +25,8 @@ size_t refresh_workspace_bytes(int64_t kdim, int64_t r);
 // Recompute the projectors of up to kMaxGroup tensors with grouped launches on `stream`: `iters`
 // rounds of orthogonal iteration from the seeded Gaussian block, or, with `warm_start`, from what
 // proj_t holds on entry (a previous projector of the same tensor; must have full rank).
-hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, hipStream_t stream);
+// `crowded`: other refreshes run beside this one (overlapped calls), so kernels whose launches then
+// outnumber the CUs use their smaller-workgroup variants.  Results do not depend on it.
+hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters, bool warm_start, bool crowded, hipStream_t stream);
 
 }  // namespace galore
