@@ -156,7 +156,8 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
  * (RIGHT) singular vectors of G, obtained from the Gram matrix of the short side by
  * blocked subspace iteration with Householder QR and a final Rayleigh-Ritz rotation, so
  * columns are ordered by decreasing singular value; each column's sign makes its
- * largest-magnitude entry positive.  Writes state.proj only; M, V, W and t are untouched.
+ * largest-magnitude entry positive.  Writes state.proj and its transposed copy state.proj_t; M, V, W
+ * and t are untouched.
  * A gradient of rank below r (the zero matrix included) gets an orthonormal projector whose
  * span holds all of G; which vectors complete it is not determined by G.  The Gram matrix is
  * formed in fp32: entries of G beyond about 1e17 in magnitude overflow it, and such a gradient,
