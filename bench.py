@@ -173,7 +173,9 @@ def main():
     else:
         peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
         achieved = flops[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
-        roofline = {"kernel": "gemm_dl_kernel/" + dominant, "bound": "mfma", "achieved": achieved, "peak": peak,
+        # bf16 tensors of these shapes run on the large-tile kernel, fp32 tensors on the general one
+        roofline = {"kernel": ("gemm_dl_kernel/" if dtype == "bf16" else "gemm_group_kernel/") + dominant, "bound": "mfma",
+                    "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
