@@ -115,3 +115,33 @@ def test_q8_moments_need_rows_of_a_multiple_of_256():
     with pytest.raises(gb.GaloreError) as e:
         gb.GaLore(W, 64, moments="q8")
     assert e.value.status == 9
+
+
+def test_q8_step_is_the_same_in_every_schedule():
+    # serial, three chains inside a call, overlapped calls (two and three in flight), with a refresh
+    # falling due on the way: the 8-bit state and the weights come out bit-identical.
+    # rows of the moment matrices have to be multiples of 256: r = 256 for the RIGHT tensor, long sides 768 / 512
+    layer = [((512, 768), "bf16"), ((768, 512), "bf16"), ((512, 512), "bf16")]
+    specs = layer * 3
+    srcs = [wl.GradientSource(m, n, 300 + i, "gapped", dtype=dt, gap_rank=256) for i, ((m, n), dt) in enumerate(specs)]
+
+    def run(lanes, overlap):
+        W = [wl.make_weight(m, n, 200 + i, dt).cuda() for i, ((m, n), dt) in enumerate(specs)]
+        opt = gb.GaLore(W, 256, moments="q8", update_gap=2, refresh_iters=2, auto_refresh=True, workspace_factor=3)
+        gb.galore_set_concurrency(opt.ctx, lanes)
+        opt.set_call_overlap(overlap)
+        for step in range(3):
+            G = [s.grad(step).cuda() for s in srcs]
+            torch.cuda.synchronize()
+            for l in reversed(range(3)):
+                opt.step(W[3 * l: 3 * l + 3], G[3 * l: 3 * l + 3], 1e-2, first=3 * l)
+            opt.join()
+            torch.cuda.synchronize()
+        out = [w.clone() for w in W] + [x.clone() for x in opt.M + opt.V + opt.M_scale + opt.V_scale + opt.proj]
+        opt.close()
+        return out
+
+    ref = run(1, 0)
+    for lanes, overlap in ((3, 0), (1, 2), (1, 3)):
+        for x, y in zip(ref, run(lanes, overlap)):
+            assert torch.equal(x, y), (lanes, overlap)

@@ -385,3 +385,38 @@ def test_short_side_of_512_and_more_uses_split_bf16_products(shape, dtype):
     else:
         assert _proj_dist(P, orc.round_storage(P0, "bf16")) <= 2e-2
     opt.close()
+
+
+def test_warm_and_cold_tensors_in_one_call():
+    # T = 1: every step refreshes.  Tensor 0 is stepped once on its own first, so in the next call it
+    # starts from its projector (warm) while tensors 1 and 2 start cold: the library runs the two kinds
+    # as separate groups, and each tensor ends up bit-identical to the same history in a context of its own.
+    shapes = [(256, 688), (688, 256), (320, 512)]
+    r = 32
+    srcs = [wl.GradientSource(m, n, 400 + i, "gapped", dtype="f32", gap_rank=r) for i, (m, n) in enumerate(shapes)]
+
+    def fresh(idx):
+        W = [wl.make_weight(*shapes[i], 500 + i, "f32").cuda() for i in idx]
+        return W, gb.GaLore(W, r, update_gap=1, refresh_iters=4, refresh_warm_iters=2, auto_refresh=True, seed=9)
+
+    W, opt = fresh([0, 1, 2])
+    opt.step(W[0:1], [srcs[0].grad(0).cuda()], 1e-3, first=0)
+    opt.step(W, [srcs[0].grad(1).cuda(), srcs[1].grad(0).cuda(), srcs[2].grad(0).cuda()], 1e-3)
+    torch.cuda.synchronize()
+    together = [p.clone() for p in opt.proj] + [w.clone() for w in W]
+    opt.close()
+    alone = [None] * 6
+    for i in range(3):
+        # the Gaussian start block is seeded per tensor INDEX, so the lone contexts keep the list (and
+        # with it the index) and step only tensor i
+        Wi, oi = fresh([0, 1, 2])
+        if i == 0:
+            oi.step(Wi[0:1], [srcs[0].grad(0).cuda()], 1e-3, first=0)
+            oi.step(Wi[0:1], [srcs[0].grad(1).cuda()], 1e-3, first=0)
+        else:
+            oi.step(Wi[i:i + 1], [srcs[i].grad(0).cuda()], 1e-3, first=i)
+        torch.cuda.synchronize()
+        alone[i], alone[3 + i] = oi.proj[i].clone(), Wi[i].clone()
+        oi.close()
+    for x, y in zip(together, alone):
+        assert torch.equal(x, y)
