@@ -82,3 +82,33 @@ int main() {
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O1", "-std=c++17", "-I", inc, "-Xclang", "-target-feature",
                            "-Xclang", "-packed-fp32-ops", "-o", exe, str(src)], stderr=subprocess.DEVNULL)
     assert subprocess.check_output([exe]).decode().strip() == "10100"
+
+
+def test_three_bf16_parts_hold_an_fp32_number_exactly():
+    # The refresh multiplies fp32 matrices on the bf16 matrix cores after splitting every entry into
+    # hi + mid + lo (each rounded to nearest even, the remainder formed in fp32).  The claim behind it:
+    # the three parts reproduce the fp32 number exactly (8 significant bits apiece), and the six partial
+    # products the kernel keeps miss the full product by less than 2^-22 of it.  Checked here with
+    # torch's own bf16 rounding on the CPU (same arithmetic as the kernel's split3).
+    import torch
+    g = torch.Generator().manual_seed(0)
+    x = torch.cat([torch.randn(200000, generator=g) * s for s in (1e-20, 1e-6, 1.0, 1e6, 1e20)] +
+                  [torch.tensor([0.0, 1.0, -1.0, 3.0e38, -3.0e38, 1.1754944e-38 * 2 ** 20, 0.1, 1.0 + 2 ** -23, 1.0 - 2 ** -24])])
+
+    def split(v):
+        hi = v.bfloat16().float()
+        r1 = v - hi
+        mid = r1.bfloat16().float()
+        lo = (r1 - mid).bfloat16().float()
+        return hi, mid, lo
+
+    hi, mid, lo = split(x)
+    assert torch.equal((hi.double() + mid.double() + lo.double()).float(), x)
+    assert torch.equal(hi.double() + mid.double() + lo.double(), x.double())     # not merely after rounding
+    y = x[torch.randperm(x.numel(), generator=g)]
+    yh, ym, yl = split(y)
+    kept = (hi.double() * yh.double() + hi.double() * ym.double() + mid.double() * yh.double() + mid.double() * ym.double()
+            + hi.double() * yl.double() + lo.double() * yh.double())
+    full = x.double() * y.double()
+    ok = full != 0
+    assert float(((kept - full).abs()[ok] / full.abs()[ok]).max()) <= 2.0 ** -22
