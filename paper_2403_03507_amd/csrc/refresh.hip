@@ -409,26 +409,45 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
   const int c0 = col_begin + kSW * blockIdx.x;
   // v[s][ii]: entry of the ii-th reflector IN APPLICATION ORDER (unit diagonal, zeros above it)
   float v[kRPT][kNB], x[kRPT][kSW];
+  // Every load below is unconditional, from an address that is valid whatever the guards say (the
+  // guards only select afterwards): written as "if (inside) load", each of the 32 reflector entries
+  // became a branch with its own scalar load, vector load and full wait, one after the other, and
+  // those round trips were two thirds of this kernel's time.
+  int jref[kNB];
+  float vsc[kNB], taus[kNB];
+  const float* __restrict__ vscale_p = t.vscale;
+  const float* __restrict__ tau_p = t.tau;
+#pragma unroll
+  for (int ii = 0; ii < kNB; ++ii) {
+    jref[ii] = ii < nb ? j0 + (reverse ? nb - 1 - ii : ii) : j0;
+    vsc[ii] = vscale_p[jref[ii]];
+    const float tau_any = tau_p[jref[ii]];
+    taus[ii] = ii < nb ? tau_any : 0.f;
+  }
 #pragma unroll
   for (int s = 0; s < kRPT; ++s) {
     const int row = j0 + tid + 1024 * s;
+    const int row_ok = row < k ? row : j0;  // j0 < k always
 #pragma unroll
     for (int ii = 0; ii < kNB; ++ii) {
-      float e = 0.f;
-      if (row < k && ii < nb) {
-        const int j = j0 + (reverse ? nb - 1 - ii : ii);
-        if (row > j) e = Zv[(size_t)j * k + row] * t.vscale[j];
-        else if (row == j) e = 1.f;
-      }
-      v[s][ii] = e;
+      // select by arithmetic (raw is finite wherever the matrix is): a select on the loaded value lets the
+      // compiler sink the load back under a branch
+      const float raw = Zv[(size_t)jref[ii] * k + row_ok];
+      const int j = jref[ii];
+      const bool in = row < k && ii < nb;
+      v[s][ii] = __builtin_fmaf(raw, (in && row > j) ? vsc[ii] : 0.f, (in && row == j) ? 1.f : 0.f);
     }
 #pragma unroll
-    for (int c = 0; c < kSW; ++c) x[s][c] = (row < k && c0 + c < col_end) ? X[(size_t)(c0 + c) * k + row] : 0.f;
+    for (int c = 0; c < kSW; ++c) {
+      const int col = c0 + c < col_end ? c0 + c : c0;  // c0 < col_end: the grid covers [col_begin, col_end)
+      const float raw = X[(size_t)col * k + row_ok];
+      x[s][c] = raw * ((row < k && c0 + c < col_end) ? 1.f : 0.f);
+    }
   }
 #pragma unroll
   for (int ii = 0; ii < kNB; ++ii) {
     if (ii >= nb) break;
-    const float tau = t.tau[j0 + (reverse ? nb - 1 - ii : ii)];
+    const float tau = taus[ii];
     if (tau == 0.f) continue;  // uniform over the block
     float w[kSW];
 #pragma unroll
