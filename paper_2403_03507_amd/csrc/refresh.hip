@@ -325,6 +325,8 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int k = t.k;
   float* __restrict__ Z = t.Z;  // element (row, col) at Z[col * k + row]
+  float* const tau_out = t.tau;        // fetched from the table here, not inside thread 0's branch of every reflector round
+  float* const vscale_out = t.vscale;
   const int tid = threadIdx.x;
   float x[kRPT][kNB];
 #pragma unroll
@@ -362,7 +364,7 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
       tau = (beta - x0) / beta;
       vs = 1.0f / (x0 - beta);
     }
-    if (tid == 0) { t.tau[j] = tau; t.vscale[j] = vs; }
+    if (tid == 0) { tau_out[j] = tau; vscale_out[j] = vs; }
     if (tau != 0.f) {
 #pragma unroll
       for (int c = 0; c < kNB; ++c) {
@@ -415,8 +417,8 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
   // those round trips were two thirds of this kernel's time.
   int jref[kNB];
   float vsc[kNB], taus[kNB];
-  const float* __restrict__ vscale_p = t.vscale;
-  const float* __restrict__ tau_p = t.tau;
+  float* const vscale_p = t.vscale;   // both also written by the fused factorisation below
+  float* const tau_p = t.tau;
 #pragma unroll
   for (int ii = 0; ii < kNB; ++ii) {
     jref[ii] = ii < nb ? j0 + (reverse ? nb - 1 - ii : ii) : j0;
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
         tau = (beta - x0) / beta;
         vs = 1.0f / (x0 - beta);
       }
-      if (tid == 0) { t.tau[j] = tau; t.vscale[j] = vs; }
+      if (tid == 0) { tau_p[j] = tau; vscale_p[j] = vs; }
       if (tau != 0.f) {
 #pragma unroll
         for (int c = 0; c < kNB; ++c) {
