@@ -1024,6 +1024,7 @@ __global__ __launch_bounds__(1024) void jacobi_block_round_kernel(const RefreshG
 // Needs r % 4 == 0 (16-byte row segments); no limit on r.
 typedef float jf4m __attribute__((ext_vector_type(4)));
 constexpr int kGramB = 16, kGramR2 = 32;
+constexpr int kGramSlices = 8;  // column slices of the Gram phase of the block round
 
 // Y (32 rows picked by rows[], length r) <- Rot Y, in place.  rot[h][s] = Rot[16 h + i][4 s + g]
 // for lane (i = lane % 16, g = lane / 16).  A wave owns whole columns, so it reads all 32 inputs
@@ -1074,7 +1075,7 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
   constexpr int VW = 16 / NW;  // shares ("virtual wavefronts") per wavefront
   __shared__ float Gm[2][R2 * GP];
   __shared__ float Rot[R2 * GP];             // Rot[i][k]: new row i = sum_k Rot[i][k] old row k
-  __shared__ float stage[16 * 256];          // per wave: a 16 x 16 partial Gram block
+  __shared__ float stage[kGramSlices * 3 * 256];  // per column slice: the partial blocks (0,0), (0,1), (1,1), 16 x 16 each
   __shared__ float alpha[R2], beta[R2];      // per row: new_row = alpha * row + beta * partner row
   __shared__ int partner[R2];
   __shared__ int rotated;      // some rotation was applied: Bw and Jt have to be updated
@@ -1096,20 +1097,53 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
     return ((ls < B || bj < nblocks) && g < r) ? g : -1;
   };
 
-  // 1. Gram matrix: wave w computes the 16 x 16 block (I0, J0) over a quarter of the columns.  MFMA
-  // operand lane (i = lane % 16, g = lane / 16) supplies k = 4 g + (0..3) of every 16 columns, the
-  // same for A and B, so one 16-byte load feeds four MFMAs.
-#pragma unroll
-  for (int sh = 0; sh < VW; ++sh) {
-    const int vw = wave + NW * sh;
-    const int I0 = (vw & 1) * 16, J0 = ((vw >> 1) & 1) * 16, kq = vw >> 2;
+  // 1. Gram matrix.  The columns are dealt in groups of 16 to kGramSlices slices (group S belongs to
+  // slice S mod kGramSlices; the number of slices is fixed so that the result does not depend on NW).  A
+  // wavefront takes whole slices: for each it loads, per group, one 16-byte piece of row i and one of row
+  // 16 + i (MFMA operand lane (i = lane % 16, g = lane / 16) supplies columns 4 g .. 4 g + 3 of the group) and
+  // feeds three block products with them: (0,0), (0,1) and (1,1); block (1,0) is the transpose of (0,1).
+  // All loads of a slice (8 groups at r = 1024) are in flight together: one exposed memory round trip
+  // where block-by-block products of a quarter of the columns each needed four, for half the bytes.
+  {
     const int i = lane & 15, g = lane >> 4;
-    const int ga = grow(I0 + i), gb = grow(J0 + i);
-    const float* arow = t.Bw + (size_t)(ga >= 0 ? ga : 0) * r;
-    const float* brow = t.Bw + (size_t)(gb >= 0 ? gb : 0) * r;
-    const jf4m acc = gram_partial(arow, ga >= 0, brow, gb >= 0, 0, r, kq, g);
+    const int g0 = grow(i), g1 = grow(16 + i);
+    const float* x0 = t.Bw + (size_t)(g0 >= 0 ? g0 : 0) * r;
+    const float* x1 = t.Bw + (size_t)(g1 >= 0 ? g1 : 0) * r;
+    const float m0 = g0 >= 0 ? 1.f : 0.f, m1 = g1 >= 0 ? 1.f : 0.f;   // rows that do not exist count as zero
+    const int ngroups = (r + 15) >> 4;
+    const jf4m zero = {0.f, 0.f, 0.f, 0.f};
+    for (int sl = wave; sl < kGramSlices; sl += NW) {
+      jf4m a00 = zero, a01 = zero, a11 = zero;
+      for (int S0 = sl; S0 < ngroups; S0 += 8 * kGramSlices) {
+        jf4m p0[8], p1[8];
+        // unconditional loads from clamped addresses, masked by arithmetic (the matrix is finite wherever
+        // the gradient is): a guarded load would cost a branch and a wait of its own
 #pragma unroll
-    for (int v = 0; v < 4; ++v) stage[vw * 256 + (4 * g + v) * 16 + i] = acc[v];  // row 4 g + v, column i of the block
+        for (int u = 0; u < 8; ++u) {
+          const int pos = 16 * (S0 + kGramSlices * u) + 4 * g;
+          const bool ok = pos < r;   // r is a multiple of 4: a piece is inside or outside as a whole
+          const int ps = ok ? pos : 0;
+          const float mk = ok ? 1.f : 0.f;
+          p0[u] = *reinterpret_cast<const jf4m*>(x0 + ps) * (m0 * mk);
+          p1[u] = *reinterpret_cast<const jf4m*>(x1 + ps) * (m1 * mk);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            a00 = __builtin_amdgcn_mfma_f32_16x16x4f32(p0[u][e], p0[u][e], a00, 0, 0, 0);
+            a01 = __builtin_amdgcn_mfma_f32_16x16x4f32(p0[u][e], p1[u][e], a01, 0, 0, 0);
+            a11 = __builtin_amdgcn_mfma_f32_16x16x4f32(p1[u][e], p1[u][e], a11, 0, 0, 0);
+          }
+      }
+      // element (row 4 g + v, column i) of each block
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        stage[(sl * 3 + 0) * 256 + (4 * g + v) * 16 + i] = a00[v];
+        stage[(sl * 3 + 1) * 256 + (4 * g + v) * 16 + i] = a01[v];
+        stage[(sl * 3 + 2) * 256 + (4 * g + v) * 16 + i] = a11[v];
+      }
+    }
   }
   if (tid == 0) { rotated = 0; significant = 0; }
   __syncthreads();
@@ -1117,10 +1151,13 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
   for (int sh = 0; sh < VW; ++sh) {
     const int vt = tid + 64 * NW * sh;
     const int i = vt >> 5, j = vt & 31;
-    const int blk = (i >> 4) | ((j >> 4) << 1);
+    // entry (i, j) lives in block (i / 16, j / 16); the lower-left block is read from the upper-right one, transposed
+    const int bI = i >> 4, bJ = j >> 4;
+    const int b3 = bI == bJ ? 2 * bI : 1;
+    const int rr = (bI > bJ ? j : i) & 15, cc = (bI > bJ ? i : j) & 15;
     float sum = 0.f;
 #pragma unroll
-    for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    for (int sl = 0; sl < kGramSlices; ++sl) sum += stage[(sl * 3 + b3) * 256 + rr * 16 + cc];
     Gm[0][i * GP + j] = sum;
     Rot[i * GP + j] = i == j ? 1.f : 0.f;
   }
