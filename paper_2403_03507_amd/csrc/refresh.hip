@@ -719,9 +719,16 @@ __global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup* __
   }
 }
 
-__global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup* __restrict__ gp, int J0, int col_begin, int col_end,
-                                                         int target_is_q, int backward) {
+// NW = wavefronts per workgroup: the work is laid out for 16 (one entry of the 32 x 32 products per thread
+// of 1024, 64 positions per wavefront and trip); with 8 every wavefront takes two shares, and the lanes
+// may use up to 256 registers, which the 16 pieces in flight per trip need (under the 128 of a
+// 1024-thread workgroup the scheduler issued the loads one by one, each with a wait of its own).
+constexpr int kWYUpdateWaves = 8;
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void wy_update_kernel(const RefreshGroup* __restrict__ gp, int J0, int col_begin, int col_end,
+                                                            int target_is_q, int backward) {
   const RefreshGroup& grp = *gp;
+  constexpr int VW = 16 / NW;
   __shared__ float Wm[kWY * (kWY + 1)];
   __shared__ float Ym[kWY * (kWY + 1)];
   __shared__ float Tf[kWY * (kWY + 1)];
@@ -734,18 +741,22 @@ __global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup* __r
   int p_begin, p_end;
   wy_slice(J0, k, blockIdx.y, p_begin, p_end);
   if (p_begin >= p_end) return;  // uniform
-  {
+#pragma unroll
+  for (int sh = 0; sh < VW; ++sh) {
     const float* T = t.tmat + (size_t)(J0 / kWY) * (kWY * kWY);
-    const int i = tid >> 5, j = tid & 31;
+    const int vt = tid + 64 * NW * sh;
+    const int i = vt >> 5, j = vt & 31;
     Tf[i * (kWY + 1) + j] = backward ? T[j * kWY + i] : T[i * kWY + j];
     float sum = 0.f;
 #pragma unroll
-    for (int sl = 0; sl < kWYApplySlices; ++sl) sum += t.wpart[((size_t)blockIdx.x * kWYApplySlices + sl) * (kWY * kWY) + tid];
+    for (int sl = 0; sl < kWYApplySlices; ++sl) sum += t.wpart[((size_t)blockIdx.x * kWYApplySlices + sl) * (kWY * kWY) + vt];
     Wm[i * (kWY + 1) + j] = sum;
   }
   __syncthreads();
-  {
-    const int i = tid >> 5, j = tid & 31;
+#pragma unroll
+  for (int sh = 0; sh < VW; ++sh) {
+    const int vt = tid + 64 * NW * sh;
+    const int i = vt >> 5, j = vt & 31;
     float y = 0.f;
 #pragma unroll 8
     for (int l = 0; l < kWY; ++l) y += Wm[i * (kWY + 1) + l] * Tf[l * (kWY + 1) + j];
@@ -770,19 +781,29 @@ __global__ __launch_bounds__(1024) void wy_update_kernel(const RefreshGroup* __r
     // 64 positions per trip: lane (i, g) owns positions pos0 .. pos0 + 3 (one 16-byte access per row),
     // position pos0 + c belongs to MFMA column block c, so block c holds positions {n0 + 4 n + c}.
     // All loads of a trip are issued before its MFMAs.
-    for (int n0 = p_begin + 64 * wave; n0 < p_end; n0 += 1024) {
+    for (int n0 = p_begin + 64 * wave; n0 < p_end; n0 += 64 * NW) {
       const int pos0 = n0 + 4 * i;
       const bool pok = pos0 < p_end;          // slice ends are multiples of 4: a piece is inside or outside as a whole
       wf4 b[8];
       wf4 x[2][4];
       const wf4 zero = {0.f, 0.f, 0.f, 0.f};
+      // All 16 loads are unconditional, from clamped addresses: a lane whose positions lie beyond the slice
+      // reads the slice's first positions, a target row that does not exist is read from row c0 (always
+      // valid).  Nothing is masked: in these MFMAs a lane's pieces only reach the outputs of its own
+      // positions and each output row only depends on its own input row, and those outputs are not
+      // stored.  Guarded loads ("inside ? load : 0") compiled to a region and a full wait per load.
+      const int pos_ok = pok ? pos0 : p_begin;   // p_begin < p_end here; both are multiples of 4
 #pragma unroll
-      for (int sidx = 0; sidx < 8; ++sidx) b[sidx] = pok ? *reinterpret_cast<const wf4*>(V + (size_t)(4 * sidx + g) * k + pos0) : zero;
+      for (int sidx = 0; sidx < 8; ++sidx) b[sidx] = *reinterpret_cast<const wf4*>(V + (size_t)(4 * sidx + g) * k + pos_ok);
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-          x[h][v] = (xrow[h][v] >= 0 && pok) ? *reinterpret_cast<const wf4*>(X + (size_t)xrow[h][v] * k + pos0) : zero;
+        for (int v = 0; v < 4; ++v) {
+          const int xr = xrow[h][v] >= 0 ? xrow[h][v] : c0;
+          x[h][v] = *reinterpret_cast<const wf4*>(X + (size_t)xr * k + pos_ok);
+        }
+      __builtin_amdgcn_sched_barrier(0);  // all 16 loads first: the scheduler would otherwise thread them through the MFMAs, a wait apiece
+      (void)zero;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         wf4 acc[4];
@@ -1483,7 +1504,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
           if (trailing > 0) {
             const dim3 grid((trailing + kWY - 1) / kWY, kWYApplySlices, n);
             hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0 + nb32, r, 0);
-            hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0 + nb32, r, 0, 0);
+            hipLaunchKernelGGL(wy_update_kernel<kWYUpdateWaves>, grid, dim3(64 * kWYUpdateWaves), 0, stream, dgrp, J0, J0 + nb32, r, 0, 0);
           }
         }
         GALORE_RETURN_IF(hipGetLastError());
@@ -1491,7 +1512,7 @@ hipError_t refresh_group(const std::vector<RefreshItem>& items, int r, int iters
         for (int J0 = (r - 1) / kWY * kWY; J0 >= 0; J0 -= kWY) {
           const dim3 grid((r - J0 + kWY - 1) / kWY, kWYApplySlices, n);
           hipLaunchKernelGGL(wy_project_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0, r, 1);
-          hipLaunchKernelGGL(wy_update_kernel, grid, dim3(1024), 0, stream, dgrp, J0, J0, r, 1, 1);
+          hipLaunchKernelGGL(wy_update_kernel<kWYUpdateWaves>, grid, dim3(64 * kWYUpdateWaves), 0, stream, dgrp, J0, J0, r, 1, 1);
         }
         GALORE_RETURN_IF(hipGetLastError());
         continue;
