@@ -1137,6 +1137,7 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
       jf4m a00 = zero, a01 = zero, a11 = zero;
       for (int S0 = sl; S0 < ngroups; S0 += 8 * kGramSlices) {
         jf4m p0[8], p1[8];
+        float msk0[8], msk1[8];
         // unconditional loads from clamped addresses, masked by arithmetic (the matrix is finite wherever
         // the gradient is): a guarded load would cost a branch and a wait of its own
 #pragma unroll
@@ -1145,9 +1146,13 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
           const bool ok = pos < r;   // r is a multiple of 4: a piece is inside or outside as a whole
           const int ps = ok ? pos : 0;
           const float mk = ok ? 1.f : 0.f;
-          p0[u] = *reinterpret_cast<const jf4m*>(x0 + ps) * (m0 * mk);
-          p1[u] = *reinterpret_cast<const jf4m*>(x1 + ps) * (m1 * mk);
+          p0[u] = *reinterpret_cast<const jf4m*>(x0 + ps);
+          p1[u] = *reinterpret_cast<const jf4m*>(x1 + ps);
+          msk0[u] = m0 * mk; msk1[u] = m1 * mk;
         }
+        __builtin_amdgcn_sched_barrier(0);  // all 16 loads first: the scheduler would otherwise thread them through the MFMAs, a wait apiece
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { p0[u] *= msk0[u]; p1[u] *= msk1[u]; }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
