@@ -259,6 +259,33 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_group_kernel(const GemmGroup grp
   // Epilogue.  Accumulator register v of lane l in a 32x32 MFMA tile is element
   // (row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32).
   const int ldc = pr.ldc;
+  if (EPI == Epilogue::ApplyW) {
+    // Weight update.  The 16 old weights of a 32 x 32 tile are all read before the first one is written
+    // back: as one read-modify-write per element, every load had to wait for the store before it (the
+    // compiler cannot tell that the addresses differ), 64 memory round trips in a row per thread.  Rows
+    // and columns beyond the matrix are read from its last row / column (in bounds) and not written.
+    T* W = static_cast<T*>(pr.C);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn0 + 32 * j + (lane & 31);
+        const int col_ok = col < N ? col : N - 1;
+        float w_old[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm0 + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          w_old[v] = to_f32(W[(size_t)(row < M ? row : M - 1) * ldc + col_ok]);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the loads first, in one batch
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm0 + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (row < M && col < N) W[(size_t)row * ldc + col] = (T)(pr.s0 * w_old[v] - pr.s1 * acc[i][j][v]);
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
