@@ -686,7 +686,7 @@ __device__ __forceinline__ void wy_slice(int J0, int k, int s, int& p_begin, int
 __global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup* __restrict__ gp, int J0, int col_begin, int col_end,
                                                           int target_is_q) {
   const RefreshGroup& grp = *gp;
-  __shared__ float stage[16 * 256];
+  __shared__ float stage[16 * 4 * 256];  // per wave: its shares of the four 16 x 16 blocks of w
   const RefreshTensor& t = grp.t[blockIdx.z];
   const int k = t.k;
   const float* __restrict__ X = target_is_q ? t.Q : t.Z;
@@ -695,18 +695,60 @@ __global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup* __
   const int c0 = col_begin + kWY * blockIdx.x;
   int p_begin, p_end;
   wy_slice(J0, k, blockIdx.y, p_begin, p_end);
-  // block (I0 target rows, Jb reflectors) over a quarter of the slice per wave
+  // Wave w takes the groups of 16 positions w, w + 16, ... of the slice and, for each, one 16-byte piece
+  // of target rows i and 16 + i and of reflectors i and 16 + i (lane (i = lane % 16, g = lane / 16) supplies
+  // positions 4 g .. 4 g + 3 of the group): four pieces feed the four block products, where a block per
+  // wave over a quarter of the slice loaded two pieces per product, in two batches.  All loads of a batch
+  // (4 groups, the whole share at full slice length) leave before the first MFMA, unconditionally from
+  // clamped addresses; target rows and positions that do not exist are masked to zero afterwards.
   {
-    const int I0 = (wave & 1) * 16, Jb = ((wave >> 1) & 1) * 16, kq = wave >> 2;
     const int i = lane & 15, g = lane >> 4;
-    const int xr = c0 + I0 + i;
-    const bool xok = xr < col_end;
-    const float* arow = X + (size_t)(xok ? xr : col_begin) * k;
-    const float* brow = V + (size_t)(Jb + i) * k;
-    wf4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (p_begin < p_end) acc = gram_partial(arow, xok, brow, true, p_begin, p_end, kq, g);
+    const int xr0 = c0 + i, xr1 = c0 + 16 + i;
+    const bool ok0 = xr0 < col_end, ok1 = xr1 < col_end;
+    const float* x0 = X + (size_t)(ok0 ? xr0 : col_begin) * k;
+    const float* x1 = X + (size_t)(ok1 ? xr1 : col_begin) * k;
+    const float* v0 = V + (size_t)i * k;
+    const float* v1 = V + (size_t)(16 + i) * k;
+    const float m0 = ok0 ? 1.f : 0.f, m1 = ok1 ? 1.f : 0.f;
+    const wf4 zero = {0.f, 0.f, 0.f, 0.f};
+    wf4 a00 = zero, a01 = zero, a10 = zero, a11 = zero;  // a[I][Jb]: target rows 16 I .., reflectors 16 Jb ..
+    const int ngroups = p_begin < p_end ? (p_end - p_begin + 15) >> 4 : 0;
+    for (int S0 = wave; S0 < ngroups; S0 += 4 * 16) {
+      wf4 px0[4], px1[4], pv0[4], pv1[4];
+      float mk[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) stage[wave * 256 + (4 * g + v) * 16 + i] = acc[v];
+      for (int u = 0; u < 4; ++u) {
+        const int pos = p_begin + 16 * (S0 + 16 * u) + 4 * g;
+        const bool ok = pos < p_end;   // slice ends are multiples of 4: a piece is inside or outside as a whole
+        const int ps = ok ? pos : p_begin;
+        mk[u] = ok ? 1.f : 0.f;
+        px0[u] = *reinterpret_cast<const wf4*>(x0 + ps);
+        px1[u] = *reinterpret_cast<const wf4*>(x1 + ps);
+        pv0[u] = *reinterpret_cast<const wf4*>(v0 + ps);
+        pv1[u] = *reinterpret_cast<const wf4*>(v1 + ps);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // all 16 loads first
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        px0[u] *= m0 * mk[u];
+        px1[u] *= m1 * mk[u];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a00 = __builtin_amdgcn_mfma_f32_16x16x4f32(px0[u][e], pv0[u][e], a00, 0, 0, 0);
+          a01 = __builtin_amdgcn_mfma_f32_16x16x4f32(px0[u][e], pv1[u][e], a01, 0, 0, 0);
+          a10 = __builtin_amdgcn_mfma_f32_16x16x4f32(px1[u][e], pv0[u][e], a10, 0, 0, 0);
+          a11 = __builtin_amdgcn_mfma_f32_16x16x4f32(px1[u][e], pv1[u][e], a11, 0, 0, 0);
+        }
+      }
+    }
+    // block index I + 2 Jb, element (row 4 g + v, column i) of the block
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      stage[(wave * 4 + 0) * 256 + (4 * g + v) * 16 + i] = a00[v];
+      stage[(wave * 4 + 1) * 256 + (4 * g + v) * 16 + i] = a10[v];
+      stage[(wave * 4 + 2) * 256 + (4 * g + v) * 16 + i] = a01[v];
+      stage[(wave * 4 + 3) * 256 + (4 * g + v) * 16 + i] = a11[v];
+    }
   }
   __syncthreads();
   {
@@ -714,7 +756,7 @@ __global__ __launch_bounds__(1024) void wy_project_kernel(const RefreshGroup* __
     const int blk = (i >> 4) | ((j >> 4) << 1);
     float sum = 0.f;
 #pragma unroll
-    for (int kq = 0; kq < 4; ++kq) sum += stage[(blk + 4 * kq) * 256 + (i & 15) * 16 + (j & 15)];
+    for (int w = 0; w < 16; ++w) sum += stage[(w * 4 + blk) * 256 + (i & 15) * 16 + (j & 15)];
     t.wpart[((size_t)blockIdx.x * kWYApplySlices + blockIdx.y) * (kWY * kWY) + tid] = sum;  // entry (i, j)
   }
 }
