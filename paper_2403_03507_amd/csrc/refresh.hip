@@ -1124,13 +1124,14 @@ __device__ __forceinline__ void gram_apply_rotation(float* __restrict__ Y, int r
   }
 }
 
-// NW = wavefronts per workgroup.  The work is laid out in 16 shares (one rotation per share and inner
-// round, one Gram entry per thread of 1024); a wavefront takes 16 / NW of them, one after the other, and
-// 16 / NW workgroups fit a CU (<= 128 registers per lane).  The round is a chain of dependent LDS
-// round trips, so fewer wavefronts cost little: per 7B layer set a refresh alone takes 84.0 / 84.2 /
-// 90.6 ms with NW = 16 / 8 / 4, while with three refreshes in flight (the launches of this kernel then
-// outnumber the CUs, and the memory phases of one workgroup overlap with the inner rounds of its
-// neighbours on the CU) it takes 53.3 / 50.8 / 48.9 ms.  Hence 8 alone and 4 when crowded.
+// NW = wavefronts per workgroup.  The work is laid out in 16 shares (two Gram rows per share and inner
+// round, one entry per lane); a wavefront takes 16 / NW of them and 16 / NW workgroups fit a CU (<= 128
+// registers per lane).  An inner round is bound by latency (one LDS round trip, the reciprocal / square
+// root chain, one barrier), so fewer wavefronts cost little.  Measured when an inner round still took
+// two barriers, per 7B layer set: a refresh alone 84.0 / 84.2 / 90.6 ms with NW = 16 / 8 / 4; three
+// refreshes in flight (the launches of this kernel then outnumber the CUs, and the memory phases of one
+// workgroup overlap with the inner rounds of its neighbours on the CU) 53.3 / 50.8 / 48.9 ms.  Hence 8
+// alone and 4 when crowded.
 template <int NW>
 __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(const RefreshGroup* __restrict__ gp, int round, int nplayers, int sweep) {
   const RefreshGroup& grp = *gp;
@@ -1138,9 +1139,8 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
   constexpr int VW = 16 / NW;  // shares ("virtual wavefronts") per wavefront
   __shared__ float Gm[2][R2 * GP];
   __shared__ float Rot[R2 * GP];             // Rot[i][k]: new row i = sum_k Rot[i][k] old row k
-  __shared__ float stage[kGramSlices * 3 * 256];  // per column slice: the partial blocks (0,0), (0,1), (1,1), 16 x 16 each
-  __shared__ float alpha[R2], beta[R2];      // per row: new_row = alpha * row + beta * partner row
-  __shared__ int partner[R2];
+  __shared__ float stage[kGramSlices * 3 * 256];  // per column slice: the partial blocks (0,0), (0,1), (1,1), 16 x 16 each; later the second buffer of Rot
+  static_assert(kGramSlices * 3 * 256 >= R2 * GP, "the staging area doubles as the second rotation buffer");
   __shared__ int rotated;      // some rotation was applied: Bw and Jt have to be updated
   __shared__ int significant;  // some rotation was above the stopping level: another sweep is due
   const RefreshTensor& t = grp.t[blockIdx.y];
@@ -1231,64 +1231,87 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
   }
   __syncthreads();
 
-  // 2. inner sweeps on the Gram matrix
+  // 2. inner sweeps on the Gram matrix.  One barrier and one LDS round trip per inner round: the pairing
+  // of a round is arithmetic (mate()), so every lane derives the rotation of the pair that holds its
+  // column j from three Gram entries by itself (the 32 columns of a wavefront cover all 16 pairs; the
+  // lanes of a pair read the same entries in the same order, so they agree to the bit), the two rows a
+  // wavefront updates per share take theirs from the lanes whose column has that number, and G and the
+  // accumulated rotation are both updated entry by entry from one buffer into the other.
   int cur = 0;
   // Round 0 of a sweep pairs every block exactly once: there the inner sweep covers all pairs of the
   // 32 rows (31 rounds), which also rotates the pairs INSIDE each block once per sweep.  The other
   // rounds only need the 16 x 16 pairs between the two blocks: 16 rounds of (i, 16 + (i + ir) % 16).
-  const bool all_pairs = round == 0;
-  const int inner_rounds = all_pairs ? R2 - 1 : B;
+  const int j = lane & 31;
+  const unsigned exist = (unsigned)__ballot(grow(lane & 31) >= 0);  // bit x: local row x exists
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const bool upper = lane >= 32;
+  // the two pairings are compiled apart (the choice is uniform), so each inner loop carries only its own index arithmetic
+  auto inner_sweeps = [&](auto all_pairs_t) {
+  constexpr bool all_pairs = decltype(all_pairs_t)::value;
+  constexpr int inner_rounds = all_pairs ? R2 - 1 : B;
   for (int isw = 0; isw < kGramInnerSweeps; ++isw)
     for (int ir = 0; ir < inner_rounds; ++ir) {
-      // phase A: every (virtual) wave derives the rotation of its pair
       const float* G = Gm[cur];
-#pragma unroll
-      for (int sh = 0; sh < VW; ++sh) {
-      const int vw = wave + NW * sh;
-      int p, q;
-      if (all_pairs) {
-        if (vw == 0) { p = R2 - 1; q = ir; }
-        else { p = (ir + vw) % (R2 - 1); q = (ir + (R2 - 1) - vw) % (R2 - 1); }
-        if (p > q) { const int x = p; p = q; q = x; }
-      } else {
-        p = vw; q = B + ((vw + ir) & (B - 1));
-      }
+      float* Gn = Gm[cur ^ 1];
+      const float* Rc = cur ? stage : Rot;   // the staging area of the Gram phase is free by now
+      float* Rn = cur ? Rot : stage;
+      // the row that row x is paired with in this inner round (selects only: no divergent branches)
+      auto mate = [&](int x) {
+        // round robin of 32 players: row 31 stays, rows with p + q = 2 ir (mod 31) meet
+        int y = 2 * ir - x;
+        y += y < 0 ? R2 - 1 : 0;
+        y -= y >= R2 - 1 ? R2 - 1 : 0;
+        y = x == ir ? R2 - 1 : y;
+        y = x == R2 - 1 ? ir : y;
+        const int z = x < B ? B + ((x + ir) & (B - 1)) : ((x - B - ir) & (B - 1));
+        if constexpr (all_pairs) return y;
+        else return z;
+      };
+      const int pj = mate(j);
+      const int p = j < pj ? j : pj, q = j < pj ? pj : j;
+      // every LDS read of the round is issued here, ahead of the arithmetic: one round trip
       const float a = G[p * GP + p], bb = G[q * GP + q], c = G[p * GP + q];
-      const bool rot = grow(p) >= 0 && grow(q) >= 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
-      float cs = 1.f, sn = 0.f;
-      if (rot) {
-        // hardware reciprocal / square-root approximations (1 ulp): a rotation with c^2 + s^2 = 1 to
-        // within a few ulps is all that is needed, and this chain is the latency of every inner round
-        const float zeta = (bb - a) * __builtin_amdgcn_rcpf(2.f * c);
-        const float tt = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-        cs = __builtin_amdgcn_rsqf(1.f + tt * tt);
-        sn = cs * tt;
-      }
-      if (lane == 0) {
-        alpha[p] = cs; beta[p] = -sn; partner[p] = q;
-        alpha[q] = cs; beta[q] = sn;  partner[q] = p;
-        if (rot) rotated = 1;
-        if (rot && c * c > (kJacobiStopTol * kJacobiStopTol) * a * bb) significant = 1;
-      }
-      if (rot && lane < R2) {  // rows p, q of the accumulated rotation (only this wave touches them)
-        const float uu = Rot[p * GP + lane], vv = Rot[q * GP + lane];
-        Rot[p * GP + lane] = cs * uu - sn * vv;
-        Rot[q * GP + lane] = sn * uu + cs * vv;
-      }
-      }
-      __syncthreads();
-      // phase B: G <- J^T G J for the 16 disjoint rotations of this round
+      float gij[VW], gipj[VW], gpij[VW], gpipj[VW], rij[VW], rpij[VW];
 #pragma unroll
       for (int sh = 0; sh < VW; ++sh) {
-        const int vt = tid + 64 * NW * sh;
-        const int i = vt >> 5, j = vt & 31;
-        const int pi = partner[i], pj = partner[j];
-        const float ai = alpha[i], bi2 = beta[i], aj = alpha[j], bj2 = beta[j];
-        Gm[cur ^ 1][i * GP + j] = ai * (aj * G[i * GP + j] + bj2 * G[i * GP + pj]) + bi2 * (aj * G[pi * GP + j] + bj2 * G[pi * GP + pj]);
+        const int i = 2 * (wave_u + NW * sh) + (upper ? 1 : 0);  // lanes 0 .. 31 update row i0, lanes 32 .. 63 row i0 + 1
+        const int pi = mate(i);
+        gij[sh] = G[i * GP + j]; gipj[sh] = G[i * GP + pj]; gpij[sh] = G[pi * GP + j]; gpipj[sh] = G[pi * GP + pj];
+        rij[sh] = Rc[i * GP + j]; rpij[sh] = Rc[pi * GP + j];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      const bool rot = ((exist >> p) & (exist >> q) & 1u) != 0 && a > 0.f && bb > 0.f && c * c > (kJacobiTol * kJacobiTol) * a * bb;
+      // hardware reciprocal / square-root approximations (1 ulp): a rotation with c^2 + s^2 = 1 to
+      // within a few ulps is all that is needed, and this chain is the latency of every inner round.
+      // Computed by every lane and selected afterwards (a pair that is not rotated may divide by zero).
+      const float zeta = (bb - a) * __builtin_amdgcn_rcpf(2.f * c);
+      const float tt = copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+      const float cs0 = __builtin_amdgcn_rsqf(1.f + tt * tt);
+      const float cs = rot ? cs0 : 1.f, sn = rot ? cs0 * tt : 0.f;
+      // new row x = alpha_x * row x + beta_x * row mate(x): (cs, -sn) for the lower row of a pair, (cs, sn) for the upper
+      const float aj = cs, bj2 = j == p ? -sn : sn;
+      if (wave == 0 && rot) {  // same value from every lane that writes
+        rotated = 1;
+        if (c * c > (kJacobiStopTol * kJacobiStopTol) * a * bb) significant = 1;
+      }
+#pragma unroll
+      for (int sh = 0; sh < VW; ++sh) {
+        const int i0 = 2 * (wave_u + NW * sh);
+        const float al0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aj), i0));
+        const float al1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aj), i0 + 1));
+        const float be0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bj2), i0));
+        const float be1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bj2), i0 + 1));
+        const int i = i0 + (upper ? 1 : 0);
+        const float ai = upper ? al1 : al0, bi2 = upper ? be1 : be0;
+        Gn[i * GP + j] = ai * (aj * gij[sh] + bj2 * gipj[sh]) + bi2 * (aj * gpij[sh] + bj2 * gpipj[sh]);
+        Rn[i * GP + j] = ai * rij[sh] + bi2 * rpij[sh];
       }
       __syncthreads();
       cur ^= 1;
     }
+  };
+  if (round == 0) inner_sweeps(std::true_type{});
+  else inner_sweeps(std::false_type{});
 
   if (rotated == 0) return;  // nothing changed: leave Bw, Jt and the sweep flag alone (uniform)
   if (tid == 0 && significant) t.sweep_flag[sweep] = 1;  // idempotent plain store, no atomics
@@ -1296,12 +1319,13 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void jacobi_gram_round_kernel(con
   // 3. apply the accumulated rotation to the rows of Bw and of Jt
   {
     const int i = lane & 15, g = lane >> 4;
+    const float* Rf = cur ? stage : Rot;
     float rot[2][8];
     int rows[8], out_rows[2][4];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int sidx = 0; sidx < 8; ++sidx) rot[h][sidx] = Rot[(16 * h + i) * GP + 4 * sidx + g];
+      for (int sidx = 0; sidx < 8; ++sidx) rot[h][sidx] = Rf[(16 * h + i) * GP + 4 * sidx + g];
 #pragma unroll
     for (int sidx = 0; sidx < 8; ++sidx) rows[sidx] = grow(4 * sidx + g);
 #pragma unroll
