@@ -125,8 +125,10 @@ typedef struct galore_ctx galore_ctx; /* opaque; OWNED by the library; host memo
 const char* galore_status_string(galore_status s);
 
 /* Workspace, in bytes, that lets one call process up to 8 consecutive tensors of the
- * list per kernel launch (transients R and N of the step; Gram matrix, iteration blocks
- * and reflector storage of the refresh).  Any 256-byte-aligned workspace at least as
+ * list per kernel launch (transients R and N of the step, plus, for a bf16 tensor with
+ * rows <= cols, rows a multiple of 64 and cols not a multiple of 8, a copy of G with its rows
+ * padded to a multiple of 8 elements, which the projection then reads instead of G; Gram
+ * matrix, iteration blocks and reflector storage of the refresh).  Any 256-byte-aligned workspace at least as
  * large as the largest single-tensor need is accepted by galore_init; a smaller one
  * only means more, smaller launches.  No device access. */
 galore_status galore_workspace_bytes(const galore_hparams* hp, const galore_tensor* W,

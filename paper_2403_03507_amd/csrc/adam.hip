@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
   constexpr int VEC = 16 / sizeof(TN);          // N elements per 16 bytes
   __shared__ __align__(16) TN tile[TS][TS + VEC];  // tile[j][i] = N[i][j]
   const AdamProblem& pr = grp.p[blockIdx.y];
-  const int rows = pr.rows, cols = pr.cols;
+  const int rows = pr.rows, cols = pr.cols, ldr = pr.ldr;
   const int tiles_c = (cols + TS - 1) / TS;
   const int ntiles = tiles_c * ((rows + TS - 1) / TS);
   const float beta1 = grp.beta1, beta2 = grp.beta2, eps = grp.eps;
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
   float* __restrict__ M = pr.M;
   float* __restrict__ V = pr.V;
   TN* __restrict__ N = static_cast<TN*>(pr.N);
-  const bool cols4 = cols % 4 == 0 && ((reinterpret_cast<uintptr_t>(R) | reinterpret_cast<uintptr_t>(M) | reinterpret_cast<uintptr_t>(V)) & 15) == 0;
+  const bool cols4 = cols % 4 == 0 && ldr % 4 == 0 && ((reinterpret_cast<uintptr_t>(R) | reinterpret_cast<uintptr_t>(M) | reinterpret_cast<uintptr_t>(V)) & 15) == 0;
   const bool aligned = rows % VEC == 0;  // rows of N^T stay 16-byte aligned; R, M, V rows may be of any length
   for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
     const int i0 = (t / tiles_c) * TS, j0 = (t % tiles_c) * TS;
@@ -99,13 +99,14 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
       for (int ps = 0; ps < 4; ++ps) {
         const int i = ps * 16 + (threadIdx.x >> 4), j = (threadIdx.x & 15) * 4;
         const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
+        const size_t ridx = (size_t)(i0 + i) * ldr + j0 + j;
         f32x4 g, m, v;
         if (cols4) {
-          g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + idx));
+          g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + ridx));
           m = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(M + idx));
           v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(V + idx));
         } else {
-          g = load4(R + idx); m = load4(M + idx); v = load4(V + idx);
+          g = load4(R + ridx); m = load4(M + idx); v = load4(V + idx);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
         if (i0 + i < rows && j0 + j < cols) {
           const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
           float me = M[idx], ve = V[idx];
-          const float n = adam_entry(R[idx], me, ve, beta1, beta2, eps, ic1, ic2);
+          const float n = adam_entry(R[(size_t)(i0 + i) * ldr + j0 + j], me, ve, beta1, beta2, eps, ic1, ic2);
           M[idx] = me; V[idx] = ve;
           N[(size_t)(j0 + j) * rows + i0 + i] = (TN)n;
         }
@@ -148,6 +149,8 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
 hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stream) {
   if (g.count <= 0) return hipSuccess;
   if (g.count > kMaxGroup) return hipErrorInvalidValue;
+  for (int i = 0; i < g.count; ++i)  // padded rows of R are a feature of the transposing kernel only
+    if (g.p[i].ldr < g.p[i].cols || (!g.p[0].transpose_n && g.p[i].ldr != g.p[i].cols)) return hipErrorInvalidValue;
   if (g.p[0].transpose_n) {
     int64_t maxtiles = 0;
     for (int i = 0; i < g.count; ++i) {
@@ -170,6 +173,50 @@ hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stre
   dim3 grid((unsigned)blocks, (unsigned)g.count);
   if (n_dtype == DType::BF16) hipLaunchKernelGGL(adam_group_kernel<__bf16>, grid, dim3(256), 0, stream, g);
   else hipLaunchKernelGGL(adam_group_kernel<float>, grid, dim3(256), 0, stream, g);
+  return hipGetLastError();
+}
+
+// One aligned 16-byte piece of dst per thread and trip; the source piece is read with whatever
+// alignment its row has (memcpy lets the compiler pick the widest access the target allows there).
+__global__ __launch_bounds__(256) void pad_rows_kernel(const PadGroup grp) {
+  const PadProblem& pr = grp.p[blockIdx.y];
+  const __bf16* __restrict__ src = static_cast<const __bf16*>(pr.src);
+  __bf16* __restrict__ dst = static_cast<__bf16*>(pr.dst);
+  const int cols = pr.cols, cpr = pr.ldd / 8;  // pieces per row
+  const int64_t pieces = (int64_t)pr.rows * cpr;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < pieces; c += stride) {
+    const int64_t row = c / cpr;
+    const int col = (int)(c % cpr) * 8;
+    const __bf16* s = src + row * pr.lds + col;
+    uint4 v;
+    if (col + 8 <= cols) {
+      __builtin_memcpy(&v, s, sizeof(uint4));
+    } else {
+      __bf16 tmp[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tmp[e] = col + e < cols ? s[e] : (__bf16)0.f;
+      __builtin_memcpy(&v, tmp, sizeof(uint4));
+    }
+    *reinterpret_cast<uint4*>(dst + row * pr.ldd + col) = v;
+  }
+}
+
+hipError_t launch_pad_rows_group(const PadGroup& g, hipStream_t stream) {
+  if (g.count <= 0) return hipSuccess;
+  if (g.count > kMaxGroup) return hipErrorInvalidValue;
+  int64_t most = 0;
+  for (int i = 0; i < g.count; ++i) {
+    const PadProblem& p = g.p[i];
+    if (p.rows < 1 || p.cols < 1 || p.ldd < p.cols || p.ldd % 8 != 0 || p.lds < p.cols || (reinterpret_cast<uintptr_t>(p.dst) & 15))
+      return hipErrorInvalidValue;
+    const int64_t pieces = (int64_t)p.rows * (p.ldd / 8);
+    most = pieces > most ? pieces : most;
+  }
+  int64_t blocks = (most + 256 * 4 - 1) / (256 * 4);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)blocks, (unsigned)g.count), dim3(256), 0, stream, g);
   return hipGetLastError();
 }
 

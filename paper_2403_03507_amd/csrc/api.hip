@@ -86,12 +86,29 @@ galore_status fail(galore_ctx* ctx, galore_status s, const char* fmt, ...) {
 
 bool valid_dtype(int32_t d, bool allow_u8) { return d == GALORE_F32 || d == GALORE_BF16 || (allow_u8 && d == GALORE_U8); }
 
-size_t step_need(int64_t ldim, int64_t r, DType dt) {
-  return align_up((size_t)r * ldim * 4) + align_up((size_t)r * ldim * dtype_size(dt));
+// The large-tile GEMM moves aligned 16-byte pieces, so G of a LEFT bf16 tensor (contiguous along n, the
+// GEMM's N index) cannot feed it when n is not a multiple of 8: its rows start at odd element offsets.
+// The projection of such a tensor reads a copy of G with the rows padded to a multiple of 8 (zeros) and
+// writes R with the same padded row length; the copy costs one pass over G and buys the 256 x 256 tiles.
+// Returns the row length of R: ldim itself when nothing is padded.
+int64_t projected_row_length(bool left, int64_t kdim, int64_t ldim, DType dt) {
+  const bool pad = left && dt == DType::BF16 && ldim % 8 != 0 && ldim >= 8 && kdim % 64 == 0;
+  return pad ? (ldim + 7) / 8 * 8 : ldim;
+}
+size_t step_r_bytes(bool left, int64_t kdim, int64_t ldim, int64_t r, DType dt) {
+  return align_up((size_t)r * projected_row_length(left, kdim, ldim, dt) * 4);
+}
+size_t step_n_bytes(int64_t ldim, int64_t r, DType dt) { return align_up((size_t)r * ldim * dtype_size(dt)); }
+size_t step_gpad_bytes(bool left, int64_t kdim, int64_t ldim, DType dt) {
+  const int64_t ldp = projected_row_length(left, kdim, ldim, dt);
+  return ldp == ldim ? 0 : align_up((size_t)kdim * ldp * dtype_size(dt));
+}
+size_t step_need(bool left, int64_t kdim, int64_t ldim, int64_t r, DType dt) {
+  return step_r_bytes(left, kdim, ldim, r, dt) + step_n_bytes(ldim, r, dt) + step_gpad_bytes(left, kdim, ldim, dt);
 }
 
-size_t tensor_need(const galore_hparams& hp, int64_t kdim, int64_t ldim, DType dt) {
-  const size_t a = step_need(ldim, hp.rank, dt);
+size_t tensor_need(const galore_hparams& hp, bool left, int64_t kdim, int64_t ldim, DType dt) {
+  const size_t a = step_need(left, kdim, ldim, hp.rank, dt);
   const size_t b = refresh_workspace_bytes(kdim, hp.rank);
   return a > b ? a : b;
 }
@@ -166,6 +183,8 @@ struct StepItem {
   const galore_tensor* G;
   float* R;
   void* N;
+  void* Gpad;    // copy of G with padded rows (see projected_row_length), or nullptr
+  int64_t ldr;   // row length of R
 };
 
 galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, float lr, hipStream_t stream) {
@@ -194,11 +213,21 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
     // contiguous along the contraction index; only G of a LEFT tensor is not.
     for (int left = 1; left >= 0; --left) {
       GemmGroup g{};
+      PadGroup pads{};
       for (const StepItem& it : items) {
         const TensorInfo& ti = ctx->tensors[it.tensor];
         if (ti.dt != dt || (int)ti.left != left) continue;
         GemmProblem& p = g.p[g.count++];
-        if (left) {  // R (r x n) = P^T G : A = proj_t as [M=r][K=m], B = G as [K=m][N=n]
+        if (left && it.Gpad) {  // the same product on the padded copy: the extra columns of G and of R are zero
+          PadProblem& q = pads.p[pads.count++];
+          q.src = it.G->data; q.lds = (int)it.G->ld;
+          q.dst = it.Gpad; q.ldd = (int)it.ldr;
+          q.rows = (int)ti.rows; q.cols = (int)ti.cols;
+          p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
+          p.B = it.Gpad; p.ldb = (int)it.ldr;
+          p.M = r; p.N = (int)it.ldr; p.K = (int)ti.rows;
+          p.C = it.R; p.ldc = (int)it.ldr;
+        } else if (left) {  // R (r x n) = P^T G : A = proj_t as [M=r][K=m], B = G as [K=m][N=n]
           p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
           p.B = it.G->data; p.ldb = (int)it.G->ld;
           p.M = r; p.N = (int)ti.cols; p.K = (int)ti.rows;
@@ -211,7 +240,9 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
         }
       }
       ProfScope prof(ctx, left ? GALORE_STAGE_PROJECT_LEFT : GALORE_STAGE_PROJECT_RIGHT, g.count > 0, stream);
-      hipError_t e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::StoreF32, stream);
+      hipError_t e = launch_pad_rows_group(pads, stream);
+      if (e != hipSuccess) return hip_fail(ctx, e, "row padding launch");
+      e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::StoreF32, stream);
       if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
     }
     // K2: Adam on R.  N always leaves as (long side) x r: transposed for LEFT tensors.
@@ -246,6 +277,7 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
         p.N = it.N;
         p.rows = left ? r : (int)ti.rows;
         p.cols = left ? (int)ti.cols : r;
+        p.ldr = left ? (int)it.ldr : r;
         p.count = (int64_t)r * ti.ldim;
         p.transpose_n = left;
         p.inv_c1 = ic1;
@@ -313,7 +345,7 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
   size_t need = 0;
   for (const StepItem& it : items) {
     const TensorInfo& ti = ctx->tensors[it.tensor];
-    need += align_up((size_t)r * ti.ldim * 4) + align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+    need += step_need(ti.left, ti.kdim, ti.ldim, r, ti.dt);
   }
   const bool overlap = ctx->overlap_calls && library_streams_ready(ctx) && need <= workspace_share(ctx);
   if (ctx->unjoined) {
@@ -330,9 +362,13 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
   for (StepItem& it : items) {
     const TensorInfo& ti = ctx->tensors[it.tensor];
     it.R = reinterpret_cast<float*>(ctx->ws + off);
-    off += align_up((size_t)r * ti.ldim * 4);
+    off += step_r_bytes(ti.left, ti.kdim, ti.ldim, r, ti.dt);
     it.N = ctx->ws + off;
-    off += align_up((size_t)r * ti.ldim * dtype_size(ti.dt));
+    off += step_n_bytes(ti.ldim, r, ti.dt);
+    const size_t gp = step_gpad_bytes(ti.left, ti.kdim, ti.ldim, ti.dt);
+    it.Gpad = gp ? ctx->ws + off : nullptr;
+    off += gp;
+    it.ldr = projected_row_length(ti.left, ti.kdim, ti.ldim, ti.dt);
   }
   if (overlap) {
     const int h = ctx->parity;
@@ -470,7 +506,7 @@ galore_status galore_workspace_bytes(const galore_hparams* hp, const galore_tens
     s = check_weight_shape(nullptr, *hp, W[i], i);
     if (s) return s;
     const bool left = W[i].rows <= W[i].cols;
-    need[i] = tensor_need(*hp, left ? W[i].rows : W[i].cols, left ? W[i].cols : W[i].rows, (DType)W[i].dtype);
+    need[i] = tensor_need(*hp, left, left ? W[i].rows : W[i].cols, left ? W[i].cols : W[i].rows, (DType)W[i].dtype);
   }
   size_t best = 0;
   for (int i = 0; i < n_tensors; ++i) {
@@ -547,9 +583,9 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
           return fail(nullptr, GALORE_ERR_SHAPE, "S[%d] moment scales must be dense %lld x %lld", i, (long long)mr, (long long)(mc / 256));
       }
     }
-    if (tensor_need(*hp, ti.kdim, ti.ldim, ti.dt) > workspace_bytes)
+    if (tensor_need(*hp, ti.left, ti.kdim, ti.ldim, ti.dt) > workspace_bytes)
       return fail(nullptr, GALORE_ERR_WORKSPACE, "workspace of %zu bytes cannot hold tensor %d (needs %zu)", workspace_bytes,
-                  i, tensor_need(*hp, ti.kdim, ti.ldim, ti.dt));
+                  i, tensor_need(*hp, ti.left, ti.kdim, ti.ldim, ti.dt));
   }
 
   galore_ctx* ctx = new (std::nothrow) galore_ctx;
@@ -647,9 +683,9 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
     size_t used = 0;
     while (pos < count && (int)items.size() < kMaxGroup) {
       const TensorInfo& ti = ctx->tensors[first + pos];
-      const size_t need = step_need(ti.ldim, ctx->hp.rank, ti.dt);
+      const size_t need = step_need(ti.left, ti.kdim, ti.ldim, ctx->hp.rank, ti.dt);
       if (!items.empty() && used + need > limit) break;
-      items.push_back(StepItem{first + pos, &W[pos], &G[pos], nullptr, nullptr});
+      items.push_back(StepItem{first + pos, &W[pos], &G[pos], nullptr, nullptr, nullptr, ti.ldim});
       used += need;
       ++pos;
     }
@@ -840,7 +876,7 @@ galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const 
   AdamProblem& p = g.p[0];
   p.R = static_cast<const float*>(R->data); p.M = static_cast<float*>(M->data); p.V = static_cast<float*>(V->data);
   p.N = N->data; p.count = R->rows * R->cols;
-  p.rows = (int)R->rows; p.cols = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
+  p.rows = (int)R->rows; p.cols = (int)R->cols; p.ldr = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
   p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
   p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
   hipError_t e = launch_adam_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
@@ -1056,7 +1092,7 @@ galore_status galore_two_sided_step(const galore_hparams* hp, const galore_tenso
     p.M = static_cast<float*>(S->m.data);
     p.V = static_cast<float*>(S->v.data);
     p.N = ws + L.nn;
-    p.rows = r; p.cols = r; p.count = (int64_t)r * r;
+    p.rows = r; p.cols = r; p.ldr = r; p.count = (int64_t)r * r;
     p.transpose_n = 0;
     p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, k)));
     p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, k)));

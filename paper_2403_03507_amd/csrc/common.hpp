@@ -54,8 +54,9 @@ struct AdamProblem {
   float* V;
   void* N;        // fp32 or bf16
   int64_t count;  // rows * cols
-  int32_t rows;   // shape of R, M, V (dense, row-major)
+  int32_t rows;   // shape of R, M, V (M, V dense, row-major)
   int32_t cols;
+  int32_t ldr;    // row stride of R, >= cols (only the transposing kernel takes R with padded rows; else ldr == cols)
   int32_t transpose_n;  // 0: N has R's layout; 1: N is stored transposed (cols x rows)
   float inv_c1;   // 1 / (1 - beta1^k)
   float inv_c2;   // 1 / (1 - beta2^k)
@@ -108,6 +109,19 @@ struct TransposeGroup {
   TransposeProblem p[kMaxGroup];
 };
 hipError_t launch_transpose_group(const TransposeGroup& g, DType dt, hipStream_t stream);
+
+// ---- grouped row padding (bf16): dst (rows x ldd, 16-byte aligned, ldd % 8 == 0) <- src (rows x cols, any
+// row stride and element alignment), columns cols .. ldd - 1 zero ------------------------------
+struct PadProblem {
+  const void* src;
+  void* dst;
+  int32_t rows, cols, lds, ldd;
+};
+struct PadGroup {
+  int32_t count;
+  PadProblem p[kMaxGroup];
+};
+hipError_t launch_pad_rows_group(const PadGroup& g, hipStream_t stream);
 
 // ---- small utilities -----------------------------------------------------------------------
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);

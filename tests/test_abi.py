@@ -50,6 +50,22 @@ def _status(fn, *a, **k):
     return e.value.status
 
 
+def test_workspace_bytes_counts_the_padded_gradient_copy():
+    # a bf16 tensor with rows <= cols, rows % 64 == 0 and cols % 8 != 0 is projected from a copy of G
+    # whose rows are padded to a multiple of 8: the step then needs R (r x 100008 fp32), N (r x 100003 bf16)
+    # and the copy (64 x 100008 bf16); the same shape in fp32, transposed, with rows % 64 != 0 or with
+    # cols % 8 == 0 needs no copy.  (Short, very wide tensors: there the step's need exceeds the refresh's.)
+    hp = _hp(rank=8, refresh_iters=1)
+    al = lambda x: (x + 255) // 256 * 256
+    step = lambda m, n, pad, esz: al(8 * (pad if pad else n) * 4) + al(8 * n * esz) + (al(m * pad * esz) if pad else 0)
+    ws = lambda m, n, dt: gb.galore_workspace_bytes(hp, [gb.shape_desc(m, n, dt)])
+    assert ws(64, 100003, torch.bfloat16) == step(64, 100003, 100008, 2)
+    assert ws(64, 100008, torch.bfloat16) == step(64, 100008, 0, 2)
+    assert ws(64, 100003, torch.float32) == step(64, 100003, 0, 4)
+    assert ws(100003, 64, torch.bfloat16) == step(64, 100003, 0, 2)
+    assert ws(72, 100003, torch.bfloat16) == step(72, 100003, 0, 2)
+
+
 def test_workspace_bytes_formula_and_errors():
     w = [gb.shape_desc(8, 16, torch.float32)]
     need = gb.galore_workspace_bytes(_hp(rank=4), w)

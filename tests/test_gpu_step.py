@@ -88,6 +88,16 @@ def test_ragged_and_odd_shapes():
     _run_stack(shapes, "f32", 33, steps=3, update_gap=2)
 
 
+def test_left_tensors_with_odd_row_length_are_projected_from_a_padded_copy():
+    # bf16, rows <= cols, rows % 64 == 0, cols % 8 != 0 (the 1B stack's 2048 x 5461): the projection reads
+    # a copy of G with rows padded to a multiple of 8 and writes R with padded rows; W, M, V must not notice.
+    # 1021 columns span several 256-wide tiles and a ragged last one; the (128, 128) tensor shares the launches.
+    shapes = [(128, 333), (64, 1021), (192, 523), (128, 128), (64, 65)]
+    _run_stack(shapes, "bf16", 32, steps=3, update_gap=2)
+    # the same with one call per tensor
+    _run_stack(shapes, "bf16", 32, steps=2, update_gap=2, chunked=True)
+
+
 def test_identity_projector_is_scaled_adam_on_device():
     # r = m, P = I: the device trajectory must equal plain Adam with step lr*alpha (library Adam, fp64).
     m, n = 64, 192
