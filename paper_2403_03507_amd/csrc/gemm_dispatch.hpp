@@ -18,14 +18,17 @@ using CfgDl = DlCfg<256, 256, 64, 2, 4, 2>;  // 8 waves of 128 x 64, two 64 KB s
 // problems apart), so one odd-shaped tensor does not drag its whole group onto the slow path.
 template <class T, bool AK, bool BKC, Epilogue EPI>
 inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
-  GemmGroup dl{}, al{}, un{};
+  GemmGroup dl{}, dlw{}, al{}, un{};  // dlw: weight updates whose W has an odd row length or alignment
   for (int i = 0; i < g.count; ++i) {
     GemmGroup one{};
     one.count = 1;
     one.p[0] = g.p[i];
-    bool to_dl = false;
-    if constexpr (std::is_same<T, __bf16>::value) to_dl = group_fits_dl(one, AK, BKC, EPI, CfgDl::BK);
-    GemmGroup& dst = to_dl ? dl : (group_is_aligned<T>(one, AK, BKC) ? al : un);
+    bool to_dl = false, to_dlw = false;
+    if constexpr (std::is_same<T, __bf16>::value) {
+      to_dl = group_fits_dl(one, AK, BKC, EPI, CfgDl::BK);
+      if constexpr (EPI == Epilogue::ApplyW && BKC) to_dlw = !to_dl && group_fits_dl(one, AK, BKC, EPI, CfgDl::BK, true);
+    }
+    GemmGroup& dst = to_dl ? dl : to_dlw ? dlw : (group_is_aligned<T>(one, AK, BKC) ? al : un);
     dst.p[dst.count++] = g.p[i];
   }
   if constexpr (std::is_same<T, __bf16>::value) {
@@ -34,6 +37,15 @@ inline hipError_t launch_gemm_layout(GemmGroup& g, hipStream_t stream) {
       if (dl.total_tiles > 0) {
         hipError_t e = launch_gemm_dl_instance<AK, BKC, EPI, CfgDl>(dl, stream);
         if (e != hipSuccess) return e;
+      }
+    }
+    if constexpr (EPI == Epilogue::ApplyW && BKC) {
+      if (dlw.count > 0) {
+        plan_tiles<CfgDl>(dlw);
+        if (dlw.total_tiles > 0) {
+          hipError_t e = launch_gemm_dl_instance<AK, BKC, EPI, CfgDl, true>(dlw, stream);
+          if (e != hipSuccess) return e;
+        }
       }
     }
   }

@@ -127,8 +127,12 @@ struct DlTile {
 // the current tile is multiplied, so its latency (and the whole epilogue) hides behind MFMAs and
 // stores, and no workgroup launch sits between two tiles.  The epilogue parks 8-row strips of the
 // accumulators in a wave-private LDS area OUTSIDE the ring, so it never waits for the ring.
-template <bool AK, bool BKC, Epilogue EPI, class Cfg>
+// W_ANY (weight update only): the output may have any row length, leading dimension and element
+// alignment.  Its 16-byte pieces are then read and written at element alignment, and the piece that
+// straddles the end of a row is updated element by element.
+template <bool AK, bool BKC, Epilogue EPI, class Cfg, bool W_ANY = false>
 __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
+  static_assert(!W_ANY || EPI == Epilogue::ApplyW, "W_ANY is a variant of the weight update");
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, S = Cfg::STAGES;
   constexpr int TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
   using AOp = DlOperand<AK, BM, BK, NW>;
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
     constexpr int W_EARLY = (TM / 2) * 4 * PASSES;  // load instructions of the first half
     auto fetch_w = [&](int i_begin, int i_end) {
       const __bf16* W = static_cast<const __bf16*>(pr.C);
-      const int colc = col < N ? col : 0;
+      const int colc = (W_ANY ? col + 8 <= N : col < N) ? col : 0;  // W_ANY: whole pieces only (a row holds at least 8 elements)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
         if (i >= i_begin && i < i_end) {
@@ -268,8 +272,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
               const int row = row0 + 32 * i + 8 * q + RPP * ps;
               // W is read once and written once per step: non-temporal accesses keep it from
               // displacing the operand panels that the XCD's other workgroups still need in L2
-              wpre[i][q][ps] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(
-                                   W + (size_t)(row < M ? row : M - 1) * ldc + colc)));
+              const __bf16* wsrc = W + (size_t)(row < M ? row : M - 1) * ldc + colc;
+              if (W_ANY) __builtin_memcpy(&wpre[i][q][ps], wsrc, sizeof(bf16x8));  // element-aligned; still one load instruction
+              else wpre[i][q][ps] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(wsrc)));
             }
         }
     };
@@ -383,13 +388,21 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
           if (row >= M || col >= N) continue;
           if (EPI == Epilogue::ApplyW) {
             __bf16* W = static_cast<__bf16*>(pr.C);
+            __bf16* wdst = W + (size_t)row * ldc + col;
+            if (W_ANY && col + 8 > N) {  // the piece that straddles the end of the row: its old weights were not prefetched
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (col + e < N) wdst[e] = (__bf16)(pr.s0 * (float)wdst[e] - pr.s1 * (e < 4 ? lo[e & 3] : hi[e & 3]));
+              continue;
+            }
             bf16x8 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               o[e] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e] - pr.s1 * lo[e]);
               o[e + 4] = (__bf16)(pr.s0 * (float)wpre[i][q][ps][e + 4] - pr.s1 * hi[e]);
             }
-            __builtin_nontemporal_store(__builtin_bit_cast(i32x4, o), reinterpret_cast<i32x4*>(W + (size_t)row * ldc + col));
+            if (W_ANY) __builtin_memcpy(wdst, &o, sizeof(bf16x8));
+            else __builtin_nontemporal_store(__builtin_bit_cast(i32x4, o), reinterpret_cast<i32x4*>(wdst));
           } else {
             float* C = static_cast<float*>(pr.C);
             float* dst = C + (size_t)row * ldc + col;
@@ -427,14 +440,14 @@ inline int dl_grid_size(int total_tiles) {
   return want < cus ? want : cus;
 }
 
-template <bool AK, bool BKC, Epilogue EPI, class Cfg>
+template <bool AK, bool BKC, Epilogue EPI, class Cfg, bool W_ANY = false>
 inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream) {
   using AOp = DlOperand<AK, Cfg::BM, Cfg::BK, Cfg::NW>;
   using BOp = DlOperand<BKC, Cfg::BN, Cfg::BK, Cfg::NW>;
   constexpr size_t smem = (size_t)Cfg::STAGES * (AOp::TILE_BYTES + BOp::TILE_BYTES) +
                           (size_t)Cfg::NW * 8 * (Cfg::WN + 8) * sizeof(float);  // tile ring + epilogue strips
   static_assert(smem <= 160 * 1024, "tile ring and strips do not fit the 160 KB LDS");
-  auto kern = gemm_dl_kernel<AK, BKC, EPI, Cfg>;
+  auto kern = gemm_dl_kernel<AK, BKC, EPI, Cfg, W_ANY>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -449,14 +462,17 @@ inline hipError_t launch_gemm_dl_instance(const GemmGroup& g, hipStream_t stream
 // The direct-load kernel needs 16-byte alignment of both operands and of the output (its
 // epilogue moves 8 consecutive columns per lane), K a multiple of 64, N a multiple of 8, and at
 // least 8 valid elements along each M/N index (for the edge clamp).
-inline bool group_fits_dl(const GemmGroup& g, bool ak, bool bk, Epilogue epi, int bk_step = 64) {
+// With w_any (the weight update with B contiguous along K: no operand is cut into pieces along N)
+// the output may have any row length, leading dimension and element alignment.
+inline bool group_fits_dl(const GemmGroup& g, bool ak, bool bk, Epilogue epi, int bk_step = 64, bool w_any = false) {
   if (!group_is_aligned<__bf16>(g, ak, bk)) return false;
+  if (w_any && (epi != Epilogue::ApplyW || !bk)) return false;
   const int c_vec = epi == Epilogue::ApplyW ? 8 : 4;  // elements per 16 bytes of the output
   for (int i = 0; i < g.count; ++i) {
     const GemmProblem& p = g.p[i];
     if (p.K % bk_step != 0 || p.K < bk_step) return false;
-    if (p.M < 8 || p.N < 8 || p.N % 8 != 0) return false;
-    if ((reinterpret_cast<uintptr_t>(p.C) & 15) || p.ldc % c_vec != 0) return false;
+    if (p.M < 8 || p.N < 8 || (!w_any && p.N % 8 != 0)) return false;
+    if (w_any ? (p.ldc < p.N || (reinterpret_cast<uintptr_t>(p.C) & 1)) : ((reinterpret_cast<uintptr_t>(p.C) & 15) || p.ldc % c_vec != 0)) return false;
     // the tile loads address an operand with 32-bit byte offsets from its first element
     const uint64_t a_outer = ak ? (uint64_t)p.M : (uint64_t)p.K, b_outer = bk ? (uint64_t)p.N : (uint64_t)p.K;
     if (a_outer * (uint64_t)p.lda * 2 > 0xFFFFFFFFull || b_outer * (uint64_t)p.ldb * 2 > 0xFFFFFFFFull) return false;

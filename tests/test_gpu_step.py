@@ -98,6 +98,16 @@ def test_left_tensors_with_odd_row_length_are_projected_from_a_padded_copy():
     _run_stack(shapes, "bf16", 32, steps=2, update_gap=2, chunked=True)
 
 
+def test_weight_update_of_odd_row_lengths_on_the_large_tile_kernel():
+    # r = 64 is the smallest rank the large-tile weight update takes; W with an odd row length (and so
+    # rows at odd element offsets) then goes through its any-alignment variant: 16-byte pieces at element
+    # alignment, the piece across the end of a row element by element.  Wide and tall tensors, several
+    # tiles with ragged last ones in both directions, next to an aligned tensor in the same call.
+    shapes = [(128, 333), (64, 1021), (192, 523), (128, 128), (64, 65), (1021, 65), (515, 67)]
+    _run_stack(shapes, "bf16", 64, steps=3, update_gap=2)
+    _run_stack(shapes, "bf16", 64, steps=2, update_gap=2, weight_decay=0.1)
+
+
 def test_identity_projector_is_scaled_adam_on_device():
     # r = m, P = I: the device trajectory must equal plain Adam with step lr*alpha (library Adam, fp64).
     m, n = 64, 192
