@@ -26,7 +26,10 @@ def test_early_weight_prefetch_is_exactly_eight_loads(tmp_path):
                           stderr=subprocess.DEVNULL)
     text = open(out).read()
     kernels = re.findall(r"^(_ZN6galore14gemm_dl_kernelILb1ELb[01]ELNS_8EpilogueE1E\w+):[^\n]*\n(.*?)\.end_amdhsa_kernel", text, flags=re.S | re.M)
-    assert len(kernels) == 2                                   # (K,X) and (K,K) weight-update kernels
+    # (K,X) and (K,K) weight-update kernels, and the (K,K) variant for W of any alignment, whose
+    # prefetch copies 16 bytes at element alignment and must still be one load instruction per piece
+    assert len(kernels) == 3
+    assert sum(name.endswith("Lb1EEEvNS_9GemmGroupE") for name, _ in kernels) == 1
     for name, body in kernels:
         ops = []
         for line in body.split("\n"):
