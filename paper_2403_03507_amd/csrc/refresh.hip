@@ -40,7 +40,7 @@ constexpr float kJacobiTol = 1e-5f;  // |b_p.b_q| <= tol |b_p||b_q|: a few times
 // products of long fp32 rows keep crossing kJacobiTol by rounding alone, so "no rotation at all" is
 // rarely reached although the result has stopped changing.
 constexpr float kJacobiStopTol = 4e-5f;
-constexpr int kNB = 8;               // reflectors per Householder panel
+constexpr int kNB = 8;               // reflectors per Householder panel (block_sum_vec sums 8 values)
 constexpr int kRPT = 4;              // rows per thread in the panel kernels (1024 threads): k - j0 <= 4096
 constexpr int kSW = 8;               // columns per block in the blocked reflector application
 
@@ -294,33 +294,37 @@ __global__ __launch_bounds__(1024) void householder_strip_kernel(const RefreshGr
 // Thread t of the 1024-thread block owns rows j0 + t + 1024 s (s < kRPT) and keeps them in
 // registers, so a panel is read and written once however many reflectors touch it.
 
-// Sum NV values over the block of 16 waves; every thread gets all sums.  red: [17][NV] floats.
-template <int NV>
-__device__ __forceinline__ void block_sum_vec(float (&v)[NV], float* red) {
+// Sum 8 values over the block of 16 waves; every thread gets all sums.  One barrier per call: red holds
+// two areas of 16 x 8 floats that successive calls use alternately (phase), so a wave may write its
+// partial sums of call n + 1 while slower waves still read those of call n, and the area of call n is
+// written again only after the barrier of call n + 1, which every reader of call n has passed.  Behind
+// the barrier every wave adds the 16 partial sums itself: lane 8 w + c takes waves w and w + 8 of value c,
+// three exchange steps add over w, and lanes 0 .. 7 then hold the eight sums (same bits in every wave).
+__device__ __forceinline__ void block_sum_vec(float (&v)[8], float* red, int& phase) {
 #pragma unroll
-  for (int c = 0; c < NV; ++c) v[c] = wave_sum(v[c]);
-  const int wave = threadIdx.x >> 6;
-  __syncthreads();  // earlier readers of `red` are done
-  if ((threadIdx.x & 63) == 0) {
+  for (int c = 0; c < 8; ++c) v[c] = wave_sum(v[c]);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* buf = red + phase * 128;
+  phase ^= 1;
+  if (lane == 0) {
 #pragma unroll
-    for (int c = 0; c < NV; ++c) red[wave * NV + c] = v[c];
+    for (int c = 0; c < 8; ++c) buf[wave * 8 + c] = v[c];
   }
   __syncthreads();
-  if (threadIdx.x < NV) {  // one thread per value adds the 16 wave sums, in a fixed order
-    float s = 0.f;
-    for (int w = 0; w < 16; ++w) s += red[w * NV + threadIdx.x];
-    red[16 * NV + threadIdx.x] = s;
-  }
-  __syncthreads();
+  float a = buf[lane] + buf[64 + lane];
+  a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x128, 0xF, 0xF, false));  // row_ror:8, lane ^ 8
+  a += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, __builtin_bit_cast(int, a)));
+  a += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, a)));
 #pragma unroll
-  for (int c = 0; c < NV; ++c) v[c] = red[16 * NV + c];
+  for (int c = 0; c < 8; ++c) v[c] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), c));
 }
 
 // Factor columns [j0, j0 + nb) of Z below row j0: LAPACK-style reflectors, column j keeps the
 // unscaled vector below its diagonal, tau_j and the scale 1 / (x0 - beta) go to side arrays.
 __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGroup* __restrict__ gp, int j0, int nb) {
   const RefreshGroup& grp = *gp;
-  __shared__ float red[17 * kNB];
+  __shared__ float red[2 * 16 * kNB];
+  int red_phase = 0;
   __shared__ float bc[kNB + 1];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int k = t.k;
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(1024) void householder_panel_kernel(const RefreshGr
 #pragma unroll
       for (int c = 0; c < kNB; ++c) bc[c] = x[0][c];
     }
-    block_sum_vec<kNB>(d, red);  // its barriers also publish bc
+    block_sum_vec(d, red, red_phase);  // its barriers also publish bc
     const float x0 = bc[i];
     const float sigma = d[i];
     float tau = 0.f, vs = 0.f;
@@ -401,7 +405,8 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
                                                                        int target_is_q, int reverse, int col_end, int factor_next) {
   const RefreshGroup& grp = *gp;
   static_assert(kSW == kNB, "the fused factorisation treats a workgroup's columns as one panel");
-  __shared__ float red[17 * kSW];
+  __shared__ float red[2 * 16 * kSW];
+  int red_phase = 0;
   __shared__ float bc[kNB + 1];
   const RefreshTensor& t = grp.t[blockIdx.y];
   const int k = t.k;
@@ -459,7 +464,7 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
       for (int s = 0; s < kRPT; ++s) a += v[s][ii] * x[s][c];
       w[c] = a;
     }
-    block_sum_vec<kSW>(w, red);
+    block_sum_vec(w, red, red_phase);
 #pragma unroll
     for (int s = 0; s < kRPT; ++s) {
       const float tv = tau * v[s][ii];
@@ -489,7 +494,7 @@ __global__ __launch_bounds__(1024) void householder_block_apply_kernel(const Ref
 #pragma unroll
         for (int c = 0; c < kNB; ++c) bc[c] = x[0][c];
       }
-      block_sum_vec<kNB>(d, red);  // its barriers also publish bc
+      block_sum_vec(d, red, red_phase);  // its barriers also publish bc
       const float x0 = bc[i];
       const float sigma = d[i];
       float tau = 0.f, vs = 0.f;
