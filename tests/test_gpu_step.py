@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0, grad_kw=None,
-               chunked=False, workspace_bytes=None):
+               chunked=False, workspace_bytes=None, view=None):
     grad_kw = grad_kw or dict(kind="lowrank", signal_rank=32, sigma0=10.0, decay=0.8, noise=0.01)
     srcs = [wl.GradientSource(m, n, 100 + i, dtype=dtype, **grad_kw) for i, (m, n) in enumerate(shapes)]
     W0 = [wl.make_weight(m, n, 200 + i, dtype) for i, (m, n) in enumerate(shapes)]
@@ -24,7 +24,8 @@ def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0
                                 beta2=f32(0.999), eps=f32(1e-8), weight_decay=f32(weight_decay), dtype=dtype)
                for w in W0]
     lr = f32(lr)
-    Wd = [w.cuda() for w in W0]
+    view = view or (lambda t: t)   # how W and G are laid out in device memory
+    Wd = [view(w.cuda()) for w in W0]
     opt = gb.GaLore(Wd, rank, update_gap=update_gap, weight_decay=weight_decay, auto_refresh=False,
                     workspace_bytes=workspace_bytes)
     worst = dict(W=0.0, M=0.0, V=0.0)
@@ -35,7 +36,7 @@ def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0
                 o.refresh(to64(G[i]))                      # oracle refresh (Algorithm 2, t mod T == 0)
                 opt.proj[i].copy_(dev(o.proj, dtype))       # same projector bits on the device
             o.step(to64(G[i]), lr)
-        Gd = [g.cuda() for g in G]
+        Gd = [view(g.cuda()) for g in G]
         if chunked:  # one call per tensor, reverse order (per-layer update during back-propagation)
             for i in reversed(range(len(shapes))):
                 opt.step([Wd[i]], [Gd[i]], lr, first=i)
@@ -106,6 +107,36 @@ def test_weight_update_of_odd_row_lengths_on_the_large_tile_kernel():
     shapes = [(128, 333), (64, 1021), (192, 523), (128, 128), (64, 65), (1021, 65), (515, 67)]
     _run_stack(shapes, "bf16", 64, steps=3, update_gap=2)
     _run_stack(shapes, "bf16", 64, steps=2, update_gap=2, weight_decay=0.1)
+
+
+def _offset_view(t, pad=3):
+    """t inside a wider buffer that starts one element into its allocation: leading dimension cols + pad,
+    first element only element-aligned, NaN everywhere outside the matrix."""
+    rows, cols = t.shape
+    buf = torch.full((rows * (cols + pad) + 1,), float("nan"), dtype=t.dtype, device=t.device)
+    v = buf[1:].view(rows, cols + pad)[:, :cols]
+    v.copy_(t)
+    v._buf = buf
+    return v
+
+
+@pytest.mark.parametrize("dtype,rank", [("bf16", 64), ("bf16", 33), ("f32", 33)])
+def test_element_aligned_strided_views_of_w_and_g(dtype, rank):
+    # W and G as views whose rows start at arbitrary element offsets (odd leading dimension, base one element
+    # into the allocation): every kernel that touches them must fall back to element-aligned accesses, and
+    # nothing outside the matrices may be read into a result or written (the surroundings hold NaN).
+    shapes = [(128, 333), (128, 256), (256, 128), (1021, 65), (64, 520)]
+    seen = []
+    def view(t):
+        v = _offset_view(t)
+        seen.append(v)
+        return v
+    _run_stack(shapes, dtype, rank, steps=3, update_gap=2, view=view)
+    for v in seen:
+        rows, cols = v.shape
+        body = v._buf[1:].view(rows, -1)
+        assert torch.isnan(v._buf[0]) and torch.isnan(body[:, cols:]).all()
+        assert not torch.isnan(body[:, :cols]).any()
 
 
 def test_identity_projector_is_scaled_adam_on_device():
