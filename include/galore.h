@@ -47,7 +47,9 @@ typedef enum {
   GALORE_ERR_RANK = 4,        /* rank outside 1..min(rows, cols) */
   GALORE_ERR_ALIGN = 5,       /* state / workspace pointer not 16-byte aligned */
   GALORE_ERR_WORKSPACE = 6,   /* workspace too small for even one tensor */
-  GALORE_ERR_STATE = 7,       /* call order wrong (e.g. step before any projector exists) */
+  GALORE_ERR_STATE = 7,       /* a state argument that does not fit its tensor (the two-sided calls: shapes of p, q, m, v).
+                                 Not a check of call order: with auto_refresh = 0 the projector contents are the
+                                 caller's, and the library cannot tell an unwritten projector from a written one */
   GALORE_ERR_HIP = 8,         /* a HIP runtime call or kernel launch failed */
   GALORE_ERR_UNIMPLEMENTED = 9
 } galore_status;

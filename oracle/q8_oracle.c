@@ -11,28 +11,42 @@
  * (tables from exact rationals, brute-force nearest neighbour, idempotence, error bounds), not
  * against the paper.
  *
- * Definition.
+ * Definition (stated in real arithmetic; evaluated here in fp64, see oracle_adam_q8_def).
  *   Block     256 consecutive elements of the row-major moment matrix (the last block may be short).
- *   Scale     one fp32 number per block: max |m| (first moment), max v (second moment).
- *   M code    1 sign bit, 4 exponent bits e, 3 mantissa bits f:
+ *   Scale     one fp32 number per block: max |m| (first moment), max v (second moment), rounded to
+ *             fp32 (nearest even) because it is stored as fp32.
+ *   M code    1 sign bit (set whenever m < 0, also beside the magnitude 0), 4 exponent bits e, 3 mantissa bits f:
  *               e > 0: magnitude (1 + f/8) 2^(e-15);   e = 0: magnitude (f/8) 2^-14.
  *               Largest magnitude used: e = 15, f = 0, i.e. 1.
  *   V code    5 exponent bits e, 3 mantissa bits f (no sign):
  *               e > 0: (1 + f/8) 2^(e-31);   e = 0: (f/8) 2^-30.   Largest used: e = 31, f = 0, i.e. 1.
- *   Decode    value = magnitude * scale, one fp32 multiplication.
- *   Encode    y = min(|x| * (1 / scale), 1): ONE fp32 division per block for the reciprocal, ONE fp32
- *             multiplication per element (0 when scale = 0); the code is the table entry NEAREST to
- *             y; of two equally near entries the one with the even mantissa field wins.
+ *   Decode    value = magnitude * scale.
+ *   Encode    y = |x| / scale (0 when scale = 0); the code is the table entry NEAREST to y (an y
+ *             above 1, possible only through the rounding of the scale, gets the entry 1); of two
+ *             equally near entries the one with the even mantissa field wins.
  *             Written here as a search over the table, not as bit manipulation.
- *   Step      per element, all in fp32, each operation rounded once, in this order:
- *               m = fma(beta1, m_old, (1-beta1) * g)
- *               v = fma(beta2, v_old, ((1-beta2) * g) * g)
- *               n = (m * inv_c1) / (sqrt(v * inv_c2) + eps)            [Algorithm 2, update block]
- *             with m_old, v_old decoded from the stored codes; then the block's new scales are
- *             taken over the new m, v and the new codes are encoded against them.  n uses the
- *             unquantised new moments.
- *           Integer decisions (the codes) are taken in the kernel's precision, fp32, as the
- *           rule for quantised results requires; (1-beta) and inv_c are fp32 inputs.
+ *   Step      the update block of Algorithm 2 on the decoded old moments:
+ *               m = beta1 m_old + (1-beta1) g ;  v = beta2 v_old + (1-beta2) g^2
+ *               n = (m / (1-beta1^k)) / (sqrt(v / (1-beta2^k)) + eps)
+ *             then the block's new scales are taken over the new m, v and the new codes are
+ *             encoded against them.  n uses the unquantised new moments.
+ *
+ * Two routines implement it.
+ *   oracle_adam_q8_def   THE DEFINITION: every quantity above in fp64 (decode products are exact in
+ *                        fp64, the recurrence and the quotient y are rounded at 2^-53).  A code of an
+ *                        fp32 implementation may differ from it only where y lies within fp32 rounding
+ *                        distance of the midpoint between two table entries; the GPU stage test counts
+ *                        and bounds those entries.
+ *   oracle_adam_q8       SECOND CHECKER in the kernel's precision: the same step as one stated fp32
+ *                        operation sequence (below), against which an fp32 kernel that follows the
+ *                        sequence is bit-identical.  It says nothing the definition does not say; it
+ *                        lets a test tell a wrong code from a rounding-distance code.
+ *                          y = min(|x| * (1 / scale), 1): one fp32 division per block, one fp32
+ *                              multiplication per element
+ *                          m = fma(beta1, m_old, (1-beta1) * g)
+ *                          v = fma(beta2, v_old, ((1-beta2) * g) * g)
+ *                          n = (m * inv_c1) / (sqrt(v * inv_c2) + eps)
+ *                        each operation rounded once; (1-beta) and inv_c are fp32 inputs.
  */
 #pragma STDC FP_CONTRACT OFF
 #include <math.h>
@@ -127,6 +141,48 @@ void oracle_adam_q8(const float* R, uint8_t* Mc, uint8_t* Vc, float* Ms, float* 
     for (int i = 0; i < len; ++i) {
       Mc[b0 + i] = oracle_q8_encode_m(m[i], smax);
       Vc[b0 + i] = oracle_q8_encode_v(v[i], vmax);
+    }
+  }
+}
+
+/* THE DEFINITION, in fp64.  One Adam step on `count` elements with 8-bit moments.
+ * R: projected gradient (fp32 values); Mc, Vc: codes (in/out); Ms, Vs: block scales (in/out, fp32,
+ * ceil(count/256) entries); N: normalised update (out, fp64); Ym, Yv: the quotients |m| / scale and
+ * v / scale the codes were chosen from (out, fp64; lets a test measure how far a quotient lies from
+ * the midpoint between two table entries).  beta1, beta2, eps are the numbers the caller uses (for
+ * an fp32 interface: the fp32-representable values); k >= 1 is the step of the bias correction. */
+void oracle_adam_q8_def(const float* R, uint8_t* Mc, uint8_t* Vc, float* Ms, float* Vs, double* N, double* Ym,
+                        double* Yv, int64_t count, double beta1, double beta2, double eps, int64_t k) {
+  const double c1 = 1.0 - pow(beta1, (double)k);
+  const double c2 = 1.0 - pow(beta2, (double)k);
+  double m[Q8_BLOCK], v[Q8_BLOCK];
+  for (int64_t b0 = 0; b0 < count; b0 += Q8_BLOCK) {
+    const int len = count - b0 < Q8_BLOCK ? (int)(count - b0) : Q8_BLOCK;
+    const int64_t blk = b0 / Q8_BLOCK;
+    double mmax = 0.0, vmax = 0.0;
+    for (int i = 0; i < len; ++i) {
+      const double g = (double)R[b0 + i];
+      const int mc = Mc[b0 + i];
+      double m_old = q8_magnitude(mc & 0x7f, 4) * (double)Ms[blk]; /* exact: 4 x 24 significant bits */
+      if (mc & 0x80) m_old = -m_old;
+      const double v_old = q8_magnitude(Vc[b0 + i], 5) * (double)Vs[blk];
+      m[i] = beta1 * m_old + (1.0 - beta1) * g;
+      v[i] = beta2 * v_old + (1.0 - beta2) * g * g;
+      N[b0 + i] = (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+      if (fabs(m[i]) > mmax) mmax = fabs(m[i]);
+      if (v[i] > vmax) vmax = v[i];
+    }
+    const float ms = (float)mmax, vs = (float)vmax; /* stored as fp32: nearest even */
+    Ms[blk] = ms;
+    Vs[blk] = vs;
+    for (int i = 0; i < len; ++i) {
+      const double ym = ms == 0.0f ? 0.0 : fabs(m[i]) / (double)ms;
+      const double yv = vs == 0.0f || v[i] <= 0.0 ? 0.0 : v[i] / (double)vs;
+      Ym[b0 + i] = ym;
+      Yv[b0 + i] = yv;
+      const int mag = q8_nearest(ym, 4); /* an y above 1 is nearest to the top entry, 1 */
+      Mc[b0 + i] = (uint8_t)((m[i] < 0.0 ? 0x80 : 0) | mag);
+      Vc[b0 + i] = (uint8_t)q8_nearest(yv, 5);
     }
   }
 }

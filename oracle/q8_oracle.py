@@ -2,8 +2,9 @@
 
 Loads ``libq8_oracle.so`` (plain C, built from ``q8_oracle.c`` in this directory with floating
 point contraction off, so every fp32 operation of the definition is rounded exactly once) and
-wraps one Adam step with 8-bit block-wise moments.  Parity unpinned by the paper: the number
-format is this build's own definition, stated in the header of ``q8_oracle.c``.  Imports nothing
+wraps one Adam step with 8-bit block-wise moments: ``adam_q8_def`` is the definition (fp64),
+``adam_q8`` the second checker that replays one stated fp32 operation sequence.  Parity unpinned by
+the paper: the number format is this build's own definition, stated in the header of ``q8_oracle.c``.  Imports nothing
 from the HIP package.
 """
 import ctypes
@@ -44,6 +45,8 @@ def lib():
         for name in ("oracle_q8_decode_m_array", "oracle_q8_decode_v_array"):
             getattr(L, name).argtypes = [_u8p, _f32p, _f32p, _i64]
         L.oracle_adam_q8.argtypes = [_f32p, _u8p, _u8p, _f32p, _f32p, _f32p, _i64] + [_f32] * 7
+        L.oracle_adam_q8_def.argtypes = [_f32p, _u8p, _u8p, _f32p, _f32p, _f64p, _f64p, _f64p, _i64,
+                                         ctypes.c_double, ctypes.c_double, ctypes.c_double, _i64]
     return _lib
 
 
@@ -106,3 +109,26 @@ def adam_q8(R, Mc, Vc, Ms, Vs, beta1, beta2, eps, k):
                          Ms.ctypes.data_as(_f32p), Vs.ctypes.data_as(_f32p), N.ctypes.data_as(_f32p), R.size,
                          b1, b2, np.float32(1.0) - b1, np.float32(1.0) - b2, np.float32(eps), ic1, ic2)
     return N
+
+
+def adam_q8_def(R, Mc, Vc, Ms, Vs, beta1, beta2, eps, k):
+    """THE DEFINITION of the step (fp64, see the header of q8_oracle.c) on the flattened row-major R.
+    Mc, Vc (uint8), Ms, Vs (fp32 per block) are updated in place; returns (N, Ym, Yv) in fp64: the
+    normalised update and the quotients |m| / scale, v / scale the new codes were chosen from.
+    beta1, beta2, eps are used as given (pass the fp32-representable numbers an fp32 interface sees)."""
+    R = _f(R).reshape(-1)
+    assert Mc.dtype == np.uint8 and Vc.dtype == np.uint8 and Ms.dtype == np.float32 and Vs.dtype == np.float32
+    assert Mc.size == R.size and Vc.size == R.size and Ms.size == n_blocks(R.size) and Vs.size == n_blocks(R.size)
+    N, Ym, Yv = (np.zeros(R.size, dtype=np.float64) for _ in range(3))
+    lib().oracle_adam_q8_def(R.ctypes.data_as(_f32p), Mc.ctypes.data_as(_u8p), Vc.ctypes.data_as(_u8p),
+                             Ms.ctypes.data_as(_f32p), Vs.ctypes.data_as(_f32p), N.ctypes.data_as(_f64p),
+                             Ym.ctypes.data_as(_f64p), Yv.ctypes.data_as(_f64p), R.size,
+                             float(beta1), float(beta2), float(eps), int(k))
+    return N, Ym, Yv
+
+
+def midpoints(is_v):
+    """Decision boundaries of the encoder: midpoints between consecutive magnitudes in use (fp64, exact)."""
+    t = decode_table(is_v)
+    t = t[t >= 0]
+    return 0.5 * (t[1:] + t[:-1])

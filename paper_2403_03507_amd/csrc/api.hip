@@ -489,7 +489,7 @@ const char* galore_status_string(galore_status s) {
     case GALORE_ERR_RANK: return "rank out of range";
     case GALORE_ERR_ALIGN: return "pointer alignment";
     case GALORE_ERR_WORKSPACE: return "workspace too small";
-    case GALORE_ERR_STATE: return "bad call order";
+    case GALORE_ERR_STATE: return "state does not fit the tensor";
     case GALORE_ERR_HIP: return "HIP error";
     case GALORE_ERR_UNIMPLEMENTED: return "not implemented";
   }
@@ -618,7 +618,7 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
     if (ti.q8 && e == hipSuccess) e = launch_fill_zero(ti.st.v_scale.data, (size_t)r * ti.ldim / 256 * 4, ctx->stream);
     if (e != hipSuccess) {
       galore_status st = hip_fail(nullptr, e, "zero-filling moments");
-      delete ctx;
+      galore_destroy(ctx);  // also releases the library streams and events
       return st;
     }
   }

@@ -145,6 +145,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_dl_kernel(const GemmGroup grp) {
   constexpr bool STREAM_A = false;
   constexpr bool STREAM_B = EPI == Epilogue::StoreF32 && AK && !BKC;
   static_assert(S == 2, "the cross-tile stream is written for a two-stage ring");
+  static_assert(BK == 64, "the pipelined main loop is written out for four 16-k substeps per K step");
   static_assert(WN == 64 || WN == 128, "the strip epilogue covers 8 rows with one or two passes of the wave");
   constexpr int PITCH = WN + 8;           // floats; 4 PITCH = 32 (mod 64) spreads the two half-waves over the banks
   constexpr int STRIP_FLOATS = 8 * PITCH;

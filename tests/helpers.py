@@ -36,3 +36,30 @@ def strided(t, pad):
 def f32(x):
     """The value the C ABI receives for a float hyper-parameter; the oracle is given the same number."""
     return float(np.float32(x))
+
+
+def bf16_ulp(x):
+    """Spacing of bf16 numbers at |x| (8 significant bits), as fp64."""
+    ax = np.maximum(np.abs(np.asarray(x, dtype=np.float64)), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 7)
+
+
+def check_bf16_weights(W_dev, W_orc, W_before, steps, lr, alpha, where=None, expect_moved=True):
+    """Per-entry gate on bf16 weights after `steps` steps from W_before (all fp64 arrays of bf16 values;
+    W_orc = the oracle's stored weights, rounded to bf16 after every step).  relF on W cannot see the
+    update (one step moves W by well under a per cent of its norm), so every entry is bounded: a rounding
+    that falls the other way costs one ulp per step (ulp at the larger of old and new weight), and an
+    entry of R within rounding distance of zero may flip the sign of its N on the first step after
+    zero moments, which moves a weight by a small fraction of lr*alpha.  Nearly all entries are
+    identical, and the device moved (about) as many weights as the oracle did."""
+    ulp = np.maximum(bf16_ulp(W_orc), bf16_ulp(W_before))
+    err = np.abs(W_dev - W_orc)
+    assert np.all(err <= steps * ulp + 0.1 * lr * alpha), (where, float(err.max()), float((steps * ulp).max()))
+    same = float(np.mean(W_dev == W_orc))
+    assert same >= 0.98, (where, same)
+    moved_orc = float(np.mean(W_orc != W_before))
+    moved_dev = float(np.mean(W_dev != W_before))
+    if expect_moved:
+        assert moved_orc > 0.2, (where, moved_orc)       # the comparison is not vacuous
+    assert moved_dev >= 0.9 * moved_orc - 0.01, (where, moved_dev, moved_orc)
+    return same, moved_dev

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import TOL, f32, relF, to64
+from helpers import TOL, check_bf16_weights, f32, relF, to64
 from oracle import galore_oracle as orc
 from paper_2403_03507_amd import binding as gb
 from paper_2403_03507_amd import workloads as wl
@@ -41,6 +41,8 @@ def test_one_layer_two_steps(cfg):
             assert relF(to64(Wd[i]), o.W) <= TOL[dtype], (cfg, step, i)
             assert relF(to64(opt.M[i]), o.M) <= 1e-5, (cfg, step, i)
             assert relF(to64(opt.V[i]), o.V) <= 1e-5, (cfg, step, i)
+            # every weight, per entry (the relF gate above cannot see a missing update)
+            check_bf16_weights(to64(Wd[i]), o.W, to64(W0[i]), step + 1, lr, 0.25, where=(cfg, step, i))
     opt.close()
 
 

@@ -1,8 +1,11 @@
 """GPU parity of low-rank Adam with 8-bit block-wise moments against oracle/q8_oracle.c.
 
-The stage is compared bit for bit: codes and block scales are integers / maxima decided in fp32 on
-both sides by the same stated operation sequence, and N is the same fp32 expression (rounded to
-bf16 where the step stores it so).  Whole steps run the projection on the GPU (fp32 accumulation,
+The stage is compared twice.  Against THE DEFINITION (fp64: Adam recurrence on the decoded old
+moments, scale = block maximum, code = nearest table entry to |x| / scale, ties to the even
+mantissa field): codes equal except where the definition's quotient lies within fp32 rounding
+distance of a midpoint between two table entries (those are counted, must be neighbours, and must
+be fewer than 1e-3 of the entries), scales to an fp32 ulp, N to fp32 rounding.  And bit for bit
+against the second checker, which replays one stated fp32 operation sequence.  Whole steps run the projection on the GPU (fp32 accumulation,
 not bit-identical to the fp64 oracle), so there the comparison is on the decoded moments and the
 weights, to the step's tolerances.  The paper names 8-bit moments (Sec. 4.3) without a format:
 parity with the paper itself is unpinned, the format is the library's own."""
@@ -54,6 +57,67 @@ def test_adam_q8_stage_bit_exact_over_steps(shape, transpose_n, n_dtype):
         got = got.T if transpose_n else got
         want = N_ref if n_dtype == "f32" else _bf16_round(N_ref)
         assert np.array_equal(got, want), k
+
+
+@pytest.mark.parametrize("transpose_n", [False, True])
+@pytest.mark.parametrize("shape", [(64, 512), (33, 256), (100, 1280), (40, 2816)])
+def test_adam_q8_stage_against_the_fp64_definition(shape, transpose_n):
+    rows, cols = shape
+    count = rows * cols
+    rng = np.random.default_rng(rows * 1000 + cols + 7)
+    b1, b2, eps = f32(0.9), f32(0.999), f32(1e-8)
+    mid = {False: q8.midpoints(False), True: q8.midpoints(True)}
+    base = rng.standard_normal(count) * np.exp(rng.uniform(-6, 2, count))
+    # start of every step: a seeded stored state (any codes, any scales), the same bits on both sides;
+    # k = 1 starts from the zero state of galore_init
+    near_total = 0
+    for k in (1, 2, 9, 400):
+        if k == 1:
+            Mc, Vc = np.zeros(count, np.uint8), np.zeros(count, np.uint8)
+            Ms, Vs = np.zeros(count // 256, np.float32), np.zeros(count // 256, np.float32)
+        else:
+            Mc = (rng.integers(0, 121, count) | (rng.integers(0, 2, count) << 7)).astype(np.uint8)
+            Vc = rng.integers(0, 249, count).astype(np.uint8)
+            Ms = np.exp(rng.uniform(-7, 2, count // 256)).astype(np.float32)
+            Vs = (np.exp(rng.uniform(-7, 2, count // 256)) ** 2).astype(np.float32)
+        g = (base * (1 + 0.3 * rng.standard_normal(count))).astype(np.float32)
+        if k == 9:
+            g[:256] = 0.0
+        dMc = torch.from_numpy(Mc.copy()).reshape(rows, cols).cuda()
+        dVc = torch.from_numpy(Vc.copy()).reshape(rows, cols).cuda()
+        dMs = torch.from_numpy(Ms.copy()).reshape(rows, cols // 256).cuda()
+        dVs = torch.from_numpy(Vs.copy()).reshape(rows, cols // 256).cuda()
+        dN = torch.empty((cols, rows) if transpose_n else (rows, cols), dtype=torch.float32, device="cuda")
+        gb.galore_adam_q8(torch.from_numpy(g).reshape(rows, cols).cuda(), dMc, dVc, dMs, dVs, dN, transpose_n, 0.9, 0.999, 1e-8, k)
+        torch.cuda.synchronize()
+        # terms of the recurrences, for the size of an fp32 rounding of m and v where they cancel
+        m_old = q8.decode(Mc, np.repeat(Ms, 256), False).astype(np.float64)
+        v_old = q8.decode(Vc, np.repeat(Vs, 256), True).astype(np.float64)
+        N, Ym, Yv = q8.adam_q8_def(g, Mc, Vc, Ms, Vs, b1, b2, eps, k)          # updates the oracle state in place
+        got_n = dN.cpu().numpy().astype(np.float64)
+        got_n = (got_n.T if transpose_n else got_n).reshape(-1)
+        # N: a handful of fp32 roundings (two in m, three in v, bias factors, sqrt, sum, quotient); where
+        # beta1 m_old and (1-beta1) g cancel, the roundings of the terms, not of the small result, count
+        g64 = g.astype(np.float64)
+        terms = np.abs(b1 * m_old) + np.abs((1 - b1) * g64)
+        den = np.sqrt((b2 * v_old + (1 - b2) * g64 * g64) / (1 - b2 ** k)) + eps
+        assert np.all(np.abs(got_n - N) <= 6e-7 * np.abs(N) + 2.0 ** -23 * terms / (1 - b1 ** k) / den + 1e-30), k
+        np.testing.assert_allclose(dMs.cpu().numpy().reshape(-1), Ms, rtol=2.5e-7, atol=0, err_msg=str(k))
+        np.testing.assert_allclose(dVs.cpu().numpy().reshape(-1), Vs, rtol=4e-7, atol=0, err_msg=str(k))
+        for dev_codes, want, Y, is_v, t in ((dMc, Mc, Ym, False, terms / np.maximum(np.repeat(Ms, 256), 1e-300)),
+                                            (dVc, Vc, Yv, True, None)):
+            got = dev_codes.cpu().numpy().reshape(-1)
+            mask = 0xff if is_v else 0x7f
+            diff = np.nonzero(got != want)[0]
+            near_total += len(diff)
+            assert len(diff) < 1e-3 * count, (k, is_v, len(diff))
+            for i in diff:
+                cg, cw = int(got[i]) & mask, int(want[i]) & mask
+                assert abs(cg - cw) == 1 and (int(got[i]) & ~mask) == (int(want[i]) & ~mask), (k, is_v, i, got[i], want[i])
+                b = mid[is_v][min(cg, cw)]
+                slack = 2.0 ** -20 * b + (2.0 ** -22 * t[i] if t is not None else 0.0)
+                assert abs(Y[i] - b) <= slack, (k, is_v, i, Y[i], b)
+    print("codes at rounding distance of a midpoint:", near_total, "of", 8 * count)
 
 
 def test_adam_q8_stage_rejects_unaligned_rows():

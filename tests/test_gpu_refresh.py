@@ -67,6 +67,32 @@ def test_gapped_spectrum_bf16(shape):
     opt.close()
 
 
+@pytest.mark.parametrize("shape,r,dtype", [((1024, 1024), 256, "f32"), ((1024, 2736), 256, "f32"), ((2736, 1024), 256, "f32"),
+                                           ((1024, 1024), 256, "bf16"), ((768, 2048), 256, "f32"), ((512, 1376), 128, "f32"),
+                                           ((2048, 2048), 512, "f32")])
+def test_gapped_spectrum_at_the_ranks_of_the_stacks(shape, r, dtype):
+    # The shapes and ranks of the 350M (1024 x 1024 / 1024 x 2736 / 2736 x 1024, r = 256), 130M (768 x 2048, r = 256),
+    # 60M (512 x 1376, r = 128) and 1B (2048 x 2048, r = 512) stacks against the oracle's Jacobi SVD: 8 to 16 compact-WY
+    # macro panels, 16 to 32 blocks in the Jacobi rounds, the split-bf16 products (short side >= 512).
+    m, n = shape
+    G = wl.GradientSource(m, n, 23, "gapped", dtype=dtype, gap_rank=r).grad(0)
+    P0, sig = orc.projector(to64(G), r)
+    assert sig[r - 1] / sig[r] >= 2.0
+    opt = _refresh([G], r)
+    P = to64(opt.proj[0])
+    if dtype == "f32":
+        assert _proj_dist(P, P0) <= 1e-3
+        assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
+        assert np.all(np.sum(P * P0, axis=0) >= 0.99)    # the vectors themselves, signs included (neighbouring singular values lie 0.6 - 2.4 % apart)
+    else:
+        P0r = orc.round_storage(P0, "bf16")
+        assert relF(P, P0r) <= 2e-3
+        assert np.mean(P == P0r) >= 0.97
+        assert _proj_dist(P, P0r) <= 1e-3 + 2 * relF(P, P0r) * np.sqrt(r)
+    np.testing.assert_array_equal(to64(opt.proj_t[0]), P.T)
+    opt.close()
+
+
 def test_group_of_mixed_shapes_and_dtypes_in_one_call():
     shapes = [(128, 160), (160, 128), (96, 96), (128, 300)]
     r = 24

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import TDT, TOL, dev, f32, relF, to64
+from helpers import TDT, TOL, check_bf16_weights, dev, f32, relF, to64
 from oracle import galore_oracle as orc
 from paper_2403_03507_amd import binding as gb
 from paper_2403_03507_amd import workloads as wl
@@ -29,6 +29,7 @@ def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0
     opt = gb.GaLore(Wd, rank, update_gap=update_gap, weight_decay=weight_decay, auto_refresh=False,
                     workspace_bytes=workspace_bytes)
     worst = dict(W=0.0, M=0.0, V=0.0)
+    before = [o.W.copy() for o in oracles]
     for step in range(steps):
         G = [s.grad(step) for s in srcs]
         for i, o in enumerate(oracles):
@@ -48,7 +49,9 @@ def _run_stack(shapes, dtype, rank, steps, update_gap, lr=1e-3, weight_decay=0.0
             e = dict(W=relF(to64(Wd[i]), o.W), M=relF(to64(opt.M[i]), o.M), V=relF(to64(opt.V[i]), o.V))
             for k in e:
                 worst[k] = max(worst[k], e[k])
-                assert e[k] <= TOL[dtype], (step, i, k, e[k])
+                assert e[k] <= (TOL[dtype] if k == "W" else 1e-5), (step, i, k, e[k])
+            if dtype == "bf16":   # relF cannot see one update on bf16 weights: bound every entry
+                check_bf16_weights(to64(Wd[i]), o.W, before[i], step + 1, lr, 0.25, where=(step, i, shapes[i]))
     opt.close()
     return worst
 

@@ -179,3 +179,93 @@ def test_step_is_exactly_the_stated_fp32_sequence():
     N = q8.adam_q8(np.array([g], np.float32), Mc, Vc, Ms, Vs, 0.9, 0.999, 1e-8, k)
     assert N[0] == n and Ms[0] == abs(m) and Vs[0] == v
     assert Mc[0] == (0x80 | 120) and Vc[0] == 248    # a one-element block: both moments equal their scale
+
+
+# ---- the definition routine (fp64): pins that do not go through its own formula ----------------
+
+B1, B2, EPS = float(np.float32(0.9)), float(np.float32(0.999)), float(np.float32(1e-8))
+
+
+def test_definition_moments_and_update_are_fp64_adam_on_the_decoded_state():
+    # From any stored state, the definition's N must be the separately pinned fp64 Adam of
+    # galore_oracle (Algorithm 2, update block) run on the DECODED old moments, and the new
+    # scales the fp32 rounding of that Adam's block maxima.
+    rng = np.random.default_rng(21)
+    count = 256 * 3 + 100
+    nb = q8.n_blocks(count)
+    Mc = rng.integers(0, 121, count).astype(np.uint8) | (rng.integers(0, 2, count).astype(np.uint8) << 7)
+    Vc = rng.integers(0, 249, count).astype(np.uint8)
+    Ms = np.exp(rng.uniform(-8, 2, nb)).astype(np.float32)
+    Vs = np.exp(rng.uniform(-12, 2, nb)).astype(np.float32)
+    g = (rng.standard_normal(count) * np.exp(rng.uniform(-6, 1, count))).astype(np.float32)
+    M64 = q8.decode_table(False)[Mc & 0x7f] * np.where(Mc & 0x80, -1.0, 1.0) * np.repeat(Ms.astype(np.float64), 256)[:count]
+    V64 = q8.decode_table(True)[Vc] * np.repeat(Vs.astype(np.float64), 256)[:count]
+    N64 = orc.adam(g.astype(np.float64), M64, V64, B1, B2, EPS, 17)          # updates M64, V64 in place
+    N, Ym, Yv = q8.adam_q8_def(g, Mc, Vc, Ms, Vs, B1, B2, EPS, 17)
+    np.testing.assert_allclose(N, N64, rtol=1e-13, atol=0)
+    for b in range(nb):
+        sl = slice(256 * b, min(256 * (b + 1), count))
+        assert Ms[b] == np.float32(np.abs(M64[sl]).max()) and Vs[b] == np.float32(V64[sl].max())
+        np.testing.assert_allclose(Ym[sl], np.abs(M64[sl]) / float(Ms[b]), rtol=1e-13)
+        np.testing.assert_allclose(Yv[sl], V64[sl] / float(Vs[b]), rtol=1e-13)
+    # and the codes are the exact-rational nearest neighbours of those quotients
+    tm, tv = closed_form_table(False), closed_form_table(True)
+    for i in rng.integers(0, count, 150):
+        assert (Mc[i] & 0x7f) == brute_force_nearest(min(Ym[i], 1.0), tm)
+        assert Vc[i] == brute_force_nearest(min(Yv[i], 1.0), tv)
+        assert bool(Mc[i] & 0x80) == (M64[i] < 0)
+
+
+def test_definition_on_exactly_representable_moments_and_ties():
+    # beta = 0 makes the new moments m = g, v = g^2 exactly.  With a block maximum of 1 the quotient
+    # is the moment itself, so table entries come back as their own codes and exact midpoints go to
+    # the even mantissa field.
+    tm = q8.decode_table(False)[:121]
+    mids = q8.midpoints(False)[8:]                      # midpoints of normal entries (exact in fp32)
+    g = np.zeros(512, np.float32)
+    g[:121] = tm
+    g[120] = 1.0                                        # the block maximum
+    g[256:256 + len(mids)] = -mids
+    g[511] = -1.0
+    Mc, Vc, Ms, Vs = _fresh(512)
+    q8.adam_q8_def(g, Mc, Vc, Ms, Vs, 0.0, 0.0, EPS, 1)
+    assert Ms[0] == 1 and Ms[1] == 1 and Vs[0] == 1
+    assert np.array_equal(Mc[:121], np.arange(121, dtype=np.uint8))
+    got = Mc[256:256 + len(mids)]
+    assert np.all(got & 0x80) and np.all((got & 1) == 0)
+    lo = np.arange(8, 8 + len(mids))
+    assert np.all(((got & 0x7f) == lo) | ((got & 0x7f) == lo + 1))
+    # v = g^2: squares of powers of two are table entries of the V format
+    pw = np.array([2.0 ** -e for e in range(0, 15)], np.float32)
+    g2 = np.zeros(256, np.float32); g2[:15] = pw
+    Mc, Vc, Ms, Vs = _fresh(256)
+    q8.adam_q8_def(g2, Mc, Vc, Ms, Vs, 0.0, 0.0, EPS, 1)
+    assert np.array_equal(Vc[:15], np.array([248 - 16 * e for e in range(15)], np.uint8))
+
+
+def test_fp32_sequence_agrees_with_the_definition_up_to_rounding_distance():
+    # The second checker (one stated fp32 operation sequence) may pick another code than the
+    # definition only where the definition's quotient lies within fp32 rounding distance of a
+    # midpoint between two table entries; then the two codes are neighbours.
+    rng = np.random.default_rng(23)
+    count = 256 * 64
+    base = rng.standard_normal(count) * np.exp(rng.uniform(-6, 2, count))
+    a = _fresh(count)
+    b = _fresh(count)
+    mid_m, mid_v = q8.midpoints(False), q8.midpoints(True)
+    for k in range(1, 5):
+        g = (base * (1 + 0.3 * rng.standard_normal(count))).astype(np.float32)
+        for x, y in zip(a, b):
+            y[:] = x                                     # both start from the same stored state
+        N32 = q8.adam_q8(g, *a, 0.9, 0.999, 1e-8, k)
+        N64, Ym, Yv = q8.adam_q8_def(g, *b, B1, B2, EPS, k)
+        np.testing.assert_allclose(N32, N64, rtol=2e-6, atol=1e-30)
+        np.testing.assert_allclose(a[2], b[2], rtol=2.5e-7)
+        np.testing.assert_allclose(a[3], b[3], rtol=2.5e-7)
+        for got, want, Y, mids, mask in ((a[0], b[0], Ym, mid_m, 0x7f), (a[1], b[1], Yv, mid_v, 0xff)):
+            diff = np.nonzero(got != want)[0]
+            assert len(diff) <= 1e-3 * count
+            for i in diff:
+                cg, cw = int(got[i] & mask), int(want[i] & mask)
+                assert abs(cg - cw) == 1 and (int(got[i]) & ~mask) == (int(want[i]) & ~mask)
+                assert abs(Y[i] - mids[min(cg, cw)]) <= 2.0 ** -20 * mids[min(cg, cw)]
