@@ -51,12 +51,17 @@ def check_bf16_weights(W_dev, W_orc, W_before, steps, lr, alpha, where=None, exp
     that falls the other way costs one ulp per step (ulp at the larger of old and new weight), and an
     entry of R within rounding distance of zero may flip the sign of its N on the first step after
     zero moments, which moves a weight by a small fraction of lr*alpha.  Nearly all entries are
-    identical, and the device moved (about) as many weights as the oracle did."""
+    identical: the device rounds N to bf16 before the back-projection (N is stored in the tensor's dtype), the
+    oracle does not, so the two updates differ by about 2^-9 of their size and a weight lands on the other
+    side of a rounding boundary with probability about 2 * 2^-9 |dW| / ulp per step (0.4 % at the paper's
+    lr*alpha = 2.5e-4, ten times that at lr = 1e-2).  And the device moved (about) as many weights as the
+    oracle did."""
     ulp = np.maximum(bf16_ulp(W_orc), bf16_ulp(W_before))
     err = np.abs(W_dev - W_orc)
     assert np.all(err <= steps * ulp + 0.1 * lr * alpha), (where, float(err.max()), float((steps * ulp).max()))
     same = float(np.mean(W_dev == W_orc))
-    assert same >= 0.98, (where, same)
+    per_step = 0.005 + 2.0 ** -8 * float(np.median(np.abs(W_orc - W_before)) / steps / np.median(ulp))
+    assert same >= 1.0 - steps * per_step, (where, same, per_step)
     moved_orc = float(np.mean(W_orc != W_before))
     moved_dev = float(np.mean(W_dev != W_before))
     if expect_moved:

