@@ -155,6 +155,26 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
 galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G,
                           int32_t first, int32_t count, float lr);
 
+/* galore_step for callers that cannot allocate device memory or size a workspace at call time: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results, but the transients of the step (R, N and, for a bf16 tensor
+ * with an odd row length, the padded copy of G) live in a file-scope device array of the library,
+ * 80 MiB on every GPU the library runs on, held until the process ends, instead of the caller's
+ * workspace; the call allocates nothing (no hipMalloc / hipFree, no events, no streams).  The tensors
+ * run as one chain on the context's stream, in launch groups of as many consecutive tensors as fit
+ * the array (galore_set_concurrency and galore_set_call_overlap do not apply; pending overlapped
+ * calls are joined first).
+ * Limits: GALORE_ERR_WORKSPACE if one tensor's transients exceed the array (4 r max(rows, cols) bytes
+ * of R plus s r max(rows, cols) of N, s = element size of W; every tensor of the LLaMA 60M ... 7B
+ * stacks at the paper's ranks fits); GALORE_ERR_UNIMPLEMENTED if auto_refresh is on and a tensor of
+ * the call is due for a subspace refresh (t mod T == 0: the refresh needs hundreds of MB; take that
+ * step with galore_step); GALORE_ERR_INVALID_ARG between galore_profile_start and _stop.  On any
+ * error nothing has been enqueued and no counter has advanced.
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (other streams,
+ * other contexts, other threads) race on it.  Calls on one stream are ordered by the stream. */
+galore_status galore_step_static(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G,
+                                 int32_t first, int32_t count, float lr);
+
 /* Recompute the projectors of tensors first..first+count-1 from the gradients G
  * (Algorithm 2, refresh branch; Sec. 3.3 SVD equation): the leading r left (LEFT) or right
  * (RIGHT) singular vectors of G, obtained from the Gram matrix of the short side by

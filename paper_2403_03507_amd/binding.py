@@ -46,7 +46,7 @@ class GaloreError(RuntimeError):
         self.status = status
 
 
-EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step",
+EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "galore_step", "galore_step_static",
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
@@ -71,6 +71,7 @@ def lib():
         L.galore_workspace_bytes.argtypes = [hp, tp, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.galore_init.argtypes = [ctypes.POINTER(vp), hp, tp, sp, i32, vp, ctypes.c_size_t, vp]
         L.galore_step.argtypes = [vp, tp, tp, i32, i32, f32]
+        L.galore_step_static.argtypes = [vp, tp, tp, i32, i32, f32]
         L.galore_refresh_subspace.argtypes = [vp, tp, i32, i32]
         L.galore_get_step.argtypes = [vp, i32, ctypes.POINTER(i64)]
         L.galore_set_step.argtypes = [vp, i32, i64]
@@ -156,6 +157,10 @@ def galore_init(hp, w_descs, states, workspace_ptr, workspace_bytes, stream=None
 
 def galore_step(ctx, w_descs, g_descs, first, count, lr):
     _check(lib().galore_step(ctx, _arr(w_descs, galore_tensor), _arr(g_descs, galore_tensor), first, count, lr), ctx)
+
+
+def galore_step_static(ctx, w_descs, g_descs, first, count, lr):
+    _check(lib().galore_step_static(ctx, _arr(w_descs, galore_tensor), _arr(g_descs, galore_tensor), first, count, lr), ctx)
 
 
 def galore_refresh_subspace(ctx, g_descs, first, count):
@@ -312,6 +317,10 @@ class GaLore:
 
     def step(self, weights, grads, lr, first=0):
         galore_step(self.ctx, [desc(w) for w in weights], [desc(g) for g in grads], first, len(weights), lr)
+
+    def step_static(self, weights, grads, lr, first=0):
+        """galore_step with the transients in the library's static device array (allocates nothing)."""
+        galore_step_static(self.ctx, [desc(w) for w in weights], [desc(g) for g in grads], first, len(weights), lr)
 
     def set_call_overlap(self, on):
         galore_set_call_overlap(self.ctx, on)

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <algorithm>
 #include <string>
@@ -14,9 +15,39 @@
 
 using namespace galore;
 
+// Device memory of galore_step_static, the entry point for callers that cannot allocate: the
+// transients R, N (and the padded copy of G) of one launch group live here instead of in the
+// caller's workspace.  Every GPU the library runs on holds its own copy of the array at its own
+// address; host code never uses the array's name as an address, only the per-device pointer that
+// hipGetSymbolAddress returned.
+constexpr size_t kStaticScratchBytes = (size_t)80 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_last_error;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device: address of that device's copy of `scratch`
+
+// Address of the current device's scratch array (resolved once per device, with that device current).
+hipError_t static_scratch_ptr(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+  return hipSuccess;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -429,6 +460,25 @@ galore_status check_step_tensor(galore_ctx* ctx, const TensorInfo& ti, const gal
   return GALORE_OK;
 }
 
+// Argument checks shared by galore_step and galore_step_static; nothing is enqueued on failure.
+galore_status check_step_args(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G, int32_t first, int32_t count, float lr) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  const int n = (int)ctx->tensors.size();
+  if (first < 0 || count < 0 || first > n || count > n - first)
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "range [%d, %d+%d) outside the %d tensors", first, first, count, n);
+  if (count == 0) return GALORE_OK;
+  if (!W || !G) return fail(ctx, GALORE_ERR_INVALID_ARG, "W or G is NULL");
+  if (!std::isfinite(lr)) return fail(ctx, GALORE_ERR_INVALID_ARG, "lr is not finite");
+  for (int i = 0; i < count; ++i) {
+    const TensorInfo& ti = ctx->tensors[first + i];
+    galore_status s = check_step_tensor(ctx, ti, W[i], "W", i);
+    if (s) return s;
+    s = check_step_tensor(ctx, ti, G[i], "G", i);
+    if (s) return s;
+  }
+  return GALORE_OK;
+}
+
 galore_status run_refresh(galore_ctx* ctx, const galore_tensor* G, int32_t first, const std::vector<int>& local,
                           hipStream_t stream, unsigned char* ws, size_t ws_bytes) {
   // local: indices i (relative to `first`) of tensors to refresh, in order; [ws, ws + ws_bytes) is the
@@ -609,6 +659,15 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
       return st;
     }
   }
+  {  // set-up of galore_step_static: this device's address of the static scratch array
+    unsigned char* sp = nullptr;
+    hipError_t e = static_scratch_ptr(&sp);
+    if (e != hipSuccess) {
+      galore_status st = hip_fail(nullptr, e, "resolving the static scratch array");
+      galore_destroy(ctx);
+      return st;
+    }
+  }
   // M_0 = V_0 = 0 (Algorithm 2, initialisation)
   for (const TensorInfo& ti : ctx->tensors) {
     const size_t bytes = (size_t)r * ti.ldim * (ti.q8 ? 1 : 4);  // code 0 decodes to 0
@@ -628,20 +687,9 @@ galore_status galore_init(galore_ctx** out, const galore_hparams* hp, const galo
 
 galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G, int32_t first, int32_t count,
                           float lr) {
-  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
-  const int n = (int)ctx->tensors.size();
-  if (first < 0 || count < 0 || first > n || count > n - first)
-    return fail(ctx, GALORE_ERR_INVALID_ARG, "range [%d, %d+%d) outside the %d tensors", first, first, count, n);
+  galore_status s0 = check_step_args(ctx, W, G, first, count, lr);
+  if (s0) return s0;
   if (count == 0) return GALORE_OK;
-  if (!W || !G) return fail(ctx, GALORE_ERR_INVALID_ARG, "W or G is NULL");
-  if (!std::isfinite(lr)) return fail(ctx, GALORE_ERR_INVALID_ARG, "lr is not finite");
-  for (int i = 0; i < count; ++i) {
-    const TensorInfo& ti = ctx->tensors[first + i];
-    galore_status s = check_step_tensor(ctx, ti, W[i], "W", i);
-    if (s) return s;
-    s = check_step_tensor(ctx, ti, G[i], "G", i);
-    if (s) return s;
-  }
   // Refresh branch of Algorithm 2: t mod T == 0, on this step's gradient, before projecting.
   if (ctx->hp.auto_refresh) {
     std::vector<int> due;
@@ -690,6 +738,60 @@ galore_status galore_step(galore_ctx* ctx, const galore_tensor* W, const galore_
       ++pos;
     }
     galore_status s = run_step_chunk(ctx, items, lr);
+    if (s) return s;
+  }
+  for (int i = 0; i < count; ++i) ctx->tensors[first + i].t += 1;
+  return GALORE_OK;
+}
+
+galore_status galore_step_static(galore_ctx* ctx, const galore_tensor* W, const galore_tensor* G, int32_t first,
+                                 int32_t count, float lr) {
+  galore_status s = check_step_args(ctx, W, G, first, count, lr);
+  if (s) return s;
+  if (count == 0) return GALORE_OK;
+  if (ctx->profiling) return fail(ctx, GALORE_ERR_INVALID_ARG, "galore_step_static cannot run between galore_profile_start and _stop (the brackets create events)");
+  const int r = ctx->hp.rank;
+  for (int i = 0; i < count; ++i) {
+    const TensorInfo& ti = ctx->tensors[first + i];
+    if (ctx->hp.auto_refresh && ti.t % ctx->hp.update_gap == 0)
+      return fail(ctx, GALORE_ERR_UNIMPLEMENTED, "tensor %d is due for a subspace refresh (t = %lld, T = %d), whose working set of %zu bytes "
+                  "exceeds the static scratch array: take this step with galore_step", first + i, (long long)ti.t, ctx->hp.update_gap,
+                  refresh_workspace_bytes(ti.kdim, r));
+    const size_t need = step_need(ti.left, ti.kdim, ti.ldim, r, ti.dt);
+    if (need > kStaticScratchBytes)
+      return fail(ctx, GALORE_ERR_WORKSPACE, "tensor %d needs %zu bytes of transients, the static scratch array holds %zu", first + i, need,
+                  kStaticScratchBytes);
+  }
+  unsigned char* sp = nullptr;
+  hipError_t e = static_scratch_ptr(&sp);  // this device's copy of the array; never the array's name
+  if (e != hipSuccess) return hip_fail(ctx, e, "resolving the static scratch array");
+  if (ctx->unjoined) {  // overlapped calls may still hold these tensors on a library stream
+    s = join_all(ctx);
+    if (s) return s;
+  }
+  // Launch groups of as many consecutive tensors as fit the array, one chain on the context's stream.
+  // Stream order protects the array between groups and between calls on this stream.
+  int pos = 0;
+  while (pos < count) {
+    std::vector<StepItem> items;
+    size_t off = 0;
+    while (pos < count && (int)items.size() < kMaxGroup) {
+      const TensorInfo& ti = ctx->tensors[first + pos];
+      const size_t need = step_need(ti.left, ti.kdim, ti.ldim, r, ti.dt);
+      if (off + need > kStaticScratchBytes) break;
+      StepItem it{first + pos, &W[pos], &G[pos], nullptr, nullptr, nullptr, ti.ldim};
+      it.R = reinterpret_cast<float*>(sp + off);
+      off += step_r_bytes(ti.left, ti.kdim, ti.ldim, r, ti.dt);
+      it.N = sp + off;
+      off += step_n_bytes(ti.ldim, r, ti.dt);
+      const size_t gp = step_gpad_bytes(ti.left, ti.kdim, ti.ldim, ti.dt);
+      it.Gpad = gp ? sp + off : nullptr;
+      off += gp;
+      it.ldr = projected_row_length(ti.left, ti.kdim, ti.ldim, ti.dt);
+      items.push_back(it);
+      ++pos;
+    }
+    s = run_chain(ctx, items, lr, ctx->stream);
     if (s) return s;
   }
   for (int i = 0; i < count; ++i) ctx->tensors[first + i].t += 1;
