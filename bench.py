@@ -22,15 +22,65 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch (one LLaMA-7B layer set, r = 1024) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs of paper_2403_03507_amd/traffic_probe.py, calibrated with a 1 GiB copy (see
-# profiles/step_llama7b_hbm_traffic.md).  Reported as roofline.traffic; null for other shapes.
-MEASURED_TRAFFIC_BYTES_7B = {
-    "project_left": 590.0e6 + 157.6e6,
-    "project_right": 205.7e6 + 45.1e6,
-    "back": 1090.4e6 + 404.8e6,
-    "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
+# HBM bytes per launch (one LLaMA-7B layer set, r = 1024) from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE) of `python3 bench.py --probe-traffic`, each scaled by what the same counter reads for the 1 GiB
+# copy at the end of that run (profiles/step_llama7b_hbm_traffic.md has the commands and the table).  Counters
+# cannot be read inside a timed run, so the figures are tied to the kernel sources they were measured on:
+# `sources` is the digest of the files named in TRAFFIC_SOURCES at that time, and roofline.traffic is reported
+# only while the digest still matches (null otherwise: re-run the probe and update both together).
+TRAFFIC_SOURCES = ["gemm_mfma_dl.hpp", "gemm_mfma.hpp", "gemm_dispatch.hpp", "common.hpp", "adam.hip"]
+MEASURED_TRAFFIC_7B = {
+    "sources": "unmeasured",
+    "bytes": {
+        "project_left": 590.0e6 + 157.6e6,
+        "project_right": 205.7e6 + 45.1e6,
+        "back": 1090.4e6 + 404.8e6,
+        "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
+    },
 }
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, "paper_2403_03507_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def probe_traffic(layers=3, steps=2):
+    """Workload of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: a few strictly serial steps of the library on
+    LLaMA-7B-shaped layer sets with given projectors (no refresh: its thousands of short launches would only slow
+    the counter run down), then ONE 1 GiB device-to-device copy whose traffic is known exactly (2^30 bytes read,
+    2^30 written) and calibrates the counter."""
+    import torch
+    from paper_2403_03507_amd import binding as gb
+    from paper_2403_03507_amd import workloads as wl
+    torch.cuda.set_device(0)
+    c = wl.CONFIGS["llama7b"]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    r = c["rank"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    W = [(torch.randn(m, n, generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(layers) for (m, n) in shapes]
+    G = [(torch.randn(m, n, generator=gen, device="cuda") * 0.01).to(torch.bfloat16) for _ in range(layers) for (m, n) in shapes]
+    opt = gb.GaLore(W, r, auto_refresh=False)
+    gb.galore_set_concurrency(opt.ctx, 1)
+    for p in opt.proj:  # traffic does not depend on the values: a scaled Gaussian block stands in for a projector
+        p.copy_((torch.randn(p.shape, generator=gen, device="cuda") / 64).to(torch.bfloat16))
+    n7 = len(shapes)
+    for s in range(steps):
+        for l in reversed(range(layers)):
+            opt.step(W[n7 * l: n7 * (l + 1)], G[n7 * l: n7 * (l + 1)], 1e-3, first=n7 * l)
+        torch.cuda.synchronize()
+        print("step", s, "done", flush=True)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    print("copy done; kernel sources digest", kernel_sources_digest(), flush=True)
 
 
 def main():
@@ -42,6 +92,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--refresh-iters", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-traffic", action="store_true",
+                    help="run only the workload of the rocprofv3 --pmc traffic runs (see probe_traffic) and exit")
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
@@ -65,6 +117,9 @@ def main():
         from paper_2403_03507_amd import build as lib_build
         lib_build.build()
     gb.lib()
+    if args.probe_traffic:
+        probe_traffic()
+        return
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
@@ -179,8 +234,12 @@ def main():
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
-        roofline["traffic"] = MEASURED_TRAFFIC_BYTES_7B[dominant] * (LPC if L % LPC == 0 else 1)
-        roofline["traffic_unit"] = "bytes per launch (L2 fetch + write-back counters; cache hits in the 256 MB MALL are included)"
+        if MEASURED_TRAFFIC_7B["sources"] == kernel_sources_digest():
+            roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"][dominant] * (LPC if L % LPC == 0 else 1)
+            roofline["traffic_unit"] = ("bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of `bench.py --probe-traffic`, scaled by a "
+                                        "1 GiB copy; hits in the 256 MB MALL are included; read on these kernel sources, not in this run)")
+        else:
+            roofline["traffic_unit"] = "null: the kernel sources changed since the counters were last read"
     per_stage = {}
     for k in gemm_stages:
         if prof[k][1]:
@@ -191,19 +250,56 @@ def main():
     cpu = None
     if not args.no_cpu_baseline and args.moments == "f32":  # the timed oracle is the fp32-moment step
         from oracle import galore_oracle as orc
-        dt = 0.0
-        for i in range(n_per_layer):  # layer 0, one tensor after the other; only the step itself is timed
-            Gs = Gpool[0][i].to("cpu").to(torch.float64).numpy()
-            Ps = opt.proj[i].to("cpu").to(torch.float64).numpy()
-            o = orc.GaLoreTensor(W[i].to("cpu").to(torch.float64).numpy(), r, dtype=dtype, auto_refresh=False)
-            o.set_projector(Ps)
-            t0 = time.time()
-            o.step(Gs, lr)
-            dt += time.time() - t0
-            del o, Gs, Ps
-        cpu = {"value": dt * 1e3, "unit": "ms per layer set", "cores": orc.num_threads(), "kind": "oracle",
+        threads = orc.num_threads()
+
+        def oracle_step_seconds(fraction):
+            """One oracle step on every tensor of layer 0, one after the other, on the first `fraction` of the
+            columns of a LEFT tensor / rows of a RIGHT tensor (the step is separable along the long side: column j
+            of W, M, V depends on column j of G only).  Only the step itself is timed."""
+            dt = 0.0
+            for i, (m, n) in enumerate(shapes):
+                left = m <= n
+                keep = max(1, int(round(max(m, n) * fraction)))
+                cut = (lambda x: x[:, :keep]) if left else (lambda x: x[:keep, :])
+                Gs = cut(Gpool[0][i]).to("cpu").to(torch.float64).numpy()
+                Ws = cut(W[i]).to("cpu").to(torch.float64).numpy()
+                Ps = opt.proj[i].to("cpu").to(torch.float64).numpy()
+                rr = orc.round_storage
+                t0 = time.time()
+                R = orc.project_left(Ps, Gs) if left else orc.project_right(Ps, Gs)
+                Mo, Vo = np.zeros_like(R), np.zeros_like(R)
+                N = orc.adam(R, Mo, Vo, 0.9, 0.999, 1e-8, 1)
+                (orc.apply_left if left else orc.apply_right)(Ws, Ps, N, lr, 0.25, 0.0)
+                Ws = rr(Ws, dtype)
+                dt += time.time() - t0
+            return dt
+
+        import numpy as np
+        dt_all = oracle_step_seconds(1.0)
+        ONE_CORE_FRACTION = 1.0 / 32
+        orc.set_num_threads(1)
+        dt_one = oracle_step_seconds(ONE_CORE_FRACTION)
+        orc.set_num_threads(threads)
+        # the oracle's refresh (one-sided Jacobi SVD) on ONE square tensor of side min(d, 2048) at the stack's
+        # rank-to-width ratio: its cost grows with the cube of the side, so the 7B stack's 4096 x 4096 would take
+        # about 8 times as long (minutes) and is left out of the default run
+        side = min(d, 2048)
+        rr_rank = max(1, r * side // d)
+        Gr = wl.GradientSource(side, side, 99, cfg["grad"], device="cpu", dtype=dtype, noise=cfg["noise"],
+                               **{k: cfg[k] for k in ("signal_rank", "sigma0", "decay") if k in cfg}).grad(0)
+        t0 = time.time()
+        orc.projector(Gr.to(torch.float64).numpy(), rr_rank)
+        dt_refresh = time.time() - t0
+        cpu = {"value": dt_all * 1e3, "unit": "ms per layer set", "cores": threads, "kind": "oracle",
                "sample": "one oracle step (project, Adam, apply; projectors given) on each of the %d tensors of one layer "
-                         "set of this workload, r=%d: %.1f s in all, no scaling" % (n_per_layer, r, dt)}
+                         "set of this workload, r=%d: %.1f s in all, no scaling" % (n_per_layer, r, dt_all),
+               "one_core": {"value": dt_one / ONE_CORE_FRACTION * 1e3, "unit": "ms per layer set", "cores": 1,
+                            "sample": "the same step on the first 1/32 of the columns (rows for the tall matrix) of each tensor, "
+                                      "%.1f s on one thread, scaled by 32 (the step is separable along the long side)" % dt_one},
+               "refresh": {"value": dt_refresh * 1e3, "unit": "ms per tensor", "cores": threads,
+                           "sample": "the oracle's Jacobi SVD of ONE %d x %d gradient of this stack's spectrum, r=%d: %.1f s; "
+                                     "cost grows with the cube of the side (a %d x %d tensor: about %.0fx)"
+                                     % (side, side, rr_rank, dt_refresh, d, d, (d / side) ** 3)}}
 
     out = {
         # BASELINE.json's metric on its headline configuration; other stacks are labelled as what they are

@@ -40,6 +40,15 @@ int oracle_num_threads(void) {
 #endif
 }
 
+/* Threads the parallel loops below use from now on (timing on one core vs. all cores; no effect on results). */
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 /* ---------- storage rounding (round-to-nearest-even from fp64) ------------ */
 
 /* Round x to a binary format with `p` significand bits (hidden bit included)

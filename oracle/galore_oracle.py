@@ -56,6 +56,7 @@ def lib():
         _lib = ctypes.CDLL(build())
         L = _lib
         L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_set_num_threads.argtypes = [ctypes.c_int]
         L.oracle_round_bf16.argtypes = [_dp, _i64]
         L.oracle_round_f32.argtypes = [_dp, _i64]
         L.oracle_project_left.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64]
@@ -86,6 +87,11 @@ def _p(a):
 
 def num_threads():
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n):
+    """Threads of the oracle's parallel loops from now on (for timing; results do not depend on it)."""
+    lib().oracle_set_num_threads(int(n))
 
 
 def round_storage(x, dtype):
