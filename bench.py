@@ -210,6 +210,8 @@ def main():
     right = [(m, n) for (m, n) in shapes if m > n]
     flops = {"project_left": sum(2.0 * m * n * r for m, n in left), "project_right": sum(2.0 * m * n * r for m, n in right)}
     flops["back"] = flops["project_left"] + flops["project_right"]
+    if prof["project_right"][1] == 0:  # both orientations ran in the one grouped projection launch (recorded as project_left)
+        flops["project_left"] += flops["project_right"]
     if L % LPC == 0:  # a launch covers the tensors of LPC layers
         flops = {k: v * LPC for k, v in flops.items()}
     sN = 2 if dtype == "bf16" else 4
@@ -229,7 +231,8 @@ def main():
         peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
         achieved = flops[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
         # bf16 tensors of these shapes run on the large-tile kernel, fp32 tensors on the general one
-        roofline = {"kernel": ("gemm_dl_kernel/" if dtype == "bf16" else "gemm_group_kernel/") + dominant, "bound": "mfma",
+        kname = {"project_left": "proj_dl_kernel/project", "project_right": "gemm_dl_kernel/project_right", "back": "gemm_dl_kernel/back"}
+        roofline = {"kernel": kname[dominant] if dtype == "bf16" else "gemm_group_kernel/" + dominant, "bound": "mfma",
                     "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]

@@ -199,7 +199,11 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
  * stream and on up to two library-owned streams of default priority, forked from and joined
  * back into the context's stream with events inside the call, so tail waves of one GEMM and the
  * bandwidth-bound Adam pass overlap with another chain's MFMA work.  1 = strictly serial on the
- * context's stream.  Results do not depend on the setting. */
+ * context's stream.  W, M, V agree between settings to the fp32 rounding of R, and bit for bit whenever
+ * the projection launches cut no tile into K pieces (short sides under 512) or cut the same tiles
+ * the same way: the projection sums the K range of a tile that does not fill a round of the chip
+ * in pieces, and which tiles those are depends on what shares the launch.  For one setting and one
+ * sequence of calls results are bit-identical from run to run. */
 galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
 
 /* Overlap of consecutive calls (off by default; on = 0 off, 1 or 2 = two calls in flight, 3 =
@@ -216,8 +220,9 @@ galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
  * stream, the library joins first and proceeds as without overlap.  The caller must call
  * galore_join() before work on the context's stream (or the host) reads or writes W, M, V or the
  * projectors of tensors passed since the last join, and must not overwrite their G buffers before
- * it.  galore_set_concurrency does not apply to overlapped calls.  Results do not depend on the
- * setting.  Turning it off, or changing the number of calls in flight, joins.
+ * it.  galore_set_concurrency does not apply to overlapped calls.  Results depend on the setting as
+ * described for galore_set_concurrency (fp32 rounding of R at most).  Turning it off, or changing the
+ * number of calls in flight, joins.
  * Errors: GALORE_ERR_INVALID_ARG for on outside 0 ... 3. */
 galore_status galore_set_call_overlap(galore_ctx* ctx, int32_t on);
 
@@ -321,8 +326,9 @@ galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_te
  * device time in milliseconds and the number of bracketed launches (arrays of
  * GALORE_STAGE_COUNT entries, host memory).  A refresh counts as one launch per tensor group. */
 typedef enum {
-  GALORE_STAGE_PROJECT_LEFT = 0,   /* R = P^T G  (grouped MFMA GEMM) */
-  GALORE_STAGE_PROJECT_RIGHT = 1,  /* R = G Q */
+  GALORE_STAGE_PROJECT_LEFT = 0,   /* the grouped projection launch: R = P^T G, and R = G Q of the tensors that share it
+                                      (bf16 tensors on the large-tile kernel: both orientations in one launch) */
+  GALORE_STAGE_PROJECT_RIGHT = 1,  /* R = G Q of tensors on the general kernel (fp32, odd shapes) */
   GALORE_STAGE_ADAM = 2,           /* fused low-rank Adam (one launch per orientation) */
   GALORE_STAGE_BACK = 3,           /* W -= lr*alpha*(P N | N Q^T)  (GEMM + weight epilogue) */
   GALORE_STAGE_TRANSPOSE = 4,      /* proj -> proj_t */

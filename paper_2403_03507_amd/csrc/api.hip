@@ -95,6 +95,7 @@ struct galore_ctx {
   // one of the first `slots` library streams, taking turns, and the context's stream is not made to
   // wait until galore_join.  The chunk on stream h uses share h of the workspace (one of `slots`
   // equal parts), so stream order alone protects the workspace.
+  bool merged_projection = true;  // LEFT and RIGHT projections of the large-tile kernel in one launch (see gemm_proj_dl.hpp)
   bool overlap_calls = false;
   int slots = 2;
   bool unjoined = false;          // library streams hold work the context's stream has not waited for
@@ -218,7 +219,8 @@ struct StepItem {
   int64_t ldr;   // row length of R
 };
 
-galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, float lr, hipStream_t stream) {
+galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, float lr, hipStream_t stream,
+                        float* slabs = nullptr, size_t slab_bytes = 0) {
   const galore_hparams& hp = ctx->hp;
   const int r = hp.rank;
   // The list may mix dtypes; launches are split by dtype (and by orientation where layouts differ).
@@ -241,40 +243,59 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
       if (e != hipSuccess) return hip_fail(ctx, e, "projector transpose launch");
     }
     // K1: project.  Both operands are read from layouts in which as much as possible is
-    // contiguous along the contraction index; only G of a LEFT tensor is not.
-    for (int left = 1; left >= 0; --left) {
-      GemmGroup g{};
+    // contiguous along the contraction index; only G of a LEFT tensor is not.  bf16 tensors that meet the
+    // large-tile kernel's rules go into ONE launch, LEFT and RIGHT together (the layout of B is a field of
+    // each problem there); the rest take the general kernel, one launch per orientation.
+    {
+      ProjGroup pg{};
+      GemmGroup rest[2] = {};  // [0] RIGHT, [1] LEFT
       PadGroup pads{};
-      for (const StepItem& it : items) {
-        const TensorInfo& ti = ctx->tensors[it.tensor];
-        if (ti.dt != dt || (int)ti.left != left) continue;
-        GemmProblem& p = g.p[g.count++];
-        if (left && it.Gpad) {  // the same product on the padded copy: the extra columns of G and of R are zero
-          PadProblem& q = pads.p[pads.count++];
-          q.src = it.G->data; q.lds = (int)it.G->ld;
-          q.dst = it.Gpad; q.ldd = (int)it.ldr;
-          q.rows = (int)ti.rows; q.cols = (int)ti.cols;
-          p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
-          p.B = it.Gpad; p.ldb = (int)it.ldr;
-          p.M = r; p.N = (int)it.ldr; p.K = (int)ti.rows;
-          p.C = it.R; p.ldc = (int)it.ldr;
-        } else if (left) {  // R (r x n) = P^T G : A = proj_t as [M=r][K=m], B = G as [K=m][N=n]
-          p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
-          p.B = it.G->data; p.ldb = (int)it.G->ld;
-          p.M = r; p.N = (int)ti.cols; p.K = (int)ti.rows;
-          p.C = it.R; p.ldc = (int)ti.cols;
-        } else {     // R (m x r) = G Q : A = G as [M=m][K=n], B = proj_t as [N=r][K=n]
-          p.A = it.G->data; p.lda = (int)it.G->ld;
-          p.B = ti.st.proj_t.data; p.ldb = (int)ti.st.proj_t.ld;
-          p.M = (int)ti.rows; p.N = r; p.K = (int)ti.cols;
-          p.C = it.R; p.ldc = r;
+      for (int left = 1; left >= 0; --left) {
+        for (const StepItem& it : items) {
+          const TensorInfo& ti = ctx->tensors[it.tensor];
+          if (ti.dt != dt || (int)ti.left != left) continue;
+          GemmProblem p{};
+          if (left && it.Gpad) {  // the same product on the padded copy: the extra columns of G and of R are zero
+            PadProblem& q = pads.p[pads.count++];
+            q.src = it.G->data; q.lds = (int)it.G->ld;
+            q.dst = it.Gpad; q.ldd = (int)it.ldr;
+            q.rows = (int)ti.rows; q.cols = (int)ti.cols;
+            p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
+            p.B = it.Gpad; p.ldb = (int)it.ldr;
+            p.M = r; p.N = (int)it.ldr; p.K = (int)ti.rows;
+            p.C = it.R; p.ldc = (int)it.ldr;
+          } else if (left) {  // R (r x n) = P^T G : A = proj_t as [M=r][K=m], B = G as [K=m][N=n]
+            p.A = ti.st.proj_t.data; p.lda = (int)ti.st.proj_t.ld;
+            p.B = it.G->data; p.ldb = (int)it.G->ld;
+            p.M = r; p.N = (int)ti.cols; p.K = (int)ti.rows;
+            p.C = it.R; p.ldc = (int)ti.cols;
+          } else {     // R (m x r) = G Q : A = G as [M=m][K=n], B = proj_t as [N=r][K=n]
+            p.A = it.G->data; p.lda = (int)it.G->ld;
+            p.B = ti.st.proj_t.data; p.ldb = (int)ti.st.proj_t.ld;
+            p.M = (int)ti.rows; p.N = r; p.K = (int)ti.cols;
+            p.C = it.R; p.ldc = r;
+          }
+          ProjProblem q{};
+          q.A = p.A; q.B = p.B; q.R = static_cast<float*>(p.C);
+          q.M = p.M; q.N = p.N; q.K = p.K; q.lda = p.lda; q.ldb = p.ldb; q.ldr = p.ldc;
+          q.b_kcontig = left ? 0 : 1;
+          if (dt == DType::BF16 && ctx->merged_projection && proj_problem_fits(q)) pg.p[pg.count++] = q;
+          else rest[left].p[rest[left].count++] = p;
         }
       }
-      ProfScope prof(ctx, left ? GALORE_STAGE_PROJECT_LEFT : GALORE_STAGE_PROJECT_RIGHT, g.count > 0, stream);
-      hipError_t e = launch_pad_rows_group(pads, stream);
-      if (e != hipSuccess) return hip_fail(ctx, e, "row padding launch");
-      e = launch_gemm_group(g, dt, /*a_kcontig=*/true, /*b_kcontig=*/!left, Epilogue::StoreF32, stream);
-      if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
+      {
+        ProfScope prof(ctx, GALORE_STAGE_PROJECT_LEFT, pg.count + rest[1].count > 0, stream);
+        hipError_t e = launch_pad_rows_group(pads, stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "row padding launch");
+        e = launch_proj_group(pg, slabs, slab_bytes, stream);
+        if (e == hipSuccess) e = launch_gemm_group(rest[1], dt, /*a_kcontig=*/true, /*b_kcontig=*/false, Epilogue::StoreF32, stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
+      }
+      {
+        ProfScope prof(ctx, GALORE_STAGE_PROJECT_RIGHT, rest[0].count > 0, stream);
+        hipError_t e = launch_gemm_group(rest[0], dt, /*a_kcontig=*/true, /*b_kcontig=*/true, Epilogue::StoreF32, stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
+      }
     }
     // K2: Adam on R.  N always leaves as (long side) x r: transposed for LEFT tensors.
     for (int left = 1; left >= 0; --left) {
@@ -401,12 +422,19 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
     off += gp;
     it.ldr = projected_row_length(ti.left, ti.kdim, ti.ldim, ti.dt);
   }
+  // What is left of this call's part of the workspace holds the partial tiles of the projection GEMM
+  // (at most 64 MiB per chain are of use: one 256 x 256 fp32 tile per CU).
+  const size_t region_end = overlap ? (size_t)(ctx->parity + 1) * workspace_share(ctx) : ctx->ws_bytes;
+  const size_t slab_off = align_up(off);
+  size_t slab_avail = region_end > slab_off ? region_end - slab_off : 0;
+  constexpr size_t kSlabMax = (size_t)64 << 20;
   if (overlap) {
     const int h = ctx->parity;
     hipError_t e = hipEventRecord(ctx->fork_ev, ctx->stream);  // inputs produced on the context's stream are ready
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->aux[h], ctx->fork_ev, 0);
     if (e != hipSuccess) return hip_fail(ctx, e, "forking streams");
-    const galore_status st = run_chain(ctx, items, lr, ctx->aux[h]);
+    const galore_status st = run_chain(ctx, items, lr, ctx->aux[h], reinterpret_cast<float*>(ctx->ws + slab_off),
+                                       slab_avail < kSlabMax ? slab_avail : kSlabMax);
     for (const StepItem& it : items) ctx->in_flight[it.tensor] = (char)(1 + h);
     ctx->unjoined = true;
     ctx->parity = (ctx->parity + 1) % ctx->slots;
@@ -416,7 +444,8 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
   int lanes = ctx->lanes;
   if (lanes > 1 && !library_streams_ready(ctx)) lanes = 1;
   if ((int)items.size() < 2) lanes = 1;
-  if (lanes <= 1) return run_chain(ctx, items, lr, ctx->stream);
+  if (lanes <= 1)
+    return run_chain(ctx, items, lr, ctx->stream, reinterpret_cast<float*>(ctx->ws + slab_off), slab_avail < kSlabMax ? slab_avail : kSlabMax);
 
   // Greedy balance by cost (m n, as r is shared): heaviest tensor first, always into the lightest chain.
   std::vector<int> order(items.size());
@@ -439,7 +468,11 @@ galore_status run_step_chunk(galore_ctx* ctx, std::vector<StepItem>& items, floa
   if (e != hipSuccess) return hip_fail(ctx, e, "forking streams");
   galore_status st = GALORE_OK;
   for (int c = 0; c < lanes && st == GALORE_OK; ++c)
-    if (!chain[c].empty()) st = run_chain(ctx, chain[c], lr, c == 0 ? ctx->stream : ctx->aux[c - 1]);
+    if (!chain[c].empty()) {
+      size_t part = (slab_avail / (size_t)lanes) & ~(size_t)255;  // every chain its own slab area
+      st = run_chain(ctx, chain[c], lr, c == 0 ? ctx->stream : ctx->aux[c - 1],
+                     reinterpret_cast<float*>(ctx->ws + slab_off + (size_t)c * part), part < kSlabMax ? part : kSlabMax);
+    }
   // always join, also after a failed launch, so the caller's stream stays ordered after our streams
   for (int c = 1; c < lanes; ++c) {
     if (chain[c].empty()) continue;
@@ -791,7 +824,9 @@ galore_status galore_step_static(galore_ctx* ctx, const galore_tensor* W, const 
       items.push_back(it);
       ++pos;
     }
-    s = run_chain(ctx, items, lr, ctx->stream);
+    const size_t slab_off = align_up(off);  // what is left of the array holds the projection's partial tiles
+    s = run_chain(ctx, items, lr, ctx->stream, reinterpret_cast<float*>(sp + slab_off),
+                  kStaticScratchBytes > slab_off ? kStaticScratchBytes - slab_off : 0);
     if (s) return s;
   }
   for (int i = 0; i < count; ++i) ctx->tensors[first + i].t += 1;
@@ -952,7 +987,19 @@ galore_status galore_project(const galore_tensor* proj_t, const galore_tensor* G
     p.M = (int)G->rows; p.N = (int)r; p.K = (int)G->cols;
   }
   p.C = R->data; p.ldc = (int)R->ld;
-  hipError_t e = launch_gemm_group(g, (DType)G->dtype, true, !left, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
+  // the kernel galore_step uses for this tensor: the grouped projection where its rules are met, else the general GEMM
+  ProjGroup pg{};
+  ProjProblem& q = pg.p[0];
+  q.A = p.A; q.B = p.B; q.R = static_cast<float*>(p.C);
+  q.M = p.M; q.N = p.N; q.K = p.K; q.lda = p.lda; q.ldb = p.ldb; q.ldr = p.ldc;
+  q.b_kcontig = left ? 0 : 1;
+  hipError_t e;
+  if ((DType)G->dtype == DType::BF16 && proj_problem_fits(q)) {
+    pg.count = 1;
+    e = launch_proj_group(pg, nullptr, 0, static_cast<hipStream_t>(hip_stream));
+  } else {
+    e = launch_gemm_group(g, (DType)G->dtype, true, !left, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
+  }
   return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "projection GEMM launch");
 }
 

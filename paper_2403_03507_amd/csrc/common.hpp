@@ -47,6 +47,35 @@ enum class Epilogue : int32_t {
 hipError_t launch_gemm_group(GemmGroup& g, DType dt, bool a_kcontig, bool b_kcontig, Epilogue epi,
                              hipStream_t stream);
 
+// ---- grouped projection GEMM (bf16 operands, fp32 result): R = A * B with A as [M][K] -------------------
+// LEFT tensors:  A = the transposed projector (r x m), B = G as [K = m][N = n]  (b_kcontig = 0)
+// RIGHT tensors: A = G (m x n),                       B = the transposed projector as [N = r][K = n] (b_kcontig = 1)
+struct ProjProblem {
+  const void* A;
+  const void* B;
+  float* R;       // M x N, row stride ldr
+  int32_t M, N, K;
+  int32_t lda, ldb, ldr;
+  int32_t b_kcontig;
+  int32_t tile_begin, tiles_m, tiles_n;  // filled by the launcher
+};
+
+struct ProjGroup {
+  int32_t count;
+  int32_t total_tiles;
+  int32_t regular_tiles;  // tiles [0, regular_tiles) run over their whole K range on the persistent grid
+  int32_t pieces;         // the remaining tiles are cut into this many K ranges, one work item each
+  float* slabs;           // partial tiles of the pieces (tile-local row-major, fp32), summed by the reduce kernel
+  ProjProblem p[kMaxGroup];
+};
+
+// True if the problem meets the kernel's rules (16-byte aligned operands and rows, K a multiple of 64, ...);
+// problems that do not go through launch_gemm_group.
+bool proj_problem_fits(const ProjProblem& p);
+// Launch one grouped projection; every problem must fit.  `slabs` (256-byte aligned, slab_bytes long, may be
+// NULL / 0) is scratch for the partial tiles; without enough of it the launch simply runs whole tiles only.
+hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipStream_t stream);
+
 // ---- grouped low-rank Adam -----------------------------------------------------------------
 struct AdamProblem {
   const float* R;

@@ -50,7 +50,9 @@ template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
   // Byte offsets (relative to the tile's first k) of the PER_WAVE 16-byte pieces this lane
   // fetches for every K step; computed once per block.  X = extent of the M/N index.
   unsigned voff[PER_WAVE];
-  __device__ __forceinline__ void plan(int ld, int x0, int X, int wave, int lane) {
+  __device__ __forceinline__ void plan(int ld, int x0, int X, int wave, int lane) { plan_into(voff, ld, x0, X, wave, lane); }
+  // The same plan into an array the caller owns (a kernel that switches layouts between tiles keeps one).
+  static __device__ __forceinline__ void plan_into(unsigned (&voff)[PER_WAVE], int ld, int x0, int X, int wave, int lane) {
 #pragma unroll
     for (int it = 0; it < PER_WAVE; ++it) {
       const int c = wave + it * NW;
@@ -82,6 +84,10 @@ template <bool KCONTIG, int BX, int BK, int NW> struct DlOperand {
   // workgroups that share them and not again soon, so that they do not displace the other
   // operand's panels (which the XCD needs again in its next round) from L2.
   template <bool STREAM> __device__ __forceinline__ void issue(const void* src, unsigned lds_tile, int wave) const {
+    issue_from<STREAM>(voff, src, lds_tile, wave);
+  }
+  template <bool STREAM>
+  static __device__ __forceinline__ void issue_from(const unsigned (&voff)[PER_WAVE], const void* src, unsigned lds_tile, int wave) {
 #pragma unroll
     for (int it = 0; it < PER_WAVE; ++it) {
       const unsigned dst = __builtin_amdgcn_readfirstlane(lds_tile + (wave + it * NW) * 1024);

@@ -112,6 +112,51 @@ def test_weight_update_of_odd_row_lengths_on_the_large_tile_kernel():
     _run_stack(shapes, "bf16", 64, steps=2, update_gap=2, weight_decay=0.1)
 
 
+def _run_with_given_projectors(shapes, rank, steps, lr=1e-3, chunked=False):
+    """bf16 steps with seeded orthonormal projectors (the oracle's SVD of the larger shapes would take minutes):
+    W per entry, M and V to 1e-5 against the oracle."""
+    dtype = "bf16"
+    srcs = [wl.GradientSource(m, n, 600 + i, "lowrank", dtype=dtype, signal_rank=32, noise=0.01) for i, (m, n) in enumerate(shapes)]
+    W0 = [wl.make_weight(m, n, 620 + i, dtype) for i, (m, n) in enumerate(shapes)]
+    Wd = [w.cuda() for w in W0]
+    opt = gb.GaLore(Wd, rank, auto_refresh=False)
+    oracles = []
+    lr = f32(lr)
+    for i, (m, n) in enumerate(shapes):
+        P = wl.random_orthonormal(min(m, n), rank, 640 + i).to(torch.bfloat16)
+        opt.proj[i].copy_(P)
+        o = orc.GaLoreTensor(to64(W0[i]), rank, scale=f32(0.25), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), dtype=dtype,
+                             auto_refresh=False)
+        o.set_projector(to64(P))
+        oracles.append(o)
+    for step in range(steps):
+        G = [s.grad(step) for s in srcs]
+        Gd = [g.cuda() for g in G]
+        if chunked:
+            for i in reversed(range(len(shapes))):
+                opt.step([Wd[i]], [Gd[i]], lr, first=i)
+        else:
+            opt.step(Wd, Gd, lr)
+        torch.cuda.synchronize()
+        for i, o in enumerate(oracles):
+            o.step(to64(G[i]), lr)
+            assert relF(to64(opt.M[i]), o.M) <= 1e-5, (step, i, shapes[i])
+            assert relF(to64(opt.V[i]), o.V) <= 1e-5, (step, i, shapes[i])
+            check_bf16_weights(to64(Wd[i]), o.W, to64(W0[i]), step + 1, lr, 0.25, where=(step, i, shapes[i]))
+    opt.close()
+
+
+@pytest.mark.parametrize("chunked", [False, True])
+def test_grouped_projection_with_k_pieces(chunked):
+    # The projection of bf16 tensors whose short side is a multiple of 64 runs as ONE launch for both orientations,
+    # and tiles that do not fill a round of the grid are cut into K pieces whose partial tiles are summed afterwards.
+    # Short sides 512 / 1024 / 1536 give 8 / 16 / 24 K steps, i.e. 2 / 4 / 6 pieces when a tensor runs alone (one
+    # call per tensor) and the group's smallest count when they share a launch; 1000 and 1096 columns leave ragged
+    # tiles whose slabs are only partly written; rank 192 leaves a ragged tile along r.
+    shapes = [(512, 1024), (1024, 512), (512, 512), (1024, 1000), (1096, 1024), (1536, 1536)]
+    _run_with_given_projectors(shapes, 192, steps=2, chunked=chunked)
+
+
 def _offset_view(t, pad=3):
     """t inside a wider buffer that starts one element into its allocation: leading dimension cols + pad,
     first element only element-aligned, NaN everywhere outside the matrix."""
