@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
+    ap.add_argument("--fused-adam", type=int, choices=[0, 1], default=0,
+                    help="1: Adam in the epilogue of the projection GEMM (two kernels per step); 0: separate Adam kernel (three)")
     ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="overlapped calls: calls in flight (library streams used)")
     ap.add_argument("--layers-per-call", type=int, default=1, choices=[1, 2],
                     help="layers handed to one galore_step call (the small stacks fill the chip better with 2)")
@@ -151,6 +153,7 @@ def main():
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
                     workspace_factor=args.in_flight * args.layers_per_call)
     gb.galore_set_concurrency(opt.ctx, args.lanes)
+    gb.galore_set_fused_adam(opt.ctx, args.fused_adam)
     overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
     gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
@@ -220,7 +223,7 @@ def main():
     else:
         adam_bytes = sum(r * max(m, n) * (4 * 5 + sN) for m, n in shapes)  # read R, M, V; write M, V, N
     stage_ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}        # average duration of one launch
-    stage_ms["adam"] = prof["adam"][0] / max(K * L, 1)                  # Adam: two launches (one per orientation) per layer
+    stage_ms["adam"] = prof["adam"][0] / max(K * L, 1)                  # Adam: two launches (one per orientation) per layer; 0 when fused
     gemm_stages = ["project_left", "project_right", "back"]
     dominant = max(gemm_stages + ["adam"], key=lambda k: prof[k][0])
     if dominant == "adam":
@@ -247,7 +250,8 @@ def main():
     for k in gemm_stages:
         if prof[k][1]:
             per_stage[k] = {"ms_per_launch": stage_ms[k], "tflops": flops[k] / (stage_ms[k] * 1e-3) / 1e12}
-    per_stage["adam"] = {"ms_per_launch": stage_ms["adam"], "gbs": adam_bytes / (stage_ms["adam"] * 1e-3) / 1e9}
+    if prof["adam"][1]:
+        per_stage["adam"] = {"ms_per_launch": stage_ms["adam"], "gbs": adam_bytes / (stage_ms["adam"] * 1e-3) / 1e9}
 
     # ---- CPU baseline: the fp64 oracle on a bounded sample --------------------------------------------
     cpu = None
@@ -319,6 +323,7 @@ def main():
                                                                                    "fp32" if args.moments == "f32" else "8-bit", r,
                                                                                    "per-layer" if LPC == 1 else "%d-layer" % LPC, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
+                   "adam": "in the projection GEMM's epilogue" if args.fused_adam else "separate kernel",
                    "schedule": "consecutive calls overlap on %d library streams, one join per step" % overlap if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},
         "roofline": roofline,

@@ -206,6 +206,14 @@ galore_status galore_refresh_subspace(galore_ctx* ctx, const galore_tensor* G, i
  * sequence of calls results are bit-identical from run to run. */
 galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes);
 
+/* Adam inside the projection (off by default; 1 = on).  When on, a bf16 tensor with fp32 moments whose
+ * projection runs on the large-tile kernel gets the update block of Algorithm 2 (moments, bias correction,
+ * N) computed in that GEMM's epilogue, on the accumulators: R is never written to memory and read back,
+ * and the step of such a tensor is two kernels instead of three.  Other tensors (fp32, 8-bit moments,
+ * shapes the large-tile kernel does not take) keep the separate Adam kernel.  Both paths evaluate the
+ * same fp32 expression on the same R: W, M, V are bit-identical between the two settings. */
+galore_status galore_set_fused_adam(galore_ctx* ctx, int32_t on);
+
 /* Overlap of consecutive calls (off by default; on = 0 off, 1 or 2 = two calls in flight, 3 =
  * three).  When on, every galore_step call runs as ONE chain (all its tensors grouped in each
  * kernel launch) on one of `on` library-owned streams of default priority, taking turns from call

@@ -50,7 +50,7 @@ EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "gal
            "galore_refresh_subspace", "galore_get_step", "galore_set_step", "galore_last_error",
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
-           "galore_set_call_overlap", "galore_join", "galore_get_stream",
+           "galore_set_call_overlap", "galore_set_fused_adam", "galore_join", "galore_get_stream",
            "galore_two_sided_workspace_bytes", "galore_two_sided_step", "galore_two_sided_refresh"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
@@ -86,6 +86,7 @@ def lib():
         L.galore_project_back.argtypes = [tp, tp, tp, f32, f32, f32, vp]
         L.galore_set_concurrency.argtypes = [vp, i32]
         L.galore_set_call_overlap.argtypes = [vp, i32]
+        L.galore_set_fused_adam.argtypes = [vp, i32]
         L.galore_join.argtypes = [vp]
         L.galore_get_stream.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_void_p)]
         tsp = ctypes.POINTER(galore_two_sided_state)
@@ -213,6 +214,10 @@ def galore_set_call_overlap(ctx, on):
     _check(lib().galore_set_call_overlap(ctx, int(on)), ctx)  # False/0 off, True/1/2 two calls in flight, 3 three
 
 
+def galore_set_fused_adam(ctx, on):
+    _check(lib().galore_set_fused_adam(ctx, 1 if on else 0), ctx)
+
+
 def galore_join(ctx):
     _check(lib().galore_join(ctx), ctx)
 
@@ -324,6 +329,9 @@ class GaLore:
 
     def set_call_overlap(self, on):
         galore_set_call_overlap(self.ctx, on)
+
+    def set_fused_adam(self, on):
+        galore_set_fused_adam(self.ctx, on)
 
     def join(self):
         galore_join(self.ctx)

@@ -95,6 +95,7 @@ struct galore_ctx {
   // one of the first `slots` library streams, taking turns, and the context's stream is not made to
   // wait until galore_join.  The chunk on stream h uses share h of the workspace (one of `slots`
   // equal parts), so stream order alone protects the workspace.
+  bool fused_adam = false;        // Adam in the epilogue of the projection launch (galore_set_fused_adam)
   bool merged_projection = true;  // LEFT and RIGHT projections of the large-tile kernel in one launch (see gemm_proj_dl.hpp)
   bool overlap_calls = false;
   int slots = 2;
@@ -246,12 +247,15 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
     // contiguous along the contraction index; only G of a LEFT tensor is not.  bf16 tensors that meet the
     // large-tile kernel's rules go into ONE launch, LEFT and RIGHT together (the layout of B is a field of
     // each problem there); the rest take the general kernel, one launch per orientation.
+    std::vector<char> adam_done(items.size(), 0);  // tensors whose Adam ran inside the projection launch
     {
-      ProjGroup pg{};
+      ProjGroup pg{}, pgf{};   // pgf: with the update block of Algorithm 2 in the epilogue (galore_set_fused_adam)
+      pgf.beta1 = hp.beta1; pgf.beta2 = hp.beta2; pgf.eps = hp.eps;
       GemmGroup rest[2] = {};  // [0] RIGHT, [1] LEFT
       PadGroup pads{};
       for (int left = 1; left >= 0; --left) {
-        for (const StepItem& it : items) {
+        for (size_t ii = 0; ii < items.size(); ++ii) {
+          const StepItem& it = items[ii];
           const TensorInfo& ti = ctx->tensors[it.tensor];
           if (ti.dt != dt || (int)ti.left != left) continue;
           GemmProblem p{};
@@ -279,15 +283,33 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
           q.A = p.A; q.B = p.B; q.R = static_cast<float*>(p.C);
           q.M = p.M; q.N = p.N; q.K = p.K; q.lda = p.lda; q.ldb = p.ldb; q.ldr = p.ldc;
           q.b_kcontig = left ? 0 : 1;
-          if (dt == DType::BF16 && ctx->merged_projection && proj_problem_fits(q)) pg.p[pg.count++] = q;
-          else rest[left].p[rest[left].count++] = p;
+          if (dt == DType::BF16 && ctx->merged_projection && proj_problem_fits(q)) {
+            if (ctx->fused_adam && !ti.q8) {
+              const double k = (double)(ti.t + 1);
+              q.Mo = static_cast<float*>(ti.st.m.data);
+              q.Vo = static_cast<float*>(ti.st.v.data);
+              q.Nout = it.N;
+              q.ldm = q.cols_valid = left ? (int)ti.cols : r;   // M, V are dense; R may carry padded columns
+              q.ldn = r;                                         // N is always (long side) x r
+              q.n_transposed = left;
+              q.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
+              q.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
+              pgf.p[pgf.count++] = q;
+              adam_done[ii] = 1;
+            } else {
+              pg.p[pg.count++] = q;
+            }
+          } else {
+            rest[left].p[rest[left].count++] = p;
+          }
         }
       }
       {
-        ProfScope prof(ctx, GALORE_STAGE_PROJECT_LEFT, pg.count + rest[1].count > 0, stream);
+        ProfScope prof(ctx, GALORE_STAGE_PROJECT_LEFT, pg.count + pgf.count + rest[1].count > 0, stream);
         hipError_t e = launch_pad_rows_group(pads, stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "row padding launch");
-        e = launch_proj_group(pg, slabs, slab_bytes, stream);
+        e = launch_proj_group(pgf, slabs, slab_bytes, stream, /*fuse_adam=*/true);
+        if (e == hipSuccess) e = launch_proj_group(pg, slabs, slab_bytes, stream);
         if (e == hipSuccess) e = launch_gemm_group(rest[1], dt, /*a_kcontig=*/true, /*b_kcontig=*/false, Epilogue::StoreF32, stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "projection GEMM launch");
       }
@@ -304,9 +326,10 @@ galore_status run_chain(galore_ctx* ctx, const std::vector<StepItem>& items, flo
       g.beta1 = hp.beta1; g.beta2 = hp.beta2; g.eps = hp.eps;
       g8.beta1 = hp.beta1; g8.beta2 = hp.beta2; g8.eps = hp.eps;
       g8.omb1 = 1.0f - hp.beta1; g8.omb2 = 1.0f - hp.beta2;
-      for (const StepItem& it : items) {
+      for (size_t ii = 0; ii < items.size(); ++ii) {
+        const StepItem& it = items[ii];
         const TensorInfo& ti = ctx->tensors[it.tensor];
-        if (ti.dt != dt || (int)ti.left != left) continue;
+        if (ti.dt != dt || (int)ti.left != left || adam_done[ii]) continue;
         const double k = (double)(ti.t + 1);
         const float ic1 = (float)(1.0 / (1.0 - std::pow((double)hp.beta1, k)));
         const float ic2 = (float)(1.0 / (1.0 - std::pow((double)hp.beta2, k)));
@@ -890,6 +913,12 @@ galore_status galore_set_concurrency(galore_ctx* ctx, int32_t lanes) {
   if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
   if (lanes < 1 || lanes > 3) return fail(ctx, GALORE_ERR_INVALID_ARG, "lanes must be 1, 2 or 3");
   ctx->lanes = lanes;
+  return GALORE_OK;
+}
+
+galore_status galore_set_fused_adam(galore_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(nullptr, GALORE_ERR_INVALID_ARG, "ctx is NULL");
+  ctx->fused_adam = on != 0;
   return GALORE_OK;
 }
 

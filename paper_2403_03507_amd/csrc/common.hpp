@@ -58,6 +58,14 @@ struct ProjProblem {
   int32_t lda, ldb, ldr;
   int32_t b_kcontig;
   int32_t tile_begin, tiles_m, tiles_n;  // filled by the launcher
+  // Adam in the epilogue (launch_proj_group with fuse_adam): R is not stored; the tile's entries go straight
+  // into the update block of Algorithm 2.  Mo, Vo: fp32 moments with R's shape (row stride ldm, cols_valid <= N
+  // columns: R may carry padded columns); Nout: bf16, n_transposed ? cols_valid x M (row stride ldn) : M x cols_valid.
+  float* Mo;
+  float* Vo;
+  void* Nout;
+  int32_t ldm, ldn, cols_valid, n_transposed;
+  float inv_c1, inv_c2;
 };
 
 struct ProjGroup {
@@ -66,6 +74,7 @@ struct ProjGroup {
   int32_t regular_tiles;  // tiles [0, regular_tiles) run over their whole K range on the persistent grid
   int32_t pieces;         // the remaining tiles are cut into this many K ranges, one work item each
   float* slabs;           // partial tiles of the pieces (tile-local row-major, fp32), summed by the reduce kernel
+  float beta1, beta2, eps;  // fused Adam only
   ProjProblem p[kMaxGroup];
 };
 
@@ -74,7 +83,9 @@ struct ProjGroup {
 bool proj_problem_fits(const ProjProblem& p);
 // Launch one grouped projection; every problem must fit.  `slabs` (256-byte aligned, slab_bytes long, may be
 // NULL / 0) is scratch for the partial tiles; without enough of it the launch simply runs whole tiles only.
-hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipStream_t stream);
+// fuse_adam: every problem carries Mo, Vo, Nout, ...; M, V are updated and N written by the GEMM's epilogue (and by
+// the kernel that sums the partial tiles), R is left untouched.
+hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipStream_t stream, bool fuse_adam = false);
 
 // ---- grouped low-rank Adam -----------------------------------------------------------------
 struct AdamProblem {

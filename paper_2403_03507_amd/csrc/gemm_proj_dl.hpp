@@ -10,10 +10,16 @@
 //     cut into `pieces` K ranges, one item each, spread over the CUs; each piece stores its partial tile in a
 //     slab and proj_reduce_kernel adds the slabs in a fixed order afterwards (no atomics, no waiting between
 //     workgroups, bit-identical from run to run);
-//   * the K steps of consecutive items form one stream through the ring, as in the large-tile kernel.
+//   * the K steps of consecutive items form one stream through the ring, as in the large-tile kernel;
+//   * FUSE: the update block of Algorithm 2 (moments, bias correction, N) runs in the epilogue on the
+//     accumulators themselves, so R never travels to memory and back (8 of the 22 bytes per entry the separate
+//     Adam kernel moves).  The accumulator layout serves as it is: a lane holds one column and groups of four
+//     consecutive rows, so M and V are read and written as 128-byte row segments per half-wave, and N leaves
+//     transposed (LEFT tensors) as 8-byte pieces of four consecutive r, or row-wise (RIGHT tensors).
 #pragma once
 #include <type_traits>
 
+#include "adam_entry.hpp"
 #include "gemm_mfma_dl.hpp"
 
 namespace galore {
@@ -27,10 +33,12 @@ struct ProjItem {
   int ldc;       // row stride of dst
   int rows, cols;  // valid extent from the tile origin (may exceed the tile)
   int bkc;       // layout of B
-  int round;     // pass of the persistent grid (-1: a split piece)
+  int kind;      // kWhole or kPiece
+  int seq;       // position in the workgroup's item sequence
 };
+enum : int { kWhole = 0, kPiece = 1 };
 
-template <class Cfg>
+template <class Cfg, bool FUSE>
 __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, S = Cfg::STAGES;
   constexpr int TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -78,30 +86,32 @@ __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
     t.rows = p.M - t.m0; t.cols = p.N - t.n0;
     t.bkc = p.b_kcontig;
   };
-  auto regular_item = [&](int round, ProjItem& t) -> bool {
-    const int idx = round * per_xcd + q_in_xcd;
-    if (idx >= n_ids) return false;
-    tile_item(first_id + idx, t);
-    t.round = round;
-    return true;
-  };
-  auto first_item = [&](ProjItem& t) -> bool {
-    const int j = blockIdx.x;
-    if (j < n_split_items) {
+  // Item sequence of this workgroup: [piece] one K piece of a leftover tile (blockIdx < n_split_items), whose partial
+  // tile goes to a row-major slab; then its regular tiles, round after round.
+  const int has_piece = (int)blockIdx.x < n_split_items ? 1 : 0;
+  const int n_rounds = q_in_xcd < n_ids ? (n_ids - q_in_xcd + per_xcd - 1) / per_xcd : 0;
+  auto item_at = [&](int seq, ProjItem& t) -> bool {
+    t.seq = seq;
+    if (has_piece && seq == 0) {
+      const int j = blockIdx.x;
       tile_item(regular + j / grp.pieces, t);
-      const int s = j % grp.pieces, KT = t.k1;
-      t.k0 = (int)((long long)s * KT / grp.pieces);
-      t.k1 = (int)((long long)(s + 1) * KT / grp.pieces);
+      const int sp = j % grp.pieces, KT = t.k1;
+      t.k0 = (int)((long long)sp * KT / grp.pieces);
+      t.k1 = (int)((long long)(sp + 1) * KT / grp.pieces);
       t.dst = grp.slabs + (size_t)j * (BM * BN);
       t.ldc = BN;
-      t.round = -1;
+      t.kind = kPiece;
       return true;
     }
-    return regular_item(0, t);
+    const int s = seq - has_piece;  // position among the regular items
+    if (s >= n_rounds) return false;
+    tile_item(first_id + s * per_xcd + q_in_xcd, t);
+    t.kind = kWhole;
+    return true;
   };
 
   ProjItem cur;
-  if (!first_item(cur)) return;
+  if (!item_at(0, cur)) return;
 
   // ---- load side ----
   AOp opa;
@@ -136,16 +146,13 @@ __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
     else issue_step_as(std::false_type{}, kt, stage);
   };
 
-  float* strip = reinterpret_cast<float*>(smem_dl + RING_BYTES) + wave * STRIP_FLOATS;
-  const int rr = lane / LPR, cc = (lane % LPR) * 8;
-
   bind(cur);
   issue_step(cur.k0, 0);
   int g = 0;  // K steps consumed so far, over all items: step g lives in stage g & 1
 
   for (;;) {
     ProjItem nxt;
-    const bool have_next = regular_item(cur.round + 1, nxt);
+    const bool have_next = item_at(cur.seq + 1, nxt);
     const int L = cur.k1 - cur.k0;
 
     f32x16 acc[TM][TN];
@@ -222,10 +229,97 @@ __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
     if (cur.bkc) run(std::true_type{});
     else run(std::false_type{});
 
+    if (FUSE && cur.kind != kPiece) {
+      // ---- fused epilogue: Adam on the accumulators (tiles summed over their whole K range; pieces go to their slabs below) ----
+      const ProjProblem& p = grp.p[cur.pi];
+      float* Mp = p.Mo;
+      float* Vp = p.Vo;
+      __bf16* Np = static_cast<__bf16*>(p.Nout);
+      const int ldm = p.ldm, ldn = p.ldn;
+      const int rows = cur.rows, colsv = p.cols_valid - cur.n0;
+      const float b1 = grp.beta1, b2 = grp.beta2, eps = grp.eps, ic1 = p.inv_c1, ic2 = p.inv_c2;
+      const bool ntr = p.n_transposed != 0;
+      const bool nvec = ntr && (ldn & 3) == 0 && (reinterpret_cast<uintptr_t>(Np) & 7) == 0;
+      // (lane-dependent values of the epilogue are derived behind a compiler barrier: hoisted out of the item loop
+      // they would stay live across the K loop, whose register budget has no room for them)
+      int le = lane;
+      asm volatile("" : "+v"(le));
+      const int lrow = wm0 + 4 * (le >> 5), lcol = wn0 + (le & 31);
+      // entry (i, q, j, c) of this lane: row lrow + 32 i + 8 q + c, column lcol + 32 j
+      // 32-bit element offsets from uniform base pointers (the launcher checks that the moments span < 2^32 bytes):
+      // one lane-dependent register, everything that varies with (i, q, j, c) is wave-uniform
+      const unsigned mv0 = (unsigned)(cur.m0 + lrow) * (unsigned)ldm + (unsigned)(cur.n0 + lcol);
+      const unsigned mv_safe = (unsigned)cur.m0 * (unsigned)ldm + (unsigned)cur.n0;  // the tile's first entry: always inside
+      // The moments come from HBM, one group of entries ahead of the update (DEPTH = 2).  The epilogue is then a chain
+      // of 16 memory round trips per tile (measured: 56 us, 20 GB/s per CU); more groups in flight need registers the
+      // kernel does not have (DEPTH = 4 spills and measured slower).
+      constexpr int DEPTH = 2;
+      float mb[DEPTH][TN * 4], vb[DEPTH][TN * 4];
+      auto fetch = [&](int i, int q, float (&m)[TN * 4], float (&v)[TN * 4]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int ro = 32 * i + 8 * q + c;
+            const bool ok = lrow + ro < rows && lcol + 32 * j < colsv;  // lanes outside the matrix read the safe entry and store nothing
+            const unsigned off = ok ? mv0 + (unsigned)ro * (unsigned)ldm + 32u * j : mv_safe;
+            m[j * 4 + c] = __builtin_nontemporal_load(Mp + off);
+            v[j * 4 + c] = __builtin_nontemporal_load(Vp + off);
+          }
+      };
+      auto apply = [&](int i, int q, float (&m)[TN * 4], float (&v)[TN * 4]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = lcol + 32 * j;
+          const int row0 = lrow + 32 * i + 8 * q;
+          float n[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            float me = m[j * 4 + c], ve = v[j * 4 + c];
+            n[c] = adam_entry(acc[i][j][4 * q + c], me, ve, b1, b2, eps, ic1, ic2);
+            if (row0 + c < rows && col < colsv) {
+              const unsigned off = mv0 + (unsigned)(32 * i + 8 * q + c) * (unsigned)ldm + 32u * j;
+              __builtin_nontemporal_store(me, Mp + off);
+              __builtin_nontemporal_store(ve, Vp + off);
+            }
+          }
+          if (col >= colsv) continue;
+          if (ntr) {  // N^T[col][row]: four consecutive rows are 8 contiguous bytes
+            __bf16* dst = Np + (size_t)(cur.n0 + col) * ldn + cur.m0 + row0;
+            if (nvec && row0 + 3 < rows) {
+              bf16x4 o;
+              o[0] = (__bf16)n[0]; o[1] = (__bf16)n[1]; o[2] = (__bf16)n[2]; o[3] = (__bf16)n[3];
+              *reinterpret_cast<bf16x4*>(dst) = o;
+            } else {
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if (row0 + c < rows) dst[c] = (__bf16)n[c];
+            }
+          } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              if (row0 + c < rows) Np[(size_t)(cur.m0 + row0 + c) * ldn + cur.n0 + col] = (__bf16)n[c];
+          }
+        }
+      };
+      // the moments of the next group of entries are in flight while this group is updated
+#pragma unroll
+      for (int gq = 0; gq < DEPTH - 1; ++gq) fetch(gq >> 2, gq & 3, mb[gq], vb[gq]);
+#pragma unroll
+      for (int gq = 0; gq < TM * 4; ++gq) {
+        constexpr int AHEAD = DEPTH - 1;
+        if (gq + AHEAD < TM * 4) fetch((gq + AHEAD) >> 2, (gq + AHEAD) & 3, mb[(gq + AHEAD) % DEPTH], vb[(gq + AHEAD) % DEPTH]);
+        __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the update they overlap with
+        apply(gq >> 2, gq & 3, mb[gq % DEPTH], vb[gq % DEPTH]);
+      }
+    } else {
     // ---- epilogue: accumulators -> wave-private LDS strip -> 32 contiguous bytes per lane ----
     // (the strip area lies outside the ring, which keeps receiving the next item's first K step meanwhile;
     // LDS operations of one wave execute in order, so the strip can be rewritten right after it was read)
-    {
+      int le = lane;
+      asm volatile("" : "+v"(le));
+      float* strip = reinterpret_cast<float*>(smem_dl + RING_BYTES) + wave * STRIP_FLOATS;
+      const int rr = le / LPR, cc = (le % LPR) * 8;
       float* dst0 = cur.dst;
       const int ldc = cur.ldc;
       const int col = wn0 + cc;
@@ -237,7 +331,7 @@ __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
           for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-              strip[(4 * (lane >> 5) + c) * PITCH + 32 * j + (lane & 31)] = acc[i][j][4 * q + c];
+              strip[(4 * (le >> 5) + c) * PITCH + 32 * j + (le & 31)] = acc[i][j][4 * q + c];
 #pragma unroll
           for (int ps = 0; ps < PASSES; ++ps) {
             const float* src = strip + (rr + RPP * ps) * PITCH + cc;
@@ -259,7 +353,8 @@ __global__ __launch_bounds__(Cfg::NT) void proj_dl_kernel(const ProjGroup grp) {
 }
 
 // R tile = sum of its `pieces` slabs, in slab order.  blockIdx.y = split tile, blockIdx.x strides over the tile.
-template <class Cfg>
+// FUSE: the sums go into the update block of Algorithm 2 instead of into R (same expression as everywhere else).
+template <class Cfg, bool FUSE>
 __global__ __launch_bounds__(256) void proj_reduce_kernel(const ProjGroup grp) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN;
   const int id = grp.regular_tiles + blockIdx.y;
@@ -281,7 +376,22 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(const ProjGroup grp) {
       const f32x4 x = *reinterpret_cast<const f32x4*>(slab + (size_t)s * (BM * BN) + (size_t)row * BN + c4);
       sum[0] += x[0]; sum[1] += x[1]; sum[2] += x[2]; sum[3] += x[3];
     }
-    *reinterpret_cast<f32x4*>(p.R + (size_t)(m0 + row) * p.ldr + n0 + c4) = sum;
+    if (FUSE) {
+      __bf16* Np = static_cast<__bf16*>(p.Nout);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int col = n0 + c4 + c;
+        if (col >= p.cols_valid) continue;
+        const size_t idx = (size_t)(m0 + row) * p.ldm + col;
+        float me = p.Mo[idx], ve = p.Vo[idx];
+        const float n = adam_entry(sum[c], me, ve, grp.beta1, grp.beta2, grp.eps, p.inv_c1, p.inv_c2);
+        p.Mo[idx] = me; p.Vo[idx] = ve;
+        if (p.n_transposed) Np[(size_t)col * p.ldn + m0 + row] = (__bf16)n;
+        else Np[(size_t)(m0 + row) * p.ldn + col] = (__bf16)n;
+      }
+    } else {
+      *reinterpret_cast<f32x4*>(p.R + (size_t)(m0 + row) * p.ldr + n0 + c4) = sum;
+    }
   }
 }
 

@@ -15,7 +15,7 @@ bool proj_problem_fits(const ProjProblem& p) {
   return group_fits_dl(one, true, p.b_kcontig != 0, Epilogue::StoreF32, CfgDl::BK);
 }
 
-hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipStream_t stream) {
+hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipStream_t stream, bool fuse_adam) {
   using Cfg = CfgDl;
   if (g.count <= 0) return hipSuccess;
   if (g.count > kMaxGroup) return hipErrorInvalidValue;
@@ -23,6 +23,9 @@ hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipS
   for (int i = 0; i < g.count; ++i) {
     ProjProblem& p = g.p[i];
     if (!proj_problem_fits(p)) return hipErrorInvalidValue;
+    if (fuse_adam && (!p.Mo || !p.Vo || !p.Nout || p.cols_valid < 1 || p.cols_valid > p.N || p.ldm < p.cols_valid ||
+                      p.ldn < (p.n_transposed ? p.M : p.cols_valid) || (uint64_t)p.M * (uint64_t)p.ldm * 4 > 0xFFFFFFFFull))
+      return hipErrorInvalidValue;
     p.tile_begin = total;
     p.tiles_m = (p.M + Cfg::BM - 1) / Cfg::BM;
     p.tiles_n = (p.N + Cfg::BN - 1) / Cfg::BN;
@@ -61,18 +64,19 @@ hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipS
   constexpr size_t smem = (size_t)Cfg::STAGES * (AOp::TILE_BYTES + BOp::TILE_BYTES) +
                           (size_t)Cfg::NW * 8 * (Cfg::WN + 8) * sizeof(float);  // tile ring + epilogue strips
   static_assert(smem <= 160 * 1024, "tile ring and strips do not fit the 160 KB LDS");
-  auto kern = proj_dl_kernel<Cfg>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  auto kern = fuse_adam ? proj_dl_kernel<Cfg, true> : proj_dl_kernel<Cfg, false>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[fuse_adam]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[fuse_adam] = true;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), smem, stream, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (total > regular) {
-    hipLaunchKernelGGL(proj_reduce_kernel<Cfg>, dim3(16, total - regular), dim3(256), 0, stream, g);
+    if (fuse_adam) hipLaunchKernelGGL((proj_reduce_kernel<Cfg, true>), dim3(16, total - regular), dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL((proj_reduce_kernel<Cfg, false>), dim3(16, total - regular), dim3(256), 0, stream, g);
     e = hipGetLastError();
   }
   return e;

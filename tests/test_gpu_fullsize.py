@@ -19,7 +19,7 @@ from paper_2403_03507_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("schedule", ["chains", "overlapped_calls"])
+@pytest.mark.parametrize("schedule", ["chains", "overlapped_calls", "overlapped_calls_fused_adam"])
 def test_llama7b_layer_set_sampled_columns(schedule):
     c = wl.CONFIGS["llama7b"]
     shapes = wl.layer_shapes(c["d"], c["f"])
@@ -31,8 +31,10 @@ def test_llama7b_layer_set_sampled_columns(schedule):
     W = [(torch.randn(m, n, generator=gen, device=dev) * 0.02).to(torch.bfloat16) for (m, n) in shapes]
     W0 = [w.clone() for w in W]
     opt = gb.GaLore(W, r, auto_refresh=False, workspace_factor=3)   # default: three concurrent chains inside a call
-    if schedule == "overlapped_calls":
+    if schedule.startswith("overlapped_calls"):
         opt.set_call_overlap(3)
+    if schedule.endswith("fused_adam"):   # Adam in the projection's epilogue
+        opt.set_fused_adam(True)
     for i, p in enumerate(opt.proj):
         p.copy_(wl.random_orthonormal(p.shape[0], r, 50 + i, device=dev).to(torch.bfloat16))
     steps = 2

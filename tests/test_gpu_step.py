@@ -112,7 +112,7 @@ def test_weight_update_of_odd_row_lengths_on_the_large_tile_kernel():
     _run_stack(shapes, "bf16", 64, steps=2, update_gap=2, weight_decay=0.1)
 
 
-def _run_with_given_projectors(shapes, rank, steps, lr=1e-3, chunked=False):
+def _run_with_given_projectors(shapes, rank, steps, lr=1e-3, chunked=False, fused_adam=False):
     """bf16 steps with seeded orthonormal projectors (the oracle's SVD of the larger shapes would take minutes):
     W per entry, M and V to 1e-5 against the oracle."""
     dtype = "bf16"
@@ -120,6 +120,7 @@ def _run_with_given_projectors(shapes, rank, steps, lr=1e-3, chunked=False):
     W0 = [wl.make_weight(m, n, 620 + i, dtype) for i, (m, n) in enumerate(shapes)]
     Wd = [w.cuda() for w in W0]
     opt = gb.GaLore(Wd, rank, auto_refresh=False)
+    opt.set_fused_adam(fused_adam)
     oracles = []
     lr = f32(lr)
     for i, (m, n) in enumerate(shapes):
@@ -155,6 +156,39 @@ def test_grouped_projection_with_k_pieces(chunked):
     # tiles whose slabs are only partly written; rank 192 leaves a ragged tile along r.
     shapes = [(512, 1024), (1024, 512), (512, 512), (1024, 1000), (1096, 1024), (1536, 1536)]
     _run_with_given_projectors(shapes, 192, steps=2, chunked=chunked)
+
+
+@pytest.mark.parametrize("chunked", [False, True])
+def test_adam_in_the_projection_epilogue_against_the_oracle(chunked):
+    # galore_set_fused_adam: the update block of Algorithm 2 runs on the projection GEMM's accumulators (whole tiles)
+    # and in the kernel that sums the partial tiles (pieces).  LEFT and RIGHT tensors, ragged tiles in every
+    # direction, a rank that is no multiple of 32, an odd row length (padded copy of G: R has columns M and V lack).
+    shapes = [(512, 1024), (1024, 512), (1024, 1000), (1096, 1024), (1536, 1536), (512, 1021), (256, 200), (200, 256)]
+    _run_with_given_projectors(shapes, 200, steps=3, chunked=chunked, fused_adam=True)
+
+
+def test_adam_in_the_projection_epilogue_is_bit_identical_to_the_separate_kernel():
+    specs = [((512, 1024), "bf16"), ((1024, 512), "bf16"), ((1024, 1000), "bf16"), ((512, 1021), "bf16"), ((1536, 1536), "bf16"),
+             ((320, 256), "f32"), ((140, 257), "bf16")]          # the last two never take the fused path
+    rank = 136
+    srcs = [wl.GradientSource(m, n, 660 + i, "lowrank", dtype=dt) for i, ((m, n), dt) in enumerate(specs)]
+    outs = []
+    for fused in (False, True):
+        W = [wl.make_weight(m, n, 680 + i, dt).cuda() for i, ((m, n), dt) in enumerate(specs)]
+        opt = gb.GaLore(W, rank, auto_refresh=False, weight_decay=0.01)
+        opt.set_fused_adam(fused)
+        for i, ((m, n), dt) in enumerate(specs):
+            opt.proj[i].copy_(wl.random_orthonormal(min(m, n), rank, 700 + i).to(wl.TORCH_DTYPE[dt]))
+        for step in range(3):
+            opt.step(W, [s.grad(step).cuda() for s in srcs], 1e-2)
+        torch.cuda.synchronize()
+        outs.append([w.clone() for w in W] + [x.clone() for x in opt.M + opt.V])
+        opt.close()
+    n = len(specs)
+    for i in range(n):   # moments first: they tell a different R or Adam expression from a different weight update
+        assert torch.equal(outs[0][n + i], outs[1][n + i]), ("M", i, specs[i])
+        assert torch.equal(outs[0][2 * n + i], outs[1][2 * n + i]), ("V", i, specs[i])
+        assert torch.equal(outs[0][i], outs[1][i]), ("W", i, specs[i])
 
 
 def _offset_view(t, pad=3):
