@@ -100,13 +100,17 @@ def main():
     ap.add_argument("--fused-adam", type=int, choices=[0, 1], default=0,
                     help="1: Adam in the epilogue of the projection GEMM (two kernels per step); 0: separate Adam kernel (three)")
     ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="overlapped calls: calls in flight (library streams used)")
-    ap.add_argument("--layers-per-call", type=int, default=1, choices=[1, 2],
-                    help="layers handed to one galore_step call (the small stacks fill the chip better with 2)")
+    ap.add_argument("--layers-per-call", type=int, default=None,
+                    help="layers handed to one galore_step call (0 = the whole stack in one call; the library cuts a call "
+                         "into launch groups of at most 16 tensors).  Default: 1 for llama7b (the per-layer update the "
+                         "headline configuration names), 2 for the smaller stacks, whose launches fill the chip better then")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")
 
     args = ap.parse_args()
+    if args.layers_per_call is None:
+        args.layers_per_call = 1 if args.config == "llama7b" else 2
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (nothing here uses a "
               "second GPU)" % args.gpus, file=sys.stderr)
@@ -151,14 +155,14 @@ def main():
 
     # one call's workspace per call in flight: overlapped calls then overlap their subspace refreshes as well
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
-                    workspace_factor=args.in_flight * args.layers_per_call)
+                    workspace_factor=args.in_flight * min(max(args.layers_per_call, 1), 2))
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     gb.galore_set_fused_adam(opt.ctx, args.fused_adam)
     overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
     gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
-    LPC = args.layers_per_call
+    LPC = args.layers_per_call if args.layers_per_call > 0 else L
     # argument arrays are marshalled once: weights and pooled gradients stay where they are
     call_w = {l: gb.tensor_array(x for k in range(l, min(l + LPC, L)) for x in w_descs[k]) for l in range(0, L, LPC)}
     # the layers of one call take consecutive gradient sets of the pool
@@ -215,8 +219,9 @@ def main():
     flops["back"] = flops["project_left"] + flops["project_right"]
     if prof["project_right"][1] == 0:  # both orientations ran in the one grouped projection launch (recorded as project_left)
         flops["project_left"] += flops["project_right"]
-    if L % LPC == 0:  # a launch covers the tensors of LPC layers
-        flops = {k: v * LPC for k, v in flops.items()}
+    # work of ONE launch: a call's tensors are cut into launch groups of at most 16, so with several layers per call the
+    # launches of a step share its work evenly enough for an average (the 7B default, one layer per call, is exact)
+    flops = {k: v * L * K / max(prof[k][1], 1) for k, v in flops.items()}
     sN = 2 if dtype == "bf16" else 4
     if args.moments == "q8":  # read R and two code bytes, write two code bytes and N; four scale accesses per 256 elements
         adam_bytes = sum(r * max(m, n) * (4 + 4 + sN + 16.0 / 256) for m, n in shapes)
@@ -241,7 +246,7 @@ def main():
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
         if MEASURED_TRAFFIC_7B["sources"] == kernel_sources_digest():
-            roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"][dominant] * (LPC if L % LPC == 0 else 1)
+            roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"][dominant] if LPC == 1 else None
             roofline["traffic_unit"] = ("bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of `bench.py --probe-traffic`, scaled by a "
                                         "1 GiB copy; hits in the 256 MB MALL are included; read on these kernel sources, not in this run)")
         else:

@@ -148,14 +148,20 @@ def _run_with_given_projectors(shapes, rank, steps, lr=1e-3, chunked=False, fuse
 
 
 @pytest.mark.parametrize("chunked", [False, True])
-def test_grouped_projection_with_k_pieces(chunked):
-    # The projection of bf16 tensors whose short side is a multiple of 64 runs as ONE launch for both orientations,
-    # and tiles that do not fill a round of the grid are cut into K pieces whose partial tiles are summed afterwards.
-    # Short sides 512 / 1024 / 1536 give 8 / 16 / 24 K steps, i.e. 2 / 4 / 6 pieces when a tensor runs alone (one
-    # call per tensor) and the group's smallest count when they share a launch; 1000 and 1096 columns leave ragged
-    # tiles whose slabs are only partly written; rank 192 leaves a ragged tile along r.
+def test_grouped_projection_of_both_orientations(chunked):
+    # The projection of bf16 tensors whose short side is a multiple of 64 runs as ONE launch for both orientations
+    # (the layout of B is a field of each problem).  1000 and 1096 columns leave ragged tiles; rank 192 leaves a
+    # ragged tile along r.
     shapes = [(512, 1024), (1024, 512), (512, 512), (1024, 1000), (1096, 1024), (1536, 1536)]
     _run_with_given_projectors(shapes, 192, steps=2, chunked=chunked)
+
+
+@pytest.mark.parametrize("fused_adam", [False, True])
+def test_projection_with_leftover_tiles_in_k_pieces(fused_adam):
+    # 236 + 32 = 268 tiles of 256 x 256 for 256 CUs: one whole round, and 12 leftover tiles that are cut into two K
+    # pieces each (8 K steps, at least 4 per piece), whose partial tiles are summed afterwards - into R, or, with Adam
+    # in the epilogue, straight into the update block.  The leftover tiles are the last of the RIGHT tensor.
+    _run_with_given_projectors([(512, 60416), (8192, 512)], 256, steps=2, fused_adam=fused_adam)
 
 
 @pytest.mark.parametrize("chunked", [False, True])
