@@ -1,7 +1,6 @@
 // Host side of the C ABI: context, validation, chunking of tensor lists into grouped
 // launches, and the per-step orchestration of Algorithm 2.  No kernels here.
-#include "../../include/galore.h"
-#include "common.hpp"
+#include "api_internal.hpp"
 #include "refresh.hpp"
 
 #include <cmath>
@@ -14,6 +13,7 @@
 #include <vector>
 
 using namespace galore;
+using namespace galore::api;
 
 // Device memory of galore_step_static, the entry point for callers that cannot allocate: the
 // transients R, N (and the padded copy of G) of one launch group live here instead of in the
@@ -48,9 +48,6 @@ hipError_t static_scratch_ptr(unsigned char** out) {
   *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
   return hipSuccess;
 }
-
-constexpr size_t kAlign = 256;
-inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct TensorInfo {
   int64_t rows, cols;
@@ -104,7 +101,10 @@ struct galore_ctx {
   std::vector<char> in_flight;    // per tensor: 0, or 1 + the library stream its last chain ran on
 };
 
-namespace {
+namespace galore {
+namespace api {
+
+bool valid_dtype(int32_t d, bool allow_u8) { return d == GALORE_F32 || d == GALORE_BF16 || (allow_u8 && d == GALORE_U8); }
 
 galore_status fail(galore_ctx* ctx, galore_status s, const char* fmt, ...) {
   char buf[512];
@@ -117,7 +117,52 @@ galore_status fail(galore_ctx* ctx, galore_status s, const char* fmt, ...) {
   return s;
 }
 
-bool valid_dtype(int32_t d, bool allow_u8) { return d == GALORE_F32 || d == GALORE_BF16 || (allow_u8 && d == GALORE_U8); }
+galore_status check_hparams(galore_ctx* ctx, const galore_hparams* hp) {
+  if (!hp) return fail(ctx, GALORE_ERR_INVALID_ARG, "hparams is NULL");
+  if (hp->rank < 1) return fail(ctx, GALORE_ERR_RANK, "rank %d < 1", hp->rank);
+  if (hp->update_gap < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "update_gap %d < 1", hp->update_gap);
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "betas must lie in [0, 1)");
+  if (!(hp->eps >= 0.f) || !std::isfinite(hp->scale) || !(hp->weight_decay >= 0.f))
+    return fail(ctx, GALORE_ERR_INVALID_ARG, "eps / scale / weight_decay out of range");
+  if (hp->refresh_iters < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_iters %d < 1", hp->refresh_iters);
+  if (hp->refresh_warm_iters < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_warm_iters %d < 0", hp->refresh_warm_iters);
+  return GALORE_OK;
+}
+
+galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* what, int idx, bool need_data,
+                           bool allow_u8) {
+  if (need_data && !t.data) return fail(ctx, GALORE_ERR_INVALID_ARG, "%s[%d].data is NULL", what, idx);
+  if (t.rows < 1 || t.cols < 1) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] has empty shape %lld x %lld", what, idx,
+                                            (long long)t.rows, (long long)t.cols);
+  if (t.ld < t.cols) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d].ld %lld < cols %lld", what, idx, (long long)t.ld,
+                                 (long long)t.cols);
+  if (t.rows > INT32_MAX / 2 || t.ld > INT32_MAX / 2)
+    return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] dimension too large", what, idx);
+  if (!valid_dtype(t.dtype, allow_u8)) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d].dtype %d not allowed here", what, idx, t.dtype);
+  return GALORE_OK;
+}
+
+galore_status check_weight_shape(galore_ctx* ctx, const galore_hparams& hp, const galore_tensor& w, int idx) {
+  galore_status s = check_matrix(ctx, w, "W", idx, false);
+  if (s) return s;
+  const int64_t k = w.rows <= w.cols ? w.rows : w.cols;
+  if (hp.rank > k) return fail(ctx, GALORE_ERR_RANK, "rank %d exceeds min(rows, cols) = %lld of W[%d]", hp.rank,
+                               (long long)k, idx);
+  return GALORE_OK;
+}
+
+galore_status hip_fail(galore_ctx* ctx, hipError_t e, const char* where) {
+  if (e == hipErrorNotSupported) return fail(ctx, GALORE_ERR_UNIMPLEMENTED, "%s: not implemented", where);
+  return fail(ctx, GALORE_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+}  // namespace api
+}  // namespace galore
+
+namespace {
+
+
 
 // The large-tile GEMM moves aligned 16-byte pieces, so G of a LEFT bf16 tensor (contiguous along n, the
 // GEMM's N index) cannot feed it when n is not a multiple of 8: its rows start at odd element offsets.
@@ -146,45 +191,9 @@ size_t tensor_need(const galore_hparams& hp, bool left, int64_t kdim, int64_t ld
   return a > b ? a : b;
 }
 
-galore_status check_hparams(galore_ctx* ctx, const galore_hparams* hp) {
-  if (!hp) return fail(ctx, GALORE_ERR_INVALID_ARG, "hparams is NULL");
-  if (hp->rank < 1) return fail(ctx, GALORE_ERR_RANK, "rank %d < 1", hp->rank);
-  if (hp->update_gap < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "update_gap %d < 1", hp->update_gap);
-  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
-    return fail(ctx, GALORE_ERR_INVALID_ARG, "betas must lie in [0, 1)");
-  if (!(hp->eps >= 0.f) || !std::isfinite(hp->scale) || !(hp->weight_decay >= 0.f))
-    return fail(ctx, GALORE_ERR_INVALID_ARG, "eps / scale / weight_decay out of range");
-  if (hp->refresh_iters < 1) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_iters %d < 1", hp->refresh_iters);
-  if (hp->refresh_warm_iters < 0) return fail(ctx, GALORE_ERR_INVALID_ARG, "refresh_warm_iters %d < 0", hp->refresh_warm_iters);
-  return GALORE_OK;
-}
 
-galore_status check_matrix(galore_ctx* ctx, const galore_tensor& t, const char* what, int idx, bool need_data,
-                           bool allow_u8 = false) {
-  if (need_data && !t.data) return fail(ctx, GALORE_ERR_INVALID_ARG, "%s[%d].data is NULL", what, idx);
-  if (t.rows < 1 || t.cols < 1) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] has empty shape %lld x %lld", what, idx,
-                                            (long long)t.rows, (long long)t.cols);
-  if (t.ld < t.cols) return fail(ctx, GALORE_ERR_SHAPE, "%s[%d].ld %lld < cols %lld", what, idx, (long long)t.ld,
-                                 (long long)t.cols);
-  if (t.rows > INT32_MAX / 2 || t.ld > INT32_MAX / 2)
-    return fail(ctx, GALORE_ERR_SHAPE, "%s[%d] dimension too large", what, idx);
-  if (!valid_dtype(t.dtype, allow_u8)) return fail(ctx, GALORE_ERR_DTYPE, "%s[%d].dtype %d not allowed here", what, idx, t.dtype);
-  return GALORE_OK;
-}
 
-galore_status check_weight_shape(galore_ctx* ctx, const galore_hparams& hp, const galore_tensor& w, int idx) {
-  galore_status s = check_matrix(ctx, w, "W", idx, false);
-  if (s) return s;
-  const int64_t k = w.rows <= w.cols ? w.rows : w.cols;
-  if (hp.rank > k) return fail(ctx, GALORE_ERR_RANK, "rank %d exceeds min(rows, cols) = %lld of W[%d]", hp.rank,
-                               (long long)k, idx);
-  return GALORE_OK;
-}
 
-galore_status hip_fail(galore_ctx* ctx, hipError_t e, const char* where) {
-  if (e == hipErrorNotSupported) return fail(ctx, GALORE_ERR_UNIMPLEMENTED, "%s: not implemented", where);
-  return fail(ctx, GALORE_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
-}
 
 // Event bracket around one kernel group while profiling is on.
 struct ProfScope {
@@ -973,367 +982,6 @@ galore_status galore_profile_stop(galore_ctx* ctx, double* ms, int64_t* launches
   }
   ctx->records.clear();
   return st;
-}
-
-// ---- stateless stage calls ---------------------------------------------------------------------
-
-galore_status galore_transpose(const galore_tensor* src, const galore_tensor* dst, void* hip_stream) {
-  if (!src || !dst) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  galore_status s;
-  if ((s = check_matrix(nullptr, *src, "src", 0, true)) || (s = check_matrix(nullptr, *dst, "dst", 0, true))) return s;
-  if (src->dtype != dst->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "src and dst dtypes differ");
-  if (dst->rows != src->cols || dst->cols != src->rows) return fail(nullptr, GALORE_ERR_SHAPE, "dst must be cols x rows of src");
-  TransposeGroup g{};
-  g.count = 1;
-  g.p[0].src = src->data; g.p[0].lds = (int)src->ld; g.p[0].dst = dst->data; g.p[0].ldd = (int)dst->ld;
-  g.p[0].rows = (int)src->rows; g.p[0].cols = (int)src->cols;
-  hipError_t e = launch_transpose_group(g, (DType)src->dtype, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "transpose launch");
-}
-
-galore_status galore_project(const galore_tensor* proj_t, const galore_tensor* G, const galore_tensor* R, void* hip_stream) {
-  if (!proj_t || !G || !R) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  galore_status s;
-  if ((s = check_matrix(nullptr, *proj_t, "proj_t", 0, true)) || (s = check_matrix(nullptr, *G, "G", 0, true)) ||
-      (s = check_matrix(nullptr, *R, "R", 0, true)))
-    return s;
-  if (proj_t->dtype != G->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj_t and G dtypes differ");
-  if (R->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "R must be fp32");
-  const bool left = G->rows <= G->cols;
-  const int64_t r = proj_t->rows;
-  if (r > (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
-  if (proj_t->cols != (left ? G->rows : G->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj_t cols must equal the short side of G");
-  if (R->rows != (left ? r : G->rows) || R->cols != (left ? G->cols : r))
-    return fail(nullptr, GALORE_ERR_SHAPE, "R has the wrong shape");
-  GemmGroup g{};
-  g.count = 1;
-  GemmProblem& p = g.p[0];
-  if (left) {
-    p.A = proj_t->data; p.lda = (int)proj_t->ld; p.B = G->data; p.ldb = (int)G->ld;
-    p.M = (int)r; p.N = (int)G->cols; p.K = (int)G->rows;
-  } else {
-    p.A = G->data; p.lda = (int)G->ld; p.B = proj_t->data; p.ldb = (int)proj_t->ld;
-    p.M = (int)G->rows; p.N = (int)r; p.K = (int)G->cols;
-  }
-  p.C = R->data; p.ldc = (int)R->ld;
-  // the kernel galore_step uses for this tensor: the grouped projection where its rules are met, else the general GEMM
-  ProjGroup pg{};
-  ProjProblem& q = pg.p[0];
-  q.A = p.A; q.B = p.B; q.R = static_cast<float*>(p.C);
-  q.M = p.M; q.N = p.N; q.K = p.K; q.lda = p.lda; q.ldb = p.ldb; q.ldr = p.ldc;
-  q.b_kcontig = left ? 0 : 1;
-  hipError_t e;
-  if ((DType)G->dtype == DType::BF16 && proj_problem_fits(q)) {
-    pg.count = 1;
-    e = launch_proj_group(pg, nullptr, 0, static_cast<hipStream_t>(hip_stream));
-  } else {
-    e = launch_gemm_group(g, (DType)G->dtype, true, !left, Epilogue::StoreF32, static_cast<hipStream_t>(hip_stream));
-  }
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "projection GEMM launch");
-}
-
-galore_status galore_adam(const galore_tensor* R, const galore_tensor* M, const galore_tensor* V, const galore_tensor* N,
-                          int32_t transpose_n, float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
-  if (!R || !M || !V || !N) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  const galore_tensor* all[4] = {R, M, V, N};
-  const char* names[4] = {"R", "M", "V", "N"};
-  for (int i = 0; i < 4; ++i) {
-    galore_status s = check_matrix(nullptr, *all[i], names[i], 0, true);
-    if (s) return s;
-    const bool tr = i == 3 && transpose_n;
-    if (all[i]->rows != (tr ? R->cols : R->rows) || all[i]->cols != (tr ? R->rows : R->cols) || all[i]->ld != all[i]->cols)
-      return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense with R's shape%s", names[i], tr ? " transposed" : "");
-    if (i < 3 && all[i]->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "%s must be fp32", names[i]);
-    if (reinterpret_cast<uintptr_t>(all[i]->data) & 15) return fail(nullptr, GALORE_ERR_ALIGN, "%s must be 16-byte aligned", names[i]);
-  }
-  if (k < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "k must be >= 1");
-  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
-    return fail(nullptr, GALORE_ERR_INVALID_ARG, "betas / eps out of range");
-  AdamGroup g{};
-  g.count = 1; g.beta1 = beta1; g.beta2 = beta2; g.eps = eps;
-  AdamProblem& p = g.p[0];
-  p.R = static_cast<const float*>(R->data); p.M = static_cast<float*>(M->data); p.V = static_cast<float*>(V->data);
-  p.N = N->data; p.count = R->rows * R->cols;
-  p.rows = (int)R->rows; p.cols = (int)R->cols; p.ldr = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
-  p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
-  p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
-  hipError_t e = launch_adam_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "Adam launch");
-}
-
-galore_status galore_adam_q8(const galore_tensor* R, const galore_tensor* Mc, const galore_tensor* Vc,
-                             const galore_tensor* Ms, const galore_tensor* Vs, const galore_tensor* N,
-                             int32_t transpose_n, float beta1, float beta2, float eps, int64_t k, void* hip_stream) {
-  if (!R || !Mc || !Vc || !Ms || !Vs || !N) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  const galore_tensor* all[6] = {R, Mc, Vc, N, Ms, Vs};
-  const char* names[6] = {"R", "Mc", "Vc", "N", "Ms", "Vs"};
-  for (int i = 0; i < 6; ++i) {
-    galore_status s = check_matrix(nullptr, *all[i], names[i], 0, true, i == 1 || i == 2);
-    if (s) return s;
-    if (all[i]->ld != all[i]->cols) return fail(nullptr, GALORE_ERR_SHAPE, "%s must be dense", names[i]);
-    if (reinterpret_cast<uintptr_t>(all[i]->data) & 15) return fail(nullptr, GALORE_ERR_ALIGN, "%s must be 16-byte aligned", names[i]);
-  }
-  if (R->dtype != GALORE_F32 || Ms->dtype != GALORE_F32 || Vs->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "R, Ms, Vs must be fp32");
-  if (Mc->dtype != GALORE_U8 || Vc->dtype != GALORE_U8) return fail(nullptr, GALORE_ERR_DTYPE, "Mc, Vc must be 8-bit codes");
-  if (R->cols % 256 != 0) return fail(nullptr, GALORE_ERR_UNIMPLEMENTED, "8-bit moments need rows of a multiple of 256 elements");
-  for (int i = 1; i < 3; ++i)
-    if (all[i]->rows != R->rows || all[i]->cols != R->cols) return fail(nullptr, GALORE_ERR_SHAPE, "%s must have R's shape", names[i]);
-  for (int i = 4; i < 6; ++i)
-    if (all[i]->rows != R->rows || all[i]->cols != R->cols / 256) return fail(nullptr, GALORE_ERR_SHAPE, "%s must be rows x cols/256 of R", names[i]);
-  if (N->rows != (transpose_n ? R->cols : R->rows) || N->cols != (transpose_n ? R->rows : R->cols))
-    return fail(nullptr, GALORE_ERR_SHAPE, "N must have R's shape%s", transpose_n ? " transposed" : "");
-  if (k < 1) return fail(nullptr, GALORE_ERR_INVALID_ARG, "k must be >= 1");
-  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
-    return fail(nullptr, GALORE_ERR_INVALID_ARG, "betas / eps out of range");
-  AdamQ8Group g{};
-  g.count = 1; g.beta1 = beta1; g.beta2 = beta2; g.omb1 = 1.0f - beta1; g.omb2 = 1.0f - beta2; g.eps = eps;
-  AdamQ8Problem& p = g.p[0];
-  p.R = static_cast<const float*>(R->data);
-  p.Mc = static_cast<uint8_t*>(Mc->data); p.Vc = static_cast<uint8_t*>(Vc->data);
-  p.Ms = static_cast<float*>(Ms->data); p.Vs = static_cast<float*>(Vs->data);
-  p.N = N->data; p.rows = (int)R->rows; p.cols = (int)R->cols; p.transpose_n = transpose_n ? 1 : 0;
-  p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)k)));
-  p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)k)));
-  hipError_t e = launch_adam_q8_group(g, (DType)N->dtype, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "Adam launch");
-}
-
-galore_status galore_project_back(const galore_tensor* proj, const galore_tensor* N, const galore_tensor* W, float lr,
-                                  float scale, float weight_decay, void* hip_stream) {
-  if (!proj || !N || !W) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  galore_status s;
-  if ((s = check_matrix(nullptr, *proj, "proj", 0, true)) || (s = check_matrix(nullptr, *N, "N", 0, true)) ||
-      (s = check_matrix(nullptr, *W, "W", 0, true)))
-    return s;
-  if (proj->dtype != W->dtype || N->dtype != W->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "proj, N and W dtypes must agree");
-  const bool left = W->rows <= W->cols;
-  const int64_t r = proj->cols;
-  if (r > (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_RANK, "rank exceeds the short side");
-  if (proj->rows != (left ? W->rows : W->cols)) return fail(nullptr, GALORE_ERR_SHAPE, "proj rows must equal the short side of W");
-  if (N->rows != (left ? W->cols : W->rows) || N->cols != r)
-    return fail(nullptr, GALORE_ERR_SHAPE, "N must be max(rows, cols) x r");
-  GemmGroup g{};
-  g.count = 1;
-  GemmProblem& p = g.p[0];
-  if (left) {
-    p.A = proj->data; p.lda = (int)proj->ld; p.B = N->data; p.ldb = (int)N->ld;
-  } else {
-    p.A = N->data; p.lda = (int)N->ld; p.B = proj->data; p.ldb = (int)proj->ld;
-  }
-  p.M = (int)W->rows; p.N = (int)W->cols; p.K = (int)r;
-  p.C = W->data; p.ldc = (int)W->ld;
-  p.s0 = 1.f - lr * weight_decay;
-  p.s1 = lr * scale;
-  hipError_t e = launch_gemm_group(g, (DType)W->dtype, true, true, Epilogue::ApplyW, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "back-projection GEMM launch");
-}
-
-}  // extern "C"
-
-// ---- two-sided projection (Definition 3.6) -------------------------------------------------------
-namespace {
-
-struct TwoSidedLayout {
-  // step
-  size_t pt, t1, t1c, R, nn, t2, t2c, step_total;
-  // refresh (overlays the step's region: the two never run at once on one workspace)
-  size_t rws, r_pt, r_t1, r_qt, r_tg, r_tgt, refresh_total;
-  size_t total;
-};
-
-TwoSidedLayout two_sided_layout(int64_t m, int64_t n, int64_t r, DType dt) {
-  TwoSidedLayout L{};
-  const size_t s = dtype_size(dt);
-  size_t off = 0;
-  auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
-  L.pt = take((size_t)r * m * s);
-  L.t1 = take((size_t)r * n * 4);
-  L.t1c = dt == DType::F32 ? L.t1 : take((size_t)r * n * s);
-  L.R = take((size_t)r * r * 4);
-  L.nn = take((size_t)r * r * s);
-  L.t2 = take((size_t)n * r * 4);
-  L.t2c = dt == DType::F32 ? L.t2 : take((size_t)n * r * s);
-  L.step_total = off;
-  off = 0;
-  L.rws = take(refresh_workspace_bytes(m <= n ? m : n, r));
-  L.r_pt = take((size_t)r * m * s);
-  L.r_qt = take((size_t)r * n * s);
-  if (m <= n) {
-    L.r_t1 = take((size_t)r * n * 4);
-  } else {
-    L.r_tg = take((size_t)m * r * 4);
-    L.r_tgt = take((size_t)r * m * 4);
-  }
-  L.refresh_total = off;
-  L.total = L.step_total > L.refresh_total ? L.step_total : L.refresh_total;
-  return L;
-}
-
-galore_status check_two_sided(const galore_hparams* hp, const galore_tensor* W, const galore_tensor* G,
-                              const galore_two_sided_state* S, const void* workspace, size_t workspace_bytes) {
-  galore_status s = check_hparams(nullptr, hp);
-  if (s) return s;
-  if (!W || !S) return fail(nullptr, GALORE_ERR_INVALID_ARG, "NULL argument");
-  if ((s = check_weight_shape(nullptr, *hp, *W, 0))) return s;
-  if (G) {
-    if ((s = check_matrix(nullptr, *G, "G", 0, true))) return s;
-    if (G->rows != W->rows || G->cols != W->cols) return fail(nullptr, GALORE_ERR_SHAPE, "G must have W's shape");
-    if (G->dtype != W->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "G and W dtypes must agree");
-  }
-  const int64_t r = hp->rank;
-  if ((s = check_matrix(nullptr, S->p, "state.p", 0, true)) || (s = check_matrix(nullptr, S->q, "state.q", 0, true)) ||
-      (s = check_matrix(nullptr, S->m, "state.m", 0, true)) || (s = check_matrix(nullptr, S->v, "state.v", 0, true)))
-    return s;
-  if (S->p.rows != W->rows || S->p.cols != r) return fail(nullptr, GALORE_ERR_STATE, "state.p must be rows(W) x rank");
-  if (S->q.rows != W->cols || S->q.cols != r) return fail(nullptr, GALORE_ERR_STATE, "state.q must be cols(W) x rank");
-  if (S->p.dtype != W->dtype || S->q.dtype != W->dtype) return fail(nullptr, GALORE_ERR_DTYPE, "projector dtypes must equal W's");
-  for (const galore_tensor* mv : {&S->m, &S->v}) {
-    if (mv->dtype != GALORE_F32) return fail(nullptr, GALORE_ERR_DTYPE, "two-sided moments are fp32");
-    if (mv->rows != r || mv->cols != r || mv->ld != r) return fail(nullptr, GALORE_ERR_STATE, "two-sided moments are rank x rank, dense");
-  }
-  if (!workspace) return fail(nullptr, GALORE_ERR_WORKSPACE, "workspace is NULL");
-  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return fail(nullptr, GALORE_ERR_ALIGN, "workspace must be 256-byte aligned");
-  const size_t need = two_sided_layout(W->rows, W->cols, r, (DType)W->dtype).total;
-  if (workspace_bytes < need)
-    return fail(nullptr, GALORE_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
-  return GALORE_OK;
-}
-
-// C (fp32, M x N dense) = A B with A as [M][K]; B as [N][K] (b_kcontig) or [K][N]
-hipError_t two_sided_gemm(DType dt, const void* A, int lda, const void* B, int ldb, bool b_kcontig, float* C, int M, int N, int K,
-                          hipStream_t stream) {
-  GemmGroup g{};
-  g.count = 1;
-  GemmProblem& p = g.p[0];
-  p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
-  p.M = M; p.N = N; p.K = K;
-  p.C = C; p.ldc = N;
-  return launch_gemm_group(g, dt, true, b_kcontig, Epilogue::StoreF32, stream);
-}
-
-hipError_t two_sided_transpose(DType dt, const void* src, int rows, int cols, int lds, void* dst, int ldd, hipStream_t stream) {
-  TransposeGroup g{};
-  g.count = 1;
-  g.p[0].src = src; g.p[0].rows = rows; g.p[0].cols = cols; g.p[0].lds = lds;
-  g.p[0].dst = dst; g.p[0].ldd = ldd;
-  return launch_transpose_group(g, dt, stream);
-}
-
-}  // namespace
-
-extern "C" {
-
-galore_status galore_two_sided_workspace_bytes(const galore_hparams* hp, const galore_tensor* W, size_t* out_bytes) {
-  galore_status s = check_hparams(nullptr, hp);
-  if (s) return s;
-  if (!W || !out_bytes) return fail(nullptr, GALORE_ERR_INVALID_ARG, "W / out_bytes is NULL");
-  if ((s = check_weight_shape(nullptr, *hp, *W, 0))) return s;
-  *out_bytes = two_sided_layout(W->rows, W->cols, hp->rank, (DType)W->dtype).total;
-  return GALORE_OK;
-}
-
-galore_status galore_two_sided_step(const galore_hparams* hp, const galore_tensor* W, const galore_tensor* G,
-                                    const galore_two_sided_state* S, int64_t t, float lr,
-                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!G) return fail(nullptr, GALORE_ERR_INVALID_ARG, "G is NULL");
-  galore_status s = check_two_sided(hp, W, G, S, workspace, workspace_bytes);
-  if (s) return s;
-  if (!W->data) return fail(nullptr, GALORE_ERR_INVALID_ARG, "W.data is NULL");
-  if (t < 0) return fail(nullptr, GALORE_ERR_INVALID_ARG, "t < 0");
-  if (hp->auto_refresh && t % hp->update_gap == 0) {  // Algorithm 2's refresh test, on this step's gradient
-    s = galore_two_sided_refresh(hp, G, S, workspace, workspace_bytes, hip_stream);
-    if (s) return s;
-  }
-  const DType dt = (DType)W->dtype;
-  const int m = (int)W->rows, n = (int)W->cols, r = hp->rank;
-  const TwoSidedLayout L = two_sided_layout(m, n, r, dt);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  float* T1 = reinterpret_cast<float*>(ws + L.t1);
-  float* R = reinterpret_cast<float*>(ws + L.R);
-  float* T2 = reinterpret_cast<float*>(ws + L.t2);
-  hipError_t e;
-  // T1 (r x n) = P^T G, then R (r x r) = T1 Q: every product reads its operands in the storage dtype
-  e = two_sided_transpose(dt, S->p.data, m, r, (int)S->p.ld, ws + L.pt, m, stream);
-  if (e == hipSuccess) e = two_sided_gemm(dt, ws + L.pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
-  if (e == hipSuccess && dt != DType::F32) e = launch_cast_rows(T1, ws + L.t1c, r, n, n, dt, stream);
-  if (e == hipSuccess) e = two_sided_gemm(dt, ws + L.t1c, n, S->q.data, (int)S->q.ld, false, R, r, r, n, stream);
-  if (e != hipSuccess) return hip_fail(nullptr, e, "two-sided projection");
-  // Adam on R (Algorithm 2, update block), k = t + 1
-  {
-    AdamGroup g{};
-    g.count = 1;
-    g.beta1 = hp->beta1; g.beta2 = hp->beta2; g.eps = hp->eps;
-    const double k = (double)(t + 1);
-    AdamProblem& p = g.p[0];
-    p.R = R;
-    p.M = static_cast<float*>(S->m.data);
-    p.V = static_cast<float*>(S->v.data);
-    p.N = ws + L.nn;
-    p.rows = r; p.cols = r; p.ldr = r; p.count = (int64_t)r * r;
-    p.transpose_n = 0;
-    p.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, k)));
-    p.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, k)));
-    e = launch_adam_group(g, dt, stream);
-    if (e != hipSuccess) return hip_fail(nullptr, e, "two-sided Adam");
-  }
-  // T2 (n x r) = Q N^T, then W <- (1 - lr wd) W - lr alpha P T2^T in the epilogue of the last product
-  e = two_sided_gemm(dt, S->q.data, (int)S->q.ld, ws + L.nn, r, true, T2, n, r, r, stream);
-  if (e == hipSuccess && dt != DType::F32) e = launch_cast_rows(T2, ws + L.t2c, n, r, r, dt, stream);
-  if (e == hipSuccess) {
-    GemmGroup g{};
-    g.count = 1;
-    GemmProblem& p = g.p[0];
-    p.A = S->p.data; p.lda = (int)S->p.ld;
-    p.B = ws + L.t2c; p.ldb = r;
-    p.M = m; p.N = n; p.K = r;
-    p.C = W->data; p.ldc = (int)W->ld;
-    p.s0 = 1.f - lr * hp->weight_decay;
-    p.s1 = lr * hp->scale;
-    e = launch_gemm_group(g, dt, true, true, Epilogue::ApplyW, stream);
-  }
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "two-sided weight update");
-}
-
-galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_tensor* G, const galore_two_sided_state* S,
-                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!G) return fail(nullptr, GALORE_ERR_INVALID_ARG, "G is NULL");
-  galore_tensor shape = *G;   // the weight has the gradient's shape and dtype
-  galore_status s = check_two_sided(hp, &shape, G, S, workspace, workspace_bytes);
-  if (s) return s;
-  const DType dt = (DType)G->dtype;
-  const int m = (int)G->rows, n = (int)G->cols, r = hp->rank;
-  const bool left = m <= n;
-  const TwoSidedLayout L = two_sided_layout(m, n, r, dt);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // the projector of the short side, as in Algorithm 2's refresh branch (writes it and its transpose)
-  RefreshItem it{};
-  it.G = G->data; it.ldg = G->ld; it.rows = m; it.cols = n; it.dt = dt;
-  it.proj = left ? S->p.data : S->q.data;
-  it.ldp = left ? S->p.ld : S->q.ld;
-  it.proj_t = ws + (left ? L.r_pt : L.r_qt);
-  it.ldpt = left ? m : n;
-  it.ws = ws + L.rws;
-  it.seed = hp->seed + 0x9E3779B97F4A7C15ull;
-  hipError_t e = refresh_group(std::vector<RefreshItem>{it}, r, hp->refresh_iters, /*warm_start=*/false, /*crowded=*/false, stream);
-  if (e != hipSuccess) return hip_fail(nullptr, e, "subspace refresh");
-  if (left) {
-    // rows of P^T G are s_i v_i^T: unit length makes them Q^T
-    float* T1 = reinterpret_cast<float*>(ws + L.r_t1);
-    e = two_sided_gemm(dt, ws + L.r_pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
-    if (e == hipSuccess) e = launch_normalize_rows(T1, ws + L.r_qt, r, n, n, dt, stream);
-    if (e == hipSuccess) e = two_sided_transpose(dt, ws + L.r_qt, r, n, n, S->q.data, (int)S->q.ld, stream);
-  } else {
-    // columns of G Q are s_i u_i
-    float* Tg = reinterpret_cast<float*>(ws + L.r_tg);
-    float* Tgt = reinterpret_cast<float*>(ws + L.r_tgt);
-    e = two_sided_gemm(dt, G->data, (int)G->ld, ws + L.r_qt, n, true, Tg, m, r, n, stream);
-    if (e == hipSuccess) e = two_sided_transpose(DType::F32, Tg, m, r, r, Tgt, m, stream);
-    if (e == hipSuccess) e = launch_normalize_rows(Tgt, ws + L.r_pt, r, m, m, dt, stream);
-    if (e == hipSuccess) e = two_sided_transpose(dt, ws + L.r_pt, r, m, m, S->p.data, (int)S->p.ld, stream);
-  }
-  return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "partner projector");
 }
 
 }  // extern "C"
