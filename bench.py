@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # cannot be read inside a timed run, so the figures are tied to the kernel sources they were measured on:
 # `sources` is the digest of the files named in TRAFFIC_SOURCES at that time, and roofline.traffic is reported
 # only while the digest still matches (null otherwise: re-run the probe and update both together).
-TRAFFIC_SOURCES = ["gemm_mfma_dl.hpp", "gemm_mfma.hpp", "gemm_dispatch.hpp", "common.hpp", "adam.hip"]
+TRAFFIC_SOURCES = ["gemm_mfma_dl.hpp", "gemm_proj_dl.hpp", "proj.hip", "gemm_mfma.hpp", "gemm_dispatch.hpp", "common.hpp", "adam.hip", "adam_entry.hpp"]
 MEASURED_TRAFFIC_7B = {
     "sources": "unmeasured",
     "bytes": {
@@ -49,7 +49,7 @@ def kernel_sources_digest():
     return h.hexdigest()[:16]
 
 
-def probe_traffic(layers=3, steps=2):
+def probe_traffic(layers=3, steps=2, fused_adam=False):
     """Workload of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: a few strictly serial steps of the library on
     LLaMA-7B-shaped layer sets with given projectors (no refresh: its thousands of short launches would only slow
     the counter run down), then ONE 1 GiB device-to-device copy whose traffic is known exactly (2^30 bytes read,
@@ -67,6 +67,7 @@ def probe_traffic(layers=3, steps=2):
     G = [(torch.randn(m, n, generator=gen, device="cuda") * 0.01).to(torch.bfloat16) for _ in range(layers) for (m, n) in shapes]
     opt = gb.GaLore(W, r, auto_refresh=False)
     gb.galore_set_concurrency(opt.ctx, 1)
+    opt.set_fused_adam(fused_adam)
     for p in opt.proj:  # traffic does not depend on the values: a scaled Gaussian block stands in for a projector
         p.copy_((torch.randn(p.shape, generator=gen, device="cuda") / 64).to(torch.bfloat16))
     n7 = len(shapes)
@@ -124,7 +125,7 @@ def main():
         lib_build.build()
     gb.lib()
     if args.probe_traffic:
-        probe_traffic()
+        probe_traffic(fused_adam=bool(args.fused_adam))
         return
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -337,8 +338,12 @@ def main():
         "ms_per_step_serial": serial_ms,
         "ms_per_step_serial_with_events": prof_total_ms / K,
         # step 0 = refresh + step in the timed schedule; the serial figure is the sum of the refresh launches alone
+        # amortised: the refresh of the whole stack spread over the T = update_gap steps between two refreshes, in
+        # ms per step and as a fraction of the ordinary step next to it
         "refresh": {"step0_ms": first_ms, "ms_per_layer_set": (first_ms - ms_per_step) / L,
-                    "ms_per_layer_set_serial": refresh_serial_ms / L},
+                    "ms_per_layer_set_serial": refresh_serial_ms / L,
+                    "amortised_ms_per_step": (first_ms - ms_per_step) / cfg["update_gap"],
+                    "amortised_frac_of_step": (first_ms - ms_per_step) / cfg["update_gap"] / ms_per_step},
         "step_flops": 4.0 * sum(m * n for m, n in shapes) * r * L,
         "step_tflops": 4.0 * sum(m * n for m, n in shapes) * r * L / (ms_per_step * 1e-3) / 1e12,
     }

@@ -371,11 +371,17 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(const ProjGroup grp) {
   for (int e = blockIdx.x * 256 + threadIdx.x; e < BM * BN / 4; e += gridDim.x * 256) {
     const int row = e / (BN / 4), c4 = (e % (BN / 4)) * 4;
     if (row >= rows || c4 >= cols) continue;
-    f32x4 sum = *reinterpret_cast<const f32x4*>(slab + (size_t)row * BN + c4);
-    for (int s = 1; s < grp.pieces; ++s) {
-      const f32x4 x = *reinterpret_cast<const f32x4*>(slab + (size_t)s * (BM * BN) + (size_t)row * BN + c4);
-      sum[0] += x[0]; sum[1] += x[1]; sum[2] += x[2]; sum[3] += x[3];
-    }
+    // all slabs of the entry are requested together (a slab index beyond `pieces` re-reads slab 0 and is not
+    // added): one memory round trip instead of one per slab; the sum keeps the slab order
+    constexpr int kMaxPieces = 16;
+    f32x4 x[kMaxPieces];
+#pragma unroll
+    for (int s = 0; s < kMaxPieces; ++s)
+      x[s] = *reinterpret_cast<const f32x4*>(slab + (size_t)(s < grp.pieces ? s : 0) * (BM * BN) + (size_t)row * BN + c4);
+    f32x4 sum = x[0];
+#pragma unroll
+    for (int s = 1; s < kMaxPieces; ++s)
+      if (s < grp.pieces) { sum[0] += x[s][0]; sum[1] += x[s][1]; sum[2] += x[s][2]; sum[3] += x[s][3]; }
     if (FUSE) {
       __bf16* Np = static_cast<__bf16*>(p.Nout);
 #pragma unroll

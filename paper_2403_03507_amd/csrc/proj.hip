@@ -77,8 +77,8 @@ hipError_t launch_proj_group(ProjGroup& g, float* slabs, size_t slab_bytes, hipS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (total > regular) {
-    if (fuse_adam) hipLaunchKernelGGL((proj_reduce_kernel<Cfg, true>), dim3(16, total - regular), dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL((proj_reduce_kernel<Cfg, false>), dim3(16, total - regular), dim3(256), 0, stream, g);
+    if (fuse_adam) hipLaunchKernelGGL((proj_reduce_kernel<Cfg, true>), dim3(64, total - regular), dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL((proj_reduce_kernel<Cfg, false>), dim3(64, total - regular), dim3(256), 0, stream, g);
     e = hipGetLastError();
   }
   return e;

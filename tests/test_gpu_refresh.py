@@ -69,11 +69,14 @@ def test_gapped_spectrum_bf16(shape):
 
 @pytest.mark.parametrize("shape,r,dtype", [((1024, 1024), 256, "f32"), ((1024, 2736), 256, "f32"), ((2736, 1024), 256, "f32"),
                                            ((1024, 1024), 256, "bf16"), ((768, 2048), 256, "f32"), ((512, 1376), 128, "f32"),
-                                           ((2048, 2048), 512, "f32")])
+                                           ((2048, 2048), 512, "f32"), ((1280, 1536), 1024, "f32"), ((1536, 1280), 1024, "f32"),
+                                           ((1280, 1536), 1024, "bf16")])
 def test_gapped_spectrum_at_the_ranks_of_the_stacks(shape, r, dtype):
     # The shapes and ranks of the 350M (1024 x 1024 / 1024 x 2736 / 2736 x 1024, r = 256), 130M (768 x 2048, r = 256),
     # 60M (512 x 1376, r = 128) and 1B (2048 x 2048, r = 512) stacks against the oracle's Jacobi SVD: 8 to 16 compact-WY
-    # macro panels, 16 to 32 blocks in the Jacobi rounds, the split-bf16 products (short side >= 512).
+    # macro panels, 16 to 32 blocks in the Jacobi rounds, the split-bf16 products (short side >= 512).  The last three
+    # run at the 7B stack's rank, r = 1024 (32 macro panels, 64 Jacobi blocks, the launch shapes of the full-size
+    # refresh), on a short side of 1280 that the oracle's SVD finishes in seconds.
     m, n = shape
     G = wl.GradientSource(m, n, 23, "gapped", dtype=dtype, gap_rank=r).grad(0)
     P0, sig = orc.projector(to64(G), r)
@@ -84,6 +87,23 @@ def test_gapped_spectrum_at_the_ranks_of_the_stacks(shape, r, dtype):
         assert _proj_dist(P, P0) <= 1e-3
         assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
         assert np.all(np.sum(P * P0, axis=0) >= 0.99)    # the vectors themselves, signs included (neighbouring singular values lie 0.6 - 2.4 % apart)
+    elif r == 1024:
+        # neighbouring singular values lie 0.3 % apart at this rank, so the single vectors of both sides are settled to a
+        # few per cent only (the fp32 cases above gate them the same way): the subspace against the oracle's, with the
+        # allowance that rounding the oracle's own projector to bf16 uses up, the vectors by their cosines, and the
+        # orthonormality of the stored bf16 columns
+        P0r = orc.round_storage(P0, "bf16")
+        assert _proj_dist(P, P0) <= 1e-3 + 2 * _proj_dist(P0r, P0)
+        cos = np.sum(P * P0, axis=0)
+        assert np.all(np.abs(cos) >= 0.99)
+        # the sign rule makes the entry of largest magnitude positive: where the oracle's vector has a runner-up of
+        # the opposite sign within 1 % of that magnitude, either sign is a correct reading of the rule at this accuracy
+        for c in np.nonzero(cos < 0)[0]:
+            a = np.abs(P0[:, c])
+            top, second = np.argsort(a)[::-1][:2]
+            assert a[second] >= 0.99 * a[top] and P0[top, c] * P0[second, c] < 0, (c, a[top], a[second])
+        assert np.mean(cos < 0) <= 0.01
+        assert np.abs(P.T @ P - np.eye(r)).max() <= 2e-3
     else:
         P0r = orc.round_storage(P0, "bf16")
         assert relF(P, P0r) <= 2e-3

@@ -18,39 +18,10 @@ HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 
 
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
-def test_early_weight_prefetch_is_exactly_eight_loads(tmp_path):
-    src = os.path.join(ROOT, "paper_2403_03507_amd", "csrc", "gemm_bf16.hip")
-    out = str(tmp_path / "gemm_bf16.s")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", out, src],
-                          stderr=subprocess.DEVNULL)
-    text = open(out).read()
-    kernels = re.findall(r"^(_ZN6galore14gemm_dl_kernelILb1ELb[01]ELNS_8EpilogueE1E\w+):[^\n]*\n(.*?)\.end_amdhsa_kernel", text, flags=re.S | re.M)
-    # (K,X) and (K,K) weight-update kernels, and the (K,K) variant for W of any alignment, whose
-    # prefetch copies 16 bytes at element alignment and must still be one load instruction per piece
-    assert len(kernels) == 3
-    assert sum(name.endswith("Lb1EEEvNS_9GemmGroupE") for name, _ in kernels) == 1
-    for name, body in kernels:
-        ops = []
-        for line in body.split("\n"):
-            t = line.split(";")[0].strip()
-            if t.startswith("global_load_lds"):
-                ops.append("T")                                 # tile load (direct to LDS)
-            elif t.startswith("global_load"):
-                ops.append("W")                                 # load into registers: the W prefetch
-            elif t.startswith("global_store") or t.startswith("global_atomic"):
-                ops.append("S")
-            elif t.startswith("s_waitcnt") and "vmcnt(8)" in t:
-                ops.append("8")
-            elif t.startswith("s_barrier"):
-                ops.append("B")
-        seq = "".join(ops)
-        first = seq.index("8")                                  # the hand-written wait; the compiler's own waits
-        assert seq[first + 1] == "B", name                      # for the prefetched registers come later, in the epilogue
-        before = seq[:first]
-        # the last memory operations before the wait: 8 tile loads of the step, then exactly 8 register loads
-        assert before.endswith("T" * 8 + "W" * 8), (name, before[-40:])
-        assert "S" not in before[before.rindex("B"):], name     # and no store in between
+def test_early_weight_prefetch_is_exactly_eight_loads():
+    # the check itself is part of the build (the library is not linked when it fails); here it runs on its own
+    from paper_2403_03507_amd import build as lib_build
+    assert lib_build.check_weight_prefetch_assembly() == 3
 
 
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not available")
