@@ -30,11 +30,11 @@ PEAK_HBM_GBS = 8000.0
 # only while the digest still matches (null otherwise: re-run the probe and update both together).
 TRAFFIC_SOURCES = ["gemm_mfma_dl.hpp", "gemm_proj_dl.hpp", "proj.hip", "gemm_mfma.hpp", "gemm_dispatch.hpp", "common.hpp", "adam.hip", "adam_entry.hpp"]
 MEASURED_TRAFFIC_7B = {
-    "sources": "unmeasured",
-    "bytes": {
-        "project_left": 590.0e6 + 157.6e6,
-        "project_right": 205.7e6 + 45.1e6,
-        "back": 1090.4e6 + 404.8e6,
+    "sources": "7583bf5ad650004d",
+    "bytes": {   # read (2 x FETCH_SIZE KiB x 1024) + written (WRITE_SIZE KiB x 1024)
+        "project_left": (711.2e6 + 218.9e6) + (16.8e6 + 1.0e6),   # the grouped projection launch of both orientations + the sum of the split tiles' slabs
+        "project_left_fused_adam": (1407.5e6 + 639.2e6) + (19.0e6 + 2.6e6),
+        "back": 1110.3e6 + 404.8e6,
         "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
     },
 }
@@ -247,7 +247,8 @@ def main():
     roofline["launch_ms"] = stage_ms[dominant]
     if args.config == "llama7b":
         if MEASURED_TRAFFIC_7B["sources"] == kernel_sources_digest():
-            roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"][dominant] if LPC == 1 else None
+            key = "project_left_fused_adam" if (dominant == "project_left" and args.fused_adam) else dominant
+            roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"].get(key) if LPC == 1 else None
             roofline["traffic_unit"] = ("bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of `bench.py --probe-traffic`, scaled by a "
                                         "1 GiB copy; hits in the 256 MB MALL are included; read on these kernel sources, not in this run)")
         else:
