@@ -18,7 +18,8 @@ def _setup(specs, rank, **kw):
     return W, opt
 
 
-def test_static_scratch_step_equals_workspace_step_on_two_calls_in_a_row():
+@pytest.mark.parametrize("fused_adam", [False, True])
+def test_static_scratch_step_equals_workspace_step_on_two_calls_in_a_row(fused_adam):
     # call 1: four tensors (both orientations, bf16 and fp32, one with an odd row length: padded copy of G and the
     # any-alignment weight update); call 2, right behind it on the same stream: one small tensor, so most of the array
     # still holds call 1's transients
@@ -27,6 +28,8 @@ def test_static_scratch_step_equals_workspace_step_on_two_calls_in_a_row():
     srcs = [wl.GradientSource(m, n, 970 + i, "lowrank", dtype=dt) for i, ((m, n), dt) in enumerate(specs)]
     Wa, a = _setup(specs, rank)
     Wb, b = _setup(specs, rank)
+    a.set_fused_adam(fused_adam)      # Adam in the projection's epilogue (the aligned bf16 tensors) or as its own kernel
+    b.set_fused_adam(fused_adam)
     for step in range(3):
         G = [s.grad(step).cuda() for s in srcs]
         a.step(Wa[:4], G[:4], 1e-2, first=0)
