@@ -123,3 +123,40 @@ def test_llama7b_layer_set_refresh_properties():
         assert float(((ritz[:64] - sv[:64]).abs() / sv[:64]).max()) <= 2e-3
         assert float((ritz[1:] - ritz[:-1]).clamp_min(0).max() / ritz[0]) <= 1e-4   # decreasing order
     opt.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(4096, 4096), (4096, 11008), (11008, 4096)])
+def test_llama7b_shapes_gapped_refresh_is_the_singular_basis(shape, dtype):
+    # The refresh at the 7B stack's shapes and rank on gradients WITH a spectral gap at r (the oracle's Jacobi SVD of a
+    # 4096 x 4096 matrix takes minutes, so the answer is characterised instead of recomputed).  For orthonormal P,
+    # trace(P^T C P) <= sum of the r largest eigenvalues of C = G G^T (Ky Fan), with equality only for the leading
+    # eigenspace; inside that space P^T C P is diagonal only for eigenvectors.  So: orthonormal columns, captured energy
+    # equal to the sum of the r largest squared singular values, P^T C P diagonal, its diagonal equal to those squared
+    # singular values in decreasing order - together they say that column i is the i-th singular vector (up to sign,
+    # which the sign rule fixes and the small-size tests compare).  Singular values from torch's SVD in fp64, an
+    # independent library routine.  fp32 projectors hold this to fp32 accuracy; bf16 ones to their storage rounding.
+    m, n = shape
+    r = 1024
+    G = wl.GradientSource(m, n, 31, "gapped", dtype=dtype, gap_rank=r, device="cuda").grad(0)
+    opt = gb.GaLore([G], r, refresh_iters=8, auto_refresh=False)
+    opt.refresh([G])
+    torch.cuda.synchronize()
+    P, Gd = opt.proj[0].double(), G.double()
+    A = (P.t() @ Gd) if m <= n else (Gd @ P)
+    T = (A @ A.t()) if m <= n else (A.t() @ A)                       # P^T G G^T P  (Q^T G^T G Q for the tall tensor)
+    d = torch.sqrt(torch.diag(T))
+    sv = torch.linalg.svdvals(Gd)
+    assert float(sv[r - 1] / sv[r]) >= 2.0                            # the generator's gap
+    off = (T / d[:, None] / d[None, :]).abs()
+    off.fill_diagonal_(0)
+    eye = torch.eye(r, device="cuda", dtype=torch.float64)
+    tol = {"f32": dict(off=5e-5, diag=2e-6, orth=1e-5, energy=1e-6), "bf16": dict(off=4e-3, diag=5e-4, orth=2e-3, energy=1e-4)}[dtype]
+    assert float((P.t() @ P - eye).abs().max()) <= tol["orth"]
+    assert abs(float((d ** 2).sum() / (sv[:r] ** 2).sum()) - 1.0) <= tol["energy"]
+    assert float(off.max()) <= tol["off"]
+    assert float(((d - sv[:r]).abs() / sv[:r]).max()) <= tol["diag"]
+    assert bool((d[1:] <= d[:-1] * (1 + tol["diag"])).all())
+    assert bool((opt.proj[0].max(dim=0).values >= opt.proj[0].abs().max(dim=0).values).all())   # sign rule
+    assert torch.equal(opt.proj_t[0], opt.proj[0].t())
+    opt.close()
