@@ -19,7 +19,8 @@
  *   - All tensor data pointers are DEVICE pointers (HIP global memory of the current
  *     device), row-major, leading dimension `ld` in elements (ld >= cols).  They are
  *     BORROWED: the library never allocates, frees or keeps device memory of its own
- *     except through the caller's workspace.  Argument structs and arrays of structs
+ *     except through the caller's workspace (one exception, stated there: the static
+ *     device array that galore_step_static uses in place of the workspace).  Argument structs and arrays of structs
  *     are HOST memory and are copied during the call.
  *   - The gradient is the positive gradient of the loss; the update is subtracted.
  *     (The paper negates the gradient and adds; the trajectory is the same.)
@@ -132,7 +133,9 @@ const char* galore_status_string(galore_status s);
  * padded to a multiple of 8 elements, which the projection then reads instead of G; Gram
  * matrix, iteration blocks and reflector storage of the refresh).  Any 256-byte-aligned workspace at least as
  * large as the largest single-tensor need is accepted by galore_init; a smaller one
- * only means more, smaller launches.  No device access. */
+ * only means more, smaller launches.  What a call's transients leave free of its share of the
+ * workspace also serves, up to 64 MiB, as the area for the partial tiles of projection tiles that are cut
+ * along K (see galore_set_concurrency); without room for them nothing is cut.  No device access. */
 galore_status galore_workspace_bytes(const galore_hparams* hp, const galore_tensor* W,
                                      int32_t n_tensors, size_t* out_bytes);
 
