@@ -83,26 +83,31 @@ def test_gapped_spectrum_at_the_ranks_of_the_stacks(shape, r, dtype):
     assert sig[r - 1] / sig[r] >= 2.0
     opt = _refresh([G], r)
     P = to64(opt.proj[0])
-    if dtype == "f32":
-        assert _proj_dist(P, P0) <= 1e-3
-        assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
-        assert np.all(np.sum(P * P0, axis=0) >= 0.99)    # the vectors themselves, signs included (neighbouring singular values lie 0.6 - 2.4 % apart)
-    elif r == 1024:
-        # neighbouring singular values lie 0.3 % apart at this rank, so the single vectors of both sides are settled to a
-        # few per cent only (the fp32 cases above gate them the same way): the subspace against the oracle's, with the
-        # allowance that rounding the oracle's own projector to bf16 uses up, the vectors by their cosines, and the
-        # orthonormality of the stored bf16 columns
-        P0r = orc.round_storage(P0, "bf16")
-        assert _proj_dist(P, P0) <= 1e-3 + 2 * _proj_dist(P0r, P0)
+    def vectors_agree(P, P0):
+        # the vectors themselves (neighbouring singular values lie 0.3 - 2.4 % apart, so a cosine of 0.99 is what an
+        # fp32 iteration can promise for the closest ones), signs included.  The sign rule makes the entry of largest
+        # magnitude positive: where the oracle's vector has a runner-up of the opposite sign within 1 % of that
+        # magnitude, either sign is a correct reading of the rule at this accuracy.
         cos = np.sum(P * P0, axis=0)
-        assert np.all(np.abs(cos) >= 0.99)
-        # the sign rule makes the entry of largest magnitude positive: where the oracle's vector has a runner-up of
-        # the opposite sign within 1 % of that magnitude, either sign is a correct reading of the rule at this accuracy
+        assert np.all(np.abs(cos) >= 0.99), float(np.abs(cos).min())
         for c in np.nonzero(cos < 0)[0]:
             a = np.abs(P0[:, c])
             top, second = np.argsort(a)[::-1][:2]
             assert a[second] >= 0.99 * a[top] and P0[top, c] * P0[second, c] < 0, (c, a[top], a[second])
         assert np.mean(cos < 0) <= 0.01
+
+    if dtype == "f32":
+        assert _proj_dist(P, P0) <= 1e-3
+        assert np.abs(P.T @ P - np.eye(r)).max() <= 1e-5
+        vectors_agree(P, P0)
+    elif r == 1024:
+        # neighbouring singular values lie 0.3 % apart at this rank, so the single vectors of both sides are settled to a
+        # few per cent only and entry-wise agreement of the rounded values is not to be had: the subspace against the
+        # oracle's, with the allowance that rounding the oracle's own projector to bf16 uses up, the vectors by their
+        # cosines, and the orthonormality of the stored bf16 columns
+        P0r = orc.round_storage(P0, "bf16")
+        assert _proj_dist(P, P0) <= 1e-3 + 2 * _proj_dist(P0r, P0)
+        vectors_agree(P, P0)
         assert np.abs(P.T @ P - np.eye(r)).max() <= 2e-3
     else:
         P0r = orc.round_storage(P0, "bf16")
