@@ -13,6 +13,8 @@
  *   - top-r singular vectors of G by one-sided Jacobi (no LAPACK)         [Sec. 3.3, SVD equation for P_t, Q_t; Algorithm 2, refresh branch]
  *   - the two-sided form of Definition 3.6,  G~ = P rho(P^T G Q) Q^T  with rho = Adam,
  *     P = [u_1..u_r], Q = [v_1..v_r]                                      [Sec. 3.3, Definition 3.6 and the SVD equation]
+ *   - Adafactor with first-order statistics as the entry-wise optimizer rho on R                [Sec. 4.3 and Sec. 5 name it; PARITY UNPINNED by the paper,
+ *     which prints no equations for it: the routine states the published Adafactor update, see oracle_adafactor]
  *
  * Matrices are dense row-major double arrays.  OpenMP is used on outermost
  * loops only; there is no blocking, no intrinsics and no library call.
@@ -133,6 +135,54 @@ void oracle_adam(const double* R, double* M, double* V, double* N, int64_t count
     const double mhat = mi / c1;
     const double vhat = vi / c2;
     N[i] = mhat / (sqrt(vhat) + eps);
+  }
+}
+
+/* ---------- Adafactor on the projected gradient ---------------------------- */
+
+/* The paper applies GaLore to "Adafactor with first-order statistics" (Sec. 4.3, Sec. 5) and prints no
+ * equations for it: PARITY UNPINNED by the paper.  What is stated here is the published Adafactor update
+ * for a matrix (Shazeer and Stern 2018: factored second moment, update clipping, decay rate
+ * 1 - k^decay_pow, optional momentum) on the rows x cols projected gradient R, with the learning rate
+ * left to the caller as in Algorithm 2 (no relative step size, no parameter scaling), k the 1-based step:
+ *   b2    = 1 - k^decay_pow                                    (decay_pow = -0.8 in the publication)
+ *   rowv_i <- b2 rowv_i + (1 - b2) sum_j (R_ij^2 + eps1)       (rows entries)
+ *   colv_j <- b2 colv_j + (1 - b2) sum_i (R_ij^2 + eps1)       (cols entries)
+ *   Vhat_ij = rowv_i colv_j / sum_i rowv_i
+ *   U = R / sqrt(Vhat) ;  Uhat = U / max(1, RMS(U) / clip_d)   (RMS over all rows x cols entries)
+ *   M <- b1 M + (1 - b1) Uhat ;  N = M                         (first-order statistics; b1 = 0: N = Uhat)
+ * State: M (rows x cols), rowv, colv.  Pins: tests/test_oracle_adafactor.py (torch.optim.Adafactor for
+ * b1 = 0, closed forms at rank-one |R|, scale invariance, the constant-gradient momentum sum, a hand-worked
+ * 2 x 2 step). */
+void oracle_adafactor(const double* R, double* M, double* rowv, double* colv, double* N,
+                      int64_t rows, int64_t cols, double beta1, double decay_pow, double eps1,
+                      double clip_d, int64_t k) {
+  const double b2 = 1.0 - pow((double)k, decay_pow);
+  for (int64_t i = 0; i < rows; ++i) {
+    double s = 0.0;
+    for (int64_t j = 0; j < cols; ++j) s += R[i * cols + j] * R[i * cols + j] + eps1;
+    rowv[i] = b2 * rowv[i] + (1.0 - b2) * s;
+  }
+  for (int64_t j = 0; j < cols; ++j) {
+    double s = 0.0;
+    for (int64_t i = 0; i < rows; ++i) s += R[i * cols + j] * R[i * cols + j] + eps1;
+    colv[j] = b2 * colv[j] + (1.0 - b2) * s;
+  }
+  double total = 0.0;
+  for (int64_t i = 0; i < rows; ++i) total += rowv[i];
+  double sumsq = 0.0;
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t j = 0; j < cols; ++j) {
+      const double u = R[i * cols + j] / sqrt(rowv[i] * colv[j] / total);
+      N[i * cols + j] = u;     /* U for now */
+      sumsq += u * u;
+    }
+  const double rms = sqrt(sumsq / ((double)rows * (double)cols));
+  const double denom = rms / clip_d > 1.0 ? rms / clip_d : 1.0;
+  for (int64_t e = 0; e < rows * cols; ++e) {
+    const double uhat = N[e] / denom;
+    M[e] = beta1 * M[e] + (1.0 - beta1) * uhat;
+    N[e] = M[e];
   }
 }
 

@@ -62,6 +62,7 @@ def lib():
         L.oracle_project_left.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64]
         L.oracle_project_right.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64]
         L.oracle_adam.argtypes = [_dp, _dp, _dp, _dp, _i64, _f64, _f64, _f64, _i64]
+        L.oracle_adafactor.argtypes = [_dp, _dp, _dp, _dp, _dp, _i64, _i64, _f64, _f64, _f64, _f64, _i64]
         L.oracle_apply_left.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64, _f64, _f64, _f64]
         L.oracle_apply_right.argtypes = [_dp, _dp, _dp, _i64, _i64, _i64, _f64, _f64, _f64]
         L.oracle_top_left_singular_vectors.argtypes = [_dp, _i64, _i64, _i64, _dp, _dp, _f64, ctypes.c_int]
@@ -167,6 +168,20 @@ def adam(R, M, V, beta1, beta2, eps, k):
     assert M.shape == R.shape and V.shape == R.shape
     N = np.empty_like(R)
     lib().oracle_adam(_p(R), _p(M), _p(V), _p(N), R.size, beta1, beta2, eps, int(k))
+    return N
+
+
+ADAFACTOR_DECAY_POW, ADAFACTOR_EPS1, ADAFACTOR_CLIP = -0.8, 1e-30, 1.0   # the publication's constants
+
+
+def adafactor(R, M, rowv, colv, beta1, k, decay_pow=ADAFACTOR_DECAY_POW, eps1=ADAFACTOR_EPS1, clip_d=ADAFACTOR_CLIP):
+    """Adafactor with first-order statistics on the projected gradient (see oracle_adafactor): updates M
+    (R's shape), rowv (rows) and colv (cols) in place and returns N.  k is the 1-based step number."""
+    R = _c(R)
+    rows, cols = R.shape
+    assert M.shape == R.shape and rowv.shape == (rows,) and colv.shape == (cols,)
+    N = np.empty_like(R)
+    lib().oracle_adafactor(_p(R), _p(M), _p(rowv), _p(colv), _p(N), rows, cols, beta1, decay_pow, eps1, clip_d, int(k))
     return N
 
 
@@ -329,5 +344,50 @@ class GaLoreTensor:
         self.W = round_storage(self.W, self.dtype)
         self.M = round_storage(self.M, "f32")
         self.V = round_storage(self.V, "f32")
+        self.t += 1
+        return self.W
+
+
+class GaLoreAdafactorTensor:
+    """One weight matrix under Algorithm 2 with Adafactor (first-order statistics on) in place of Adam as the
+    optimizer of the projected gradient: fp64 arithmetic, storage-dtype state (W, P in the tensor's dtype; M,
+    the row and the column statistics fp32)."""
+
+    def __init__(self, W, rank, update_gap=200, scale=0.25, beta1=0.9, weight_decay=0.0, dtype="f32", auto_refresh=True):
+        self.dtype = dtype
+        self.W = round_storage(W, dtype)
+        self.m, self.n = self.W.shape
+        self.r = int(rank)
+        assert 1 <= self.r <= min(self.m, self.n)
+        self.T, self.alpha, self.beta1, self.wd = int(update_gap), float(scale), float(beta1), float(weight_decay)
+        self.auto_refresh = auto_refresh
+        self.left = self.m <= self.n
+        shape = (self.r, self.n) if self.left else (self.m, self.r)
+        self.M = np.zeros(shape)
+        self.rowv = np.zeros(shape[0])
+        self.colv = np.zeros(shape[1])
+        self.proj = None
+        self.t = 0
+
+    def refresh(self, G):
+        P, _ = projector(G, self.r)
+        self.proj = round_storage(P, self.dtype)
+        return self.proj
+
+    def set_projector(self, proj):
+        self.proj = round_storage(proj, self.dtype)
+
+    def step(self, G, lr):
+        G = round_storage(G, self.dtype)
+        if self.auto_refresh and self.t % self.T == 0:
+            self.refresh(G)
+        R = project(self.proj, G)
+        N = adafactor(R, self.M, self.rowv, self.colv, self.beta1, self.t + 1)
+        self.last_R, self.last_N = R, N
+        apply_update(self.W, self.proj, N, lr, self.alpha, self.wd)
+        self.W = round_storage(self.W, self.dtype)
+        self.M = round_storage(self.M, "f32")
+        self.rowv = round_storage(self.rowv, "f32")
+        self.colv = round_storage(self.colv, "f32")
         self.t += 1
         return self.W
