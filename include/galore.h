@@ -330,6 +330,51 @@ galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_te
                                        const galore_two_sided_state* S,
                                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- GaLore with Adafactor (Sec. 4.3, Sec. 5: Adafactor with first-order statistics) ----
+ * The paper applies the projection to Adafactor as it does to Adam and prints no equations for it; the update
+ * used here is the published Adafactor update for a matrix (factored second moment, update clipping, decay rate
+ * 1 - k^-0.8, momentum) on the projected gradient R (r x cols for rows <= cols, rows x r otherwise), with the
+ * learning rate left to the caller as in Algorithm 2 (no relative step size, no parameter scaling), k = t + 1:
+ *     b2 = 1 - k^-0.8
+ *     row_i <- b2 row_i + (1 - b2) sum_j (R_ij^2 + 1e-30) ;  col_j <- b2 col_j + (1 - b2) sum_i (R_ij^2 + 1e-30)
+ *     Vhat_ij = row_i col_j / sum_i row_i ;  U = R / sqrt(Vhat) ;  Uhat = U / max(1, RMS(U))
+ *     M <- beta1 M + (1 - beta1) Uhat ;  N = M
+ *     W <- (1 - lr*weight_decay) W - lr*scale * P N   (N Q^T for rows > cols)
+ * State per tensor: min(rows, cols) r + max(rows, cols) r + r + max(rows, cols) elements, against the
+ * min r + 2 max r of Adam.  One tensor per call, no context: the caller keeps the step count t (0-based) and
+ * clears m, row and col before the first step.  All tensors are BORROWED device memory, row-major; proj has W's
+ * dtype; m, row, col are fp32 and dense.  The calls enqueue on hip_stream and return; errors as for the other
+ * calls (galore_last_error(NULL)).  Uses hp->rank, scale, beta1, weight_decay, update_gap, auto_refresh,
+ * refresh_iters, seed (beta2 and eps are Adam's and are not used).  Deterministic: every sum has a fixed order. */
+typedef struct {
+  galore_tensor proj;  /* P (rows x r) for rows <= cols, Q (cols x r) otherwise */
+  galore_tensor m;     /* first moment of the clipped update: r x cols or rows x r, ld == its cols */
+  galore_tensor row;   /* 1 x (rows of m): decayed row sums of R^2 */
+  galore_tensor col;   /* 1 x (cols of m): decayed column sums of R^2 */
+} galore_adafactor_state;
+
+/* Bytes of device workspace (256-byte aligned) the step and the refresh below need for a weight of W's shape
+ * and dtype; uses hp->rank. */
+galore_status galore_adafactor_workspace_bytes(const galore_hparams* hp, const galore_tensor* W, size_t* out_bytes);
+
+/* One step: R = P^T G (or G Q), the update above for step k = t + 1, weight update in the epilogue of the
+ * back-projection (the rows x cols update is never stored).  With hp->auto_refresh and t a multiple of
+ * hp->update_gap, the projector is first recomputed from this G (the refresh test of Algorithm 2). */
+galore_status galore_adafactor_step(const galore_hparams* hp, const galore_tensor* W, const galore_tensor* G,
+                                    const galore_adafactor_state* S, int64_t t, float lr,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The projector from G, exactly as galore_refresh_subspace computes it.  m, row, col are not touched. */
+galore_status galore_adafactor_refresh(const galore_hparams* hp, const galore_tensor* G, const galore_adafactor_state* S,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Stage call: the update block alone.  R fp32 (rows x cols, any ld); M fp32 dense, R's shape; row 1 x rows, col
+ * 1 x cols, fp32; N fp32 or bf16, R's shape, dense; k >= 1 the 1-based step.  Updates M, row, col in place and
+ * writes N.  workspace: 256-byte aligned, at least 4 * (ceil(cols / 256) * rows + ceil(rows / 32) * (cols +
+ * ceil(cols / 256)) + 4) bytes of partial sums. */
+galore_status galore_adafactor(const galore_tensor* R, const galore_tensor* M, const galore_tensor* row, const galore_tensor* col,
+                               const galore_tensor* N, float beta1, int64_t k, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- Instrumentation (measurement only, no part of the method) ----
  * Between galore_profile_start and galore_profile_stop every kernel group that galore_step or
  * galore_refresh_subspace enqueues is bracketed by a pair of HIP events on the context's

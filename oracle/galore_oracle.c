@@ -140,7 +140,7 @@ void oracle_adam(const double* R, double* M, double* V, double* N, int64_t count
 
 /* ---------- Adafactor on the projected gradient ---------------------------- */
 
-/* The paper applies GaLore to "Adafactor with first-order statistics" (Sec. 4.3, Sec. 5) and prints no
+/* The paper applies GaLore to Adafactor with first-order statistics (Sec. 4.3, Sec. 5) and prints no
  * equations for it: PARITY UNPINNED by the paper.  What is stated here is the published Adafactor update
  * for a matrix (Shazeer and Stern 2018: factored second moment, update clipping, decay rate
  * 1 - k^decay_pow, optional momentum) on the rows x cols projected gradient R, with the learning rate

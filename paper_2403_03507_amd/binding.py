@@ -33,6 +33,10 @@ class galore_two_sided_state(ctypes.Structure):
     _fields_ = [("p", galore_tensor), ("q", galore_tensor), ("m", galore_tensor), ("v", galore_tensor)]
 
 
+class galore_adafactor_state(ctypes.Structure):
+    _fields_ = [("proj", galore_tensor), ("m", galore_tensor), ("row", galore_tensor), ("col", galore_tensor)]
+
+
 class galore_hparams(ctypes.Structure):
     _fields_ = [("rank", ctypes.c_int32), ("update_gap", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -51,7 +55,8 @@ EXPORTS = ["galore_status_string", "galore_workspace_bytes", "galore_init", "gal
            "galore_destroy", "galore_transpose", "galore_project", "galore_adam", "galore_adam_q8", "galore_project_back",
            "galore_profile_start", "galore_profile_stop", "galore_set_concurrency",
            "galore_set_call_overlap", "galore_set_fused_adam", "galore_join", "galore_get_stream",
-           "galore_two_sided_workspace_bytes", "galore_two_sided_step", "galore_two_sided_refresh"]
+           "galore_two_sided_workspace_bytes", "galore_two_sided_step", "galore_two_sided_refresh",
+           "galore_adafactor_workspace_bytes", "galore_adafactor_step", "galore_adafactor_refresh", "galore_adafactor"]
 STAGES = ["project_left", "project_right", "adam", "back", "transpose", "refresh"]
 
 _lib = None
@@ -93,6 +98,11 @@ def lib():
         L.galore_two_sided_workspace_bytes.argtypes = [hp, tp, ctypes.POINTER(ctypes.c_size_t)]
         L.galore_two_sided_step.argtypes = [hp, tp, tp, tsp, i64, f32, vp, ctypes.c_size_t, vp]
         L.galore_two_sided_refresh.argtypes = [hp, tp, tsp, vp, ctypes.c_size_t, vp]
+        afp = ctypes.POINTER(galore_adafactor_state)
+        L.galore_adafactor_workspace_bytes.argtypes = [hp, tp, ctypes.POINTER(ctypes.c_size_t)]
+        L.galore_adafactor_step.argtypes = [hp, tp, tp, afp, i64, f32, vp, ctypes.c_size_t, vp]
+        L.galore_adafactor_refresh.argtypes = [hp, tp, afp, vp, ctypes.c_size_t, vp]
+        L.galore_adafactor.argtypes = [tp, tp, tp, tp, tp, f32, i64, vp, ctypes.c_size_t, vp]
         L.galore_profile_start.argtypes = [vp]
         L.galore_profile_stop.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         _lib = L
@@ -280,6 +290,57 @@ class GaLoreTwoSided:
 
     def step(self, weight, grad, lr):
         galore_two_sided_step(self.hp, weight, grad, self.state(), self.t, lr, self.workspace)
+        self.t += 1
+
+
+def galore_adafactor_workspace_bytes(hp, w_desc):
+    out = ctypes.c_size_t(0)
+    _check(lib().galore_adafactor_workspace_bytes(ctypes.byref(hp), ctypes.byref(w_desc), ctypes.byref(out)))
+    return out.value
+
+
+def galore_adafactor_step(hp, W, G, state, t, lr, workspace):
+    _check(lib().galore_adafactor_step(ctypes.byref(hp), ctypes.byref(desc(W)), ctypes.byref(desc(G)), ctypes.byref(state),
+                                       int(t), lr, workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def galore_adafactor_refresh(hp, G, state, workspace):
+    _check(lib().galore_adafactor_refresh(ctypes.byref(hp), ctypes.byref(desc(G)), ctypes.byref(state),
+                                          workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def galore_adafactor(R, M, row, col, N, beta1, k, workspace):
+    """Stage call: the Adafactor update block on the projected gradient R; row, col are 1-D fp32 tensors."""
+    _check(lib().galore_adafactor(ctypes.byref(desc(R)), ctypes.byref(desc(M)), ctypes.byref(desc(row.view(1, -1))),
+                                  ctypes.byref(desc(col.view(1, -1))), ctypes.byref(desc(N)), beta1, int(k),
+                                  workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+class GaLoreAdafactor:
+    """One weight matrix under GaLore with Adafactor (first-order statistics on): owns the projector, the first
+    moment, the row and column statistics and the workspace (torch memory) and keeps the step count; all arithmetic
+    happens in the library."""
+
+    def __init__(self, weight, rank, device="cuda", **hparams):
+        m, n = weight.shape
+        self.hp = make_hparams(rank, **hparams)
+        shape = (rank, n) if m <= n else (m, rank)
+        self.proj = torch.zeros(min(m, n), rank, dtype=weight.dtype, device=device)
+        self.M = torch.zeros(*shape, dtype=torch.float32, device=device)
+        self.row = torch.zeros(shape[0], dtype=torch.float32, device=device)
+        self.col = torch.zeros(shape[1], dtype=torch.float32, device=device)
+        nbytes = galore_adafactor_workspace_bytes(self.hp, shape_desc(m, n, weight.dtype))
+        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        self.t = 0
+
+    def state(self):
+        return galore_adafactor_state(desc(self.proj), desc(self.M), desc(self.row.view(1, -1)), desc(self.col.view(1, -1)))
+
+    def refresh(self, grad):
+        galore_adafactor_refresh(self.hp, grad, self.state(), self.workspace)
+
+    def step(self, weight, grad, lr):
+        galore_adafactor_step(self.hp, weight, grad, self.state(), self.t, lr, self.workspace)
         self.t += 1
 
 

@@ -77,26 +77,6 @@ galore_status check_two_sided(const galore_hparams* hp, const galore_tensor* W, 
   return GALORE_OK;
 }
 
-// C (fp32, M x N dense) = A B with A as [M][K]; B as [N][K] (b_kcontig) or [K][N]
-hipError_t two_sided_gemm(DType dt, const void* A, int lda, const void* B, int ldb, bool b_kcontig, float* C, int M, int N, int K,
-                          hipStream_t stream) {
-  GemmGroup g{};
-  g.count = 1;
-  GemmProblem& p = g.p[0];
-  p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
-  p.M = M; p.N = N; p.K = K;
-  p.C = C; p.ldc = N;
-  return launch_gemm_group(g, dt, true, b_kcontig, Epilogue::StoreF32, stream);
-}
-
-hipError_t two_sided_transpose(DType dt, const void* src, int rows, int cols, int lds, void* dst, int ldd, hipStream_t stream) {
-  TransposeGroup g{};
-  g.count = 1;
-  g.p[0].src = src; g.p[0].rows = rows; g.p[0].cols = cols; g.p[0].lds = lds;
-  g.p[0].dst = dst; g.p[0].ldd = ldd;
-  return launch_transpose_group(g, dt, stream);
-}
-
 }  // namespace
 
 extern "C" {
@@ -132,10 +112,10 @@ galore_status galore_two_sided_step(const galore_hparams* hp, const galore_tenso
   float* T2 = reinterpret_cast<float*>(ws + L.t2);
   hipError_t e;
   // T1 (r x n) = P^T G, then R (r x r) = T1 Q: every product reads its operands in the storage dtype
-  e = two_sided_transpose(dt, S->p.data, m, r, (int)S->p.ld, ws + L.pt, m, stream);
-  if (e == hipSuccess) e = two_sided_gemm(dt, ws + L.pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
+  e = single_transpose(dt, S->p.data, m, r, (int)S->p.ld, ws + L.pt, m, stream);
+  if (e == hipSuccess) e = single_gemm_store(dt, ws + L.pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
   if (e == hipSuccess && dt != DType::F32) e = launch_cast_rows(T1, ws + L.t1c, r, n, n, dt, stream);
-  if (e == hipSuccess) e = two_sided_gemm(dt, ws + L.t1c, n, S->q.data, (int)S->q.ld, false, R, r, r, n, stream);
+  if (e == hipSuccess) e = single_gemm_store(dt, ws + L.t1c, n, S->q.data, (int)S->q.ld, false, R, r, r, n, stream);
   if (e != hipSuccess) return hip_fail(nullptr, e, "two-sided projection");
   // Adam on R (Algorithm 2, update block), k = t + 1
   {
@@ -156,7 +136,7 @@ galore_status galore_two_sided_step(const galore_hparams* hp, const galore_tenso
     if (e != hipSuccess) return hip_fail(nullptr, e, "two-sided Adam");
   }
   // T2 (n x r) = Q N^T, then W <- (1 - lr wd) W - lr alpha P T2^T in the epilogue of the last product
-  e = two_sided_gemm(dt, S->q.data, (int)S->q.ld, ws + L.nn, r, true, T2, n, r, r, stream);
+  e = single_gemm_store(dt, S->q.data, (int)S->q.ld, ws + L.nn, r, true, T2, n, r, r, stream);
   if (e == hipSuccess && dt != DType::F32) e = launch_cast_rows(T2, ws + L.t2c, n, r, r, dt, stream);
   if (e == hipSuccess) {
     GemmGroup g{};
@@ -199,17 +179,17 @@ galore_status galore_two_sided_refresh(const galore_hparams* hp, const galore_te
   if (left) {
     // rows of P^T G are s_i v_i^T: unit length makes them Q^T
     float* T1 = reinterpret_cast<float*>(ws + L.r_t1);
-    e = two_sided_gemm(dt, ws + L.r_pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
+    e = single_gemm_store(dt, ws + L.r_pt, m, G->data, (int)G->ld, false, T1, r, n, m, stream);
     if (e == hipSuccess) e = launch_normalize_rows(T1, ws + L.r_qt, r, n, n, dt, stream);
-    if (e == hipSuccess) e = two_sided_transpose(dt, ws + L.r_qt, r, n, n, S->q.data, (int)S->q.ld, stream);
+    if (e == hipSuccess) e = single_transpose(dt, ws + L.r_qt, r, n, n, S->q.data, (int)S->q.ld, stream);
   } else {
     // columns of G Q are s_i u_i
     float* Tg = reinterpret_cast<float*>(ws + L.r_tg);
     float* Tgt = reinterpret_cast<float*>(ws + L.r_tgt);
-    e = two_sided_gemm(dt, G->data, (int)G->ld, ws + L.r_qt, n, true, Tg, m, r, n, stream);
-    if (e == hipSuccess) e = two_sided_transpose(DType::F32, Tg, m, r, r, Tgt, m, stream);
+    e = single_gemm_store(dt, G->data, (int)G->ld, ws + L.r_qt, n, true, Tg, m, r, n, stream);
+    if (e == hipSuccess) e = single_transpose(DType::F32, Tg, m, r, r, Tgt, m, stream);
     if (e == hipSuccess) e = launch_normalize_rows(Tgt, ws + L.r_pt, r, m, m, dt, stream);
-    if (e == hipSuccess) e = two_sided_transpose(dt, ws + L.r_pt, r, m, m, S->p.data, (int)S->p.ld, stream);
+    if (e == hipSuccess) e = single_transpose(dt, ws + L.r_pt, r, m, m, S->p.data, (int)S->p.ld, stream);
   }
   return e == hipSuccess ? GALORE_OK : hip_fail(nullptr, e, "partner projector");
 }

@@ -1,0 +1,170 @@
+"""GPU parity of GaLore with Adafactor (galore_adafactor, galore_adafactor_step / _refresh) against the fp64 oracle.
+
+The paper names the combination (Sec. 4.3, Sec. 5: Adafactor with first-order statistics) and prints no equations, so
+parity with the paper is unpinned; the oracle states the published Adafactor update and is pinned in
+tests/test_oracle_adafactor.py.  Steps are compared with shared projectors (the oracle's projector, rounded to the
+storage dtype, is written into the device state, auto_refresh = 0), so both sides consume identical bits.
+
+Tolerances: every quantity is computed in fp32 from sums of up to 11008 fp32 terms, so N, M and the statistics are held
+to 1e-5 (relative Frobenius) against fp64, as the Adam path is; W to 1e-5 (fp32) / 2e-2 plus the per-entry bound (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, bf16_ulp, check_bf16_weights, dev, f32, relF, strided, to64
+from oracle import galore_oracle as orc
+from paper_2403_03507_amd import binding as gb
+from paper_2403_03507_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+GRAD = dict(kind="lowrank", signal_rank=32, sigma0=10.0, decay=0.8, noise=0.01)
+
+
+def _stage(rows, cols, n_dtype, beta1, steps, seed=0, ld_pad=0, scale=lambda k: 1.0):
+    g = torch.Generator().manual_seed(seed)
+    M = torch.zeros(rows, cols, device="cuda")
+    row = torch.zeros(rows, device="cuda")
+    col = torch.zeros(cols, device="cuda")
+    N = torch.empty(rows, cols, dtype=wl.TORCH_DTYPE[n_dtype], device="cuda")
+    ws = torch.empty(4 * ((cols + 255) // 256 * rows + (rows + 31) // 32 * (cols + (cols + 255) // 256) + 4) + 256, dtype=torch.uint8, device="cuda")
+    Mo, ro, co = np.zeros((rows, cols)), np.zeros(rows), np.zeros(cols)
+    for k in range(1, steps + 1):
+        R = (torch.randn(rows, cols, generator=g) * torch.rand(rows, 1, generator=g) * 3.0 * scale(k)).float()
+        Rd = strided(R.cuda(), ld_pad) if ld_pad else R.cuda()
+        gb.galore_adafactor(Rd, M, row, col, N, f32(beta1), k, ws)
+        torch.cuda.synchronize()
+        No = orc.adafactor(to64(R), Mo, ro, co, f32(beta1), k)
+        assert relF(to64(M), Mo) <= 1e-5, (k, relF(to64(M), Mo))
+        assert relF(to64(row), ro) <= 1e-5 and relF(to64(col), co) <= 1e-5, k
+        if n_dtype == "f32":
+            assert relF(to64(N), No) <= 1e-5, (k, relF(to64(N), No))
+            assert torch.equal(N, M)                                  # N = M
+        else:
+            Nr = orc.round_storage(No, "bf16")
+            # one bf16 ulp, plus the fp32 error of a momentum that nearly cancels (absolute, not relative to the small result)
+            assert np.all(np.abs(to64(N) - Nr) <= bf16_ulp(Nr) + 2e-6), (k, float(np.abs(to64(N) - Nr).max()))
+            assert np.mean(to64(N) == Nr) >= 0.99
+        Mo[:] = orc.round_storage(Mo, "f32"); ro[:] = orc.round_storage(ro, "f32"); co[:] = orc.round_storage(co, "f32")
+
+
+@pytest.mark.parametrize("n_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(48, 688), (688, 48), (33, 257), (257, 33), (1, 300), (300, 1), (64, 64)])
+def test_update_block_against_the_oracle(shape, n_dtype):
+    # several workgroup tiles in both directions, ragged tails, single-row and single-column statistics;
+    # the gradient scale changes from step to step so the decay of the statistics matters
+    _stage(shape[0], shape[1], n_dtype, 0.9, steps=5, seed=shape[0], scale=lambda k: 0.3 * k)
+
+
+def test_update_block_without_momentum_and_with_padded_rows_of_R():
+    _stage(40, 515, "f32", 0.0, steps=3, seed=7, ld_pad=5)       # NaN beyond the row ends of R must not enter any sum
+
+
+@pytest.mark.parametrize("shape", [(1024, 11008), (11008, 1024)])
+def test_update_block_at_the_shapes_of_the_7b_stack(shape):
+    # R of a 4096 x 11008 (11008 x 4096) gradient at r = 1024: every entry against the oracle, 43 x 32 (4 x 344) tiles
+    _stage(shape[0], shape[1], "bf16", 0.9, steps=2, seed=11)
+
+
+def test_zero_and_tiny_gradients_stay_finite():
+    rows, cols = 24, 300
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    for value in (0.0, 1e-18):
+        M = torch.zeros(rows, cols, device="cuda"); row = torch.zeros(rows, device="cuda"); col = torch.zeros(cols, device="cuda")
+        N = torch.empty(rows, cols, device="cuda")
+        gb.galore_adafactor(torch.full((rows, cols), value, device="cuda"), M, row, col, N, 0.9, 1, ws)
+        torch.cuda.synchronize()
+        assert torch.isfinite(N).all() and torch.isfinite(row).all() and torch.isfinite(col).all()
+        No = orc.adafactor(np.full((rows, cols), value), np.zeros((rows, cols)), np.zeros(rows), np.zeros(cols), f32(0.9), 1)
+        assert np.abs(to64(N) - No).max() <= 1e-6
+
+
+def _run(shape, dtype, rank, steps, lr=1e-3, weight_decay=0.0, pad=0, beta1=0.9):
+    m, n = shape
+    src = wl.GradientSource(m, n, 300 + m + n, dtype=dtype, **GRAD)
+    W0 = wl.make_weight(m, n, 400 + m, dtype)
+    o = orc.GaLoreAdafactorTensor(to64(W0), rank, scale=f32(0.25), beta1=f32(beta1), weight_decay=f32(weight_decay), dtype=dtype,
+                                  auto_refresh=False)
+    o.refresh(to64(src.grad(1000)))
+    lr = f32(lr)
+    Wd = strided(W0.cuda(), pad) if pad else W0.cuda()
+    opt = gb.GaLoreAdafactor(Wd, rank, beta1=beta1, weight_decay=weight_decay, auto_refresh=False)
+    opt.proj.copy_(dev(o.proj, dtype))                 # the same projector bits on the device
+    W_before = to64(Wd)
+    for step in range(steps):
+        G = src.grad(step)
+        o.step(to64(G), lr)
+        Gd = strided(G.cuda(), pad) if pad else G.cuda()
+        opt.step(Wd, Gd, lr)
+        torch.cuda.synchronize()
+        assert opt.t == o.t
+        e = dict(W=relF(to64(Wd), o.W), M=relF(to64(opt.M), o.M), row=relF(to64(opt.row), o.rowv), col=relF(to64(opt.col), o.colv))
+        assert e["W"] <= TOL[dtype] and e["M"] <= 1e-5 and e["row"] <= 1e-5 and e["col"] <= 1e-5, (step, e)
+    if dtype == "bf16":
+        check_bf16_weights(to64(Wd), o.W, W_before, steps, lr, 0.25, where=shape)
+    else:
+        assert np.mean(to64(Wd) != W_before) > 0.5       # the weights really moved
+
+
+@pytest.mark.parametrize("shape", [(192, 320), (320, 192), (256, 256), (130, 257)])
+def test_steps_fp32_shared_projector(shape):
+    _run(shape, "f32", 48, steps=5)
+
+
+@pytest.mark.parametrize("shape", [(256, 688), (688, 256), (512, 512)])
+def test_steps_bf16_shared_projector(shape):
+    _run(shape, "bf16", 64, steps=4)
+
+
+def test_steps_with_weight_decay_padded_rows_and_no_momentum():
+    _run((192, 320), "f32", 48, steps=3, weight_decay=0.1, pad=3, beta1=0.0)
+
+
+@pytest.mark.parametrize("shape", [(256, 688), (688, 256)])
+def test_own_refresh_finds_the_oracles_subspace_and_steps_follow(shape):
+    # auto_refresh: the first step refreshes from its own gradient (t mod T == 0), as Algorithm 2 does
+    m, n = shape
+    r = 48
+    src = wl.GradientSource(m, n, 21, "gapped", dtype="f32", gap_rank=r)
+    W = wl.make_weight(m, n, 5, "f32").cuda()
+    W0 = W.clone()
+    opt = gb.GaLoreAdafactor(W, r, update_gap=3, refresh_iters=8, auto_refresh=True)
+    G = src.grad(0)
+    opt.step(W, G.cuda(), 1e-3)
+    torch.cuda.synchronize()
+    P0, sig = orc.projector(to64(G), r)
+    P = to64(opt.proj)
+    assert np.linalg.norm(P @ P.T - P0 @ P0.T) <= 1e-3
+    # the step that followed, replayed by the oracle from the device's projector
+    o = orc.GaLoreAdafactorTensor(to64(W0), r, scale=f32(0.25), beta1=f32(0.9), dtype="f32", auto_refresh=False)
+    o.set_projector(P)
+    o.step(to64(G), f32(1e-3))
+    assert relF(to64(W), o.W) <= 1e-5 and relF(to64(opt.M), o.M) <= 1e-5
+
+
+def test_determinism_and_argument_checks():
+    shape, r = (256, 688), 64
+    outs = []
+    for _ in range(2):
+        src = wl.GradientSource(*shape, 9, dtype="bf16", **GRAD)
+        W = wl.make_weight(*shape, 3, "bf16").cuda()
+        opt = gb.GaLoreAdafactor(W, r, update_gap=2, refresh_iters=2, auto_refresh=True)
+        for step in range(3):
+            opt.step(W, src.grad(step).cuda(), 1e-3)
+        torch.cuda.synchronize()
+        outs.append((W.clone(), opt.M.clone(), opt.row.clone(), opt.col.clone(), opt.proj.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    # a state that does not fit the tensor, a workspace that is too small
+    W = wl.make_weight(*shape, 3, "f32").cuda()
+    opt = gb.GaLoreAdafactor(W, r, auto_refresh=False)
+    G = torch.zeros_like(W)
+    opt.row = torch.zeros(r + 1, device="cuda")
+    with pytest.raises(gb.GaloreError) as e:
+        opt.step(W, G, 1e-3)
+    assert e.value.status == 7
+    opt.row = torch.zeros(r, device="cuda")
+    opt.workspace = opt.workspace[:256]
+    with pytest.raises(gb.GaloreError) as e:
+        opt.step(W, G, 1e-3)
+    assert e.value.status == 6
