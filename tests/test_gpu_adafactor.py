@@ -111,7 +111,7 @@ def test_steps_fp32_shared_projector(shape):
     _run(shape, "f32", 48, steps=5)
 
 
-@pytest.mark.parametrize("shape", [(256, 688), (688, 256), (512, 512)])
+@pytest.mark.parametrize("shape", [(256, 688), (688, 256), (512, 512), (128, 333), (333, 128)])
 def test_steps_bf16_shared_projector(shape):
     _run(shape, "bf16", 64, steps=4)
 
