@@ -8,7 +8,7 @@
 // partial sums of U^2; the clipping factor; the update.  Every sum has a fixed order (partials per workgroup, added in index order by one
 // workgroup): no atomics, bit-identical from run to run.  Bound by memory traffic: 3 reads of R, one read and write of M,
 // one write of N.
-#include "common.hpp"
+#include "adafactor.hpp"
 
 namespace galore {
 namespace {

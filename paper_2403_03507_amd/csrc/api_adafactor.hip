@@ -1,6 +1,7 @@
 // GaLore with Adafactor (first-order statistics on) as the optimizer of the projected gradient, behind the C ABI: a
 // composition of the library's kernels for one tensor, no context (the paper names this combination in Sec. 4.3 and
 // Sec. 5 and prints no equations for it; adafactor.hip states the update that is used).
+#include "adafactor.hpp"
 #include "api_internal.hpp"
 #include "refresh.hpp"
 

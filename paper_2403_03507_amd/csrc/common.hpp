@@ -166,23 +166,6 @@ hipError_t launch_pad_rows_group(const PadGroup& g, hipStream_t stream);
 // ---- small utilities -----------------------------------------------------------------------
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
 // dst (rows x cols, leading dimension ldd, dtype dt) <- src (dense fp32), rounded to nearest even
-// ---- Adafactor with first-order statistics on one projected gradient (adafactor.hip) ---------------
-// R rows x cols fp32 (row stride ldr); M rows x cols fp32 dense; rowv (rows), colv (cols) fp32; N rows x cols in n_dtype,
-// dense.  `scratch` holds adafactor_scratch_floats(rows, cols) floats of partial sums (fixed reduction order, no atomics).
-struct AdafactorProblem {
-  const float* R;
-  float* M;
-  float* rowv;
-  float* colv;
-  void* N;
-  float* scratch;
-  int rows, cols, ldr;
-  float beta1, beta2t;   // momentum; decay rate 1 - k^decay_pow of this step
-  float eps1, clip_d;
-};
-size_t adafactor_scratch_floats(int rows, int cols);
-hipError_t launch_adafactor(const AdafactorProblem& p, DType n_dtype, hipStream_t stream);
-
 hipError_t launch_cast_rows(const float* src, void* dst, int rows, int cols, int ldd, DType dt, hipStream_t stream);
 // the same with every row scaled to unit Euclidean length (a zero row stays zero)
 hipError_t launch_normalize_rows(const float* src, void* dst, int rows, int cols, int ldd, DType dt, hipStream_t stream);
