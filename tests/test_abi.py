@@ -213,3 +213,58 @@ def test_two_sided_validation_happens_before_any_device_work():
     s = state(); s.v.cols = r + 1; s.v.ld = r + 1
     assert _status(_two_sided_call, hp, w, g, s, 4096, need) == 7                            # moments are rank x rank
     assert _status(_two_sided_call, _hp(rank=9, auto_refresh=False), w, g, state(), 4096, need) == 4
+
+
+def _adafactor_call(hp, w, g, st, ws_ptr, ws_bytes, t=0):
+    L = gb.lib()
+    gb._check(L.galore_adafactor_step(ctypes.byref(hp), ctypes.byref(w) if w is not None else None,
+                                      ctypes.byref(g) if g is not None else None, ctypes.byref(st), t, 1e-3,
+                                      ws_ptr, ws_bytes, None))
+
+
+@pytest.mark.parametrize("shape", [(8, 16), (16, 8)])
+def test_adafactor_validation_happens_before_any_device_work(shape):
+    hp = _hp(rank=4, auto_refresh=False)
+    m, n = shape
+    r = 4
+    k, rows, cols = min(m, n), (r if m <= n else m), (n if m <= n else r)      # R, M: r x n (m <= n) or m x r
+    w = gb.galore_tensor(4096, m, n, n, gb.GALORE_F32)
+    g = gb.galore_tensor(4096, m, n, n, gb.GALORE_F32)
+
+    def state():
+        return gb.galore_adafactor_state(gb.galore_tensor(4096, k, r, r, gb.GALORE_F32), gb.galore_tensor(4096, rows, cols, cols, gb.GALORE_F32),
+                                         gb.galore_tensor(4096, 1, rows, rows, gb.GALORE_F32), gb.galore_tensor(4096, 1, cols, cols, gb.GALORE_F32))
+    need = gb.galore_adafactor_workspace_bytes(hp, gb.shape_desc(m, n, torch.float32))
+    assert need % 256 == 0 and need >= (r * k + 2 * rows * cols) * 4          # transposed projector, R, N
+    assert _status(gb.galore_adafactor_workspace_bytes, _hp(rank=9), gb.shape_desc(m, n, torch.float32)) == 4
+    assert _status(_adafactor_call, hp, w, None, state(), 4096, need) == 1                  # G NULL
+    assert _status(_adafactor_call, hp, w, g, state(), 0, need) == 6                         # workspace NULL
+    assert _status(_adafactor_call, hp, w, g, state(), 4096 + 8, need) == 5                  # misaligned
+    assert _status(_adafactor_call, hp, w, g, state(), 4096, need - 256) == 6                # too small
+    assert _status(_adafactor_call, hp, w, g, state(), 4096, need, t=-1) == 1
+    bad = gb.galore_tensor(4096, m, n + 1, n + 1, gb.GALORE_F32)
+    assert _status(_adafactor_call, hp, w, bad, state(), 4096, need) == 2                   # G shape
+    s = state(); s.proj.rows = k + 1
+    assert _status(_adafactor_call, hp, w, g, s, 4096, need) == 7                            # projector is min(rows, cols) x rank
+    s = state(); s.proj.dtype = gb.GALORE_BF16
+    assert _status(_adafactor_call, hp, w, g, s, 4096, need) == 3
+    s = state(); s.m.rows = rows + 1
+    assert _status(_adafactor_call, hp, w, g, s, 4096, need) == 7                            # M has R's shape
+    s = state(); s.row.cols = rows + 1; s.row.ld = rows + 1
+    assert _status(_adafactor_call, hp, w, g, s, 4096, need) == 7                            # one row statistic per row of M
+    s = state(); s.col.dtype = gb.GALORE_BF16
+    assert _status(_adafactor_call, hp, w, g, s, 4096, need) == 3                            # statistics are fp32
+    # the stage call: shapes, dtypes, step number, workspace
+    L = gb.lib()
+    R = gb.galore_tensor(4096, rows, cols, cols, gb.GALORE_F32)
+    st = state()
+
+    def stage(R=R, M=st.m, row=st.row, col=st.col, N=None, beta1=0.9, k=1, ws=4096, nbytes=1 << 20):
+        N = N if N is not None else gb.galore_tensor(4096, rows, cols, cols, gb.GALORE_F32)
+        gb._check(L.galore_adafactor(ctypes.byref(R), ctypes.byref(M), ctypes.byref(row), ctypes.byref(col), ctypes.byref(N),
+                                     beta1, k, ws, nbytes, None))
+    assert _status(stage, k=0) == 1
+    assert _status(stage, beta1=1.0) == 1
+    assert _status(stage, nbytes=16) == 6
+    assert _status(stage, N=gb.galore_tensor(4096, rows, cols + 1, cols + 1, gb.GALORE_F32)) == 2
+    assert _status(stage, R=gb.galore_tensor(4096, rows, cols, cols, gb.GALORE_BF16)) == 3
