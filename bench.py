@@ -30,12 +30,12 @@ PEAK_HBM_GBS = 8000.0
 # only while the digest still matches (null otherwise: re-run the probe and update both together).
 TRAFFIC_SOURCES = ["gemm_mfma_dl.hpp", "gemm_proj_dl.hpp", "proj.hip", "gemm_mfma.hpp", "gemm_dispatch.hpp", "common.hpp", "adam.hip", "adam_entry.hpp"]
 MEASURED_TRAFFIC_7B = {
-    "sources": "7583bf5ad650004d",
+    "sources": "7f1842964fa89488",
     "bytes": {   # read (2 x FETCH_SIZE KiB x 1024) + written (WRITE_SIZE KiB x 1024)
-        "project_left": (711.2e6 + 218.9e6) + (16.8e6 + 1.0e6),   # the grouped projection launch of both orientations + the sum of the split tiles' slabs
-        "project_left_fused_adam": (1407.5e6 + 639.2e6) + (19.0e6 + 2.6e6),
-        "back": 1110.3e6 + 404.8e6,
-        "adam": (472.0e6 + 135.3e6) + (393.2e6 + 112.7e6),
+        "project_left": (708.1e6 + 218.9e6) + (16.8e6 + 1.0e6),   # the grouped projection launch of both orientations + the sum of the split tiles' slabs
+        "project_left_fused_adam": (1420.5e6 + 636.7e6) + (19.0e6 + 2.6e6),
+        "back": 1124.7e6 + 404.8e6,
+        "adam": (471.9e6 + 135.3e6) + (393.2e6 + 112.7e6),
     },
 }
 

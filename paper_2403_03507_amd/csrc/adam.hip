@@ -68,7 +68,11 @@ __global__ __launch_bounds__(256) void adam_group_kernel(const AdamGroup grp) {
 __device__ __forceinline__ f32x4 load4(const float* p) { f32x4 v; __builtin_memcpy(&v, p, sizeof v); return v; }
 __device__ __forceinline__ void store4(float* p, f32x4 v) { __builtin_memcpy(p, &v, sizeof v); }
 
-template <class TN>
+// RAGGED: some tile of the launch is not a full, aligned 64 x 64 tile.  The variant without that path needs 48 registers
+// per lane instead of 55 (bf16 N), which is what lets a wavefront of it share a SIMD with the two wavefronts of the
+// projection GEMM (2 x 232 of the 512 registers per lane): the Adam pass of one call then runs on the CUs that the
+// projection of the next call occupies.
+template <class TN, bool RAGGED>
 __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGroup grp) {
   constexpr int TS = 64;
   constexpr int VEC = 16 / sizeof(TN);          // N elements per 16 bytes
@@ -89,18 +93,22 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
     const int i0 = (t / tiles_c) * TS, j0 = (t % tiles_c) * TS;
     const bool full = aligned && i0 + TS <= rows && j0 + TS <= cols;
     if (full) {
-#pragma unroll
+      // tile origin as a (wave-uniform) pointer, in-tile offsets in 32 bits: fewer address registers per lane
+      const float* __restrict__ Rt = R + ((size_t)i0 * ldr + j0);
+      float* __restrict__ Mt = M + ((size_t)i0 * cols + j0);
+      float* __restrict__ Vt = V + ((size_t)i0 * cols + j0);
+#pragma unroll 1
       for (int ps = 0; ps < 4; ++ps) {
         const int i = ps * 16 + (threadIdx.x >> 4), j = (threadIdx.x & 15) * 4;
-        const size_t idx = (size_t)(i0 + i) * cols + j0 + j;
-        const size_t ridx = (size_t)(i0 + i) * ldr + j0 + j;
+        const int idx = i * cols + j;
+        const int ridx = i * ldr + j;
         f32x4 g, m, v;
         if (cols4) {
-          g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + ridx));
-          m = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(M + idx));
-          v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(V + idx));
+          g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Rt + ridx));
+          m = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Mt + idx));
+          v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Vt + idx));
         } else {
-          g = load4(R + ridx); m = load4(M + idx); v = load4(V + idx);
+          g = load4(Rt + ridx); m = load4(Mt + idx); v = load4(Vt + idx);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -109,11 +117,11 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
           m[e] = me; v[e] = ve;
         }
         if (cols4) {
-          __builtin_nontemporal_store(m, reinterpret_cast<f32x4*>(M + idx));
-          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(V + idx));
+          __builtin_nontemporal_store(m, reinterpret_cast<f32x4*>(Mt + idx));
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(Vt + idx));
         } else {
-          store4(M + idx, m);
-          store4(V + idx, v);
+          store4(Mt + idx, m);
+          store4(Vt + idx, v);
         }
       }
       __syncthreads();
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(256) void adam_transpose_group_kernel(const AdamGro
         *reinterpret_cast<uint4*>(N + (size_t)(j0 + j) * rows + i0 + i) = *reinterpret_cast<const uint4*>(&tile[j][i]);
       }
       __syncthreads();
-    } else {
+    } else if constexpr (RAGGED) {
       for (int e = threadIdx.x; e < TS * TS; e += 256) {
         const int i = e / TS, j = e % TS;
         if (i0 + i < rows && j0 + j < cols) {
@@ -153,8 +161,16 @@ hipError_t launch_adam_group(const AdamGroup& g, DType n_dtype, hipStream_t stre
     }
     if (maxtiles == 0) return hipSuccess;
     const dim3 grid((unsigned)(maxtiles > 4096 ? 4096 : maxtiles), (unsigned)g.count);
-    if (n_dtype == DType::BF16) hipLaunchKernelGGL(adam_transpose_group_kernel<__bf16>, grid, dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL(adam_transpose_group_kernel<float>, grid, dim3(256), 0, stream, g);
+    // every tile of every problem full and 16-byte aligned on the N side: the lean variant
+    bool ragged = false;
+    for (int i = 0; i < g.count; ++i) ragged = ragged || g.p[i].rows % 64 != 0 || g.p[i].cols % 64 != 0;
+    if (n_dtype == DType::BF16) {
+      if (ragged) hipLaunchKernelGGL((adam_transpose_group_kernel<__bf16, true>), grid, dim3(256), 0, stream, g);
+      else hipLaunchKernelGGL((adam_transpose_group_kernel<__bf16, false>), grid, dim3(256), 0, stream, g);
+    } else {
+      if (ragged) hipLaunchKernelGGL((adam_transpose_group_kernel<float, true>), grid, dim3(256), 0, stream, g);
+      else hipLaunchKernelGGL((adam_transpose_group_kernel<float, false>), grid, dim3(256), 0, stream, g);
+    }
     return hipGetLastError();
   }
   int64_t maxcount = 0;
