@@ -7,7 +7,8 @@ LLaMA-7B-shaped stack (32 layers x {4x 4096x4096, 2x 4096x11008, 11008x4096}, bf
 M/V, r = 1024), called one layer at a time in backward order, the way a per-layer weight update
 during back-propagation calls it; consecutive calls overlap on the library's streams, which
 are joined into the caller's stream once per step (galore_join), when the next forward pass
-needs the weights.  Prints ONE JSON line.
+needs the weights.  On the step that carries the refresh a call takes two layers (the refresh is
+latency-bound and cheaper per tensor with more tensors per launch).  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -105,6 +106,10 @@ def main():
                     help="layers handed to one galore_step call (0 = the whole stack in one call; the library cuts a call "
                          "into launch groups of at most 16 tensors).  Default: 1 for llama7b (the per-layer update the "
                          "headline configuration names), 2 for the smaller stacks, whose launches fill the chip better then")
+    ap.add_argument("--refresh-layers-per-call", type=int, default=None,
+                    help="layers handed to one call on the steps that carry a subspace refresh (t mod T == 0).  The refresh is a "
+                         "long chain of short launches whose cost per tensor falls with the tensors per launch, so a training loop "
+                         "can batch two layers on those steps only.  Default: 2 (or --layers-per-call if that is larger)")
     ap.add_argument("--join-every-call", action="store_true",
                     help="join the library streams at the end of every per-layer call (3 chains inside each call) "
                          "instead of overlapping consecutive calls and joining once per step")
@@ -112,6 +117,8 @@ def main():
     args = ap.parse_args()
     if args.layers_per_call is None:
         args.layers_per_call = 1 if args.config == "llama7b" else 2
+    if args.refresh_layers_per_call is None:
+        args.refresh_layers_per_call = max(args.layers_per_call, 2) if args.layers_per_call > 0 else 0
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (nothing here uses a "
               "second GPU)" % args.gpus, file=sys.stderr)
@@ -156,7 +163,7 @@ def main():
 
     # one call's workspace per call in flight: overlapped calls then overlap their subspace refreshes as well
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
-                    workspace_factor=args.in_flight * min(max(args.layers_per_call, 1), 2))
+                    workspace_factor=args.in_flight * min(max(args.layers_per_call, args.refresh_layers_per_call, 1), 2))
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     gb.galore_set_fused_adam(opt.ctx, args.fused_adam)
     overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
@@ -164,15 +171,25 @@ def main():
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
     LPC = args.layers_per_call if args.layers_per_call > 0 else L
-    # argument arrays are marshalled once: weights and pooled gradients stay where they are
-    call_w = {l: gb.tensor_array(x for k in range(l, min(l + LPC, L)) for x in w_descs[k]) for l in range(0, L, LPC)}
-    # the layers of one call take consecutive gradient sets of the pool
-    call_g = [{l: gb.tensor_array(x for k in range(l, min(l + LPC, L)) for x in g_descs[(s + k - l) % POOL])
-               for l in range(0, L, LPC)} for s in range(POOL)]
+    LPC_REFRESH = args.refresh_layers_per_call if args.refresh_layers_per_call > 0 else L
 
-    def one_step(step_index):
-        for l in reversed(range(0, L, LPC)):  # backward order, one layer (or LPC layers) per call
-            gb.galore_step(opt.ctx, call_w[l], call_g[(l // LPC + step_index) % POOL][l], n_per_layer * l, len(call_w[l]), lr)
+    def call_arrays(lpc):
+        # argument arrays are marshalled once: weights and pooled gradients stay where they are
+        cw = {l: gb.tensor_array(x for k in range(l, min(l + lpc, L)) for x in w_descs[k]) for l in range(0, L, lpc)}
+        # the layers of one call take consecutive gradient sets of the pool
+        cg = [{l: gb.tensor_array(x for k in range(l, min(l + lpc, L)) for x in g_descs[(s + k - l) % POOL])
+               for l in range(0, L, lpc)} for s in range(POOL)]
+        return cw, cg
+
+    grouping = {LPC: call_arrays(LPC)}
+    if LPC_REFRESH not in grouping:
+        grouping[LPC_REFRESH] = call_arrays(LPC_REFRESH)
+
+    def one_step(step_index, refresh=False):
+        lpc = LPC_REFRESH if refresh else LPC
+        call_w, call_g = grouping[lpc]
+        for l in reversed(range(0, L, lpc)):  # backward order, one layer (or lpc layers) per call
+            gb.galore_step(opt.ctx, call_w[l], call_g[(l // lpc + step_index) % POOL][l], n_per_layer * l, len(call_w[l]), lr)
         gb.galore_join(opt.ctx)  # the next forward pass needs the weights: one join per step
 
     def timed(fn):
@@ -186,7 +203,7 @@ def main():
 
     # step 0: t mod T == 0 for every tensor, so it carries the subspace refresh (in the default schedule
     # the refreshes of consecutive calls overlap like the steps do)
-    first_ms = timed(lambda: one_step(0))
+    first_ms = timed(lambda: one_step(0, refresh=True))
     for w in range(1, max(args.warmup, 1)):
         one_step(w)
     K = args.steps
@@ -207,7 +224,7 @@ def main():
     for i in range(len(W)):
         opt.set_step(i, 0)
     gb.galore_profile_start(opt.ctx)
-    one_step(0)
+    one_step(0, refresh=True)
     torch.cuda.synchronize()
     refresh_serial_ms = gb.galore_profile_stop(opt.ctx)["refresh"][0]
     gb.galore_set_concurrency(opt.ctx, args.lanes)
@@ -343,6 +360,7 @@ def main():
         # ms per step and as a fraction of the ordinary step next to it
         "refresh": {"step0_ms": first_ms, "ms_per_layer_set": (first_ms - ms_per_step) / L,
                     "ms_per_layer_set_serial": refresh_serial_ms / L,
+                    "layers_per_call": min(LPC_REFRESH, L),
                     "amortised_ms_per_step": (first_ms - ms_per_step) / cfg["update_gap"],
                     "amortised_frac_of_step": (first_ms - ms_per_step) / cfg["update_gap"] / ms_per_step},
         "step_flops": 4.0 * sum(m * n for m, n in shapes) * r * L,
