@@ -367,3 +367,54 @@ def test_overlapped_calls_same_tensors_twice_and_small_workspace():
     for x, y, z in zip(a, b, c):
         assert torch.equal(x, y)
         assert torch.equal(x, z)
+
+
+def test_instrumentation_counts_the_launches_of_a_step_and_changes_no_result():
+    # galore_profile_start / _stop bracket every kernel group with events: the stage table must show the launches
+    # Algorithm 2 needs (projection, Adam per orientation, back-projection; one refresh per group at t mod T == 0)
+    # and the weights and moments must be the bits of an unbracketed run.
+    shapes = [(128, 192), (192, 128), (256, 256)]   # LEFT, RIGHT, LEFT
+    rank, steps = 32, 3
+
+    def run(profiled):
+        W = [wl.make_weight(m, n, 40 + i, "bf16").cuda() for i, (m, n) in enumerate(shapes)]
+        opt = gb.GaLore(W, rank, update_gap=2, auto_refresh=True, refresh_iters=2)
+        gb.galore_set_concurrency(opt.ctx, 1)
+        srcs = [wl.GradientSource(m, n, 60 + i, "gapped", dtype="bf16", gap_rank=rank) for i, (m, n) in enumerate(shapes)]
+        table = None
+        if profiled:
+            gb.galore_profile_start(opt.ctx)
+        for step in range(steps):
+            opt.step(W, [s.grad(step).cuda() for s in srcs], 1e-2)
+        if profiled:
+            table = gb.galore_profile_stop(opt.ctx)
+        torch.cuda.synchronize()
+        out = [w.clone() for w in W] + [x.clone() for x in opt.M + opt.V + opt.proj]
+        opt.close()
+        return out, table
+
+    plain, _ = run(False)
+    bracketed, table = run(True)
+    for x, y in zip(plain, bracketed):
+        assert torch.equal(x, y)
+    assert set(table) == set(gb.STAGES)
+    launches = {k: v[1] for k, v in table.items()}
+    assert launches["refresh"] == 2                       # t = 0 and t = 2, one group of three tensors each
+    assert launches["back"] == steps
+    assert launches["project_left"] + launches["project_right"] >= steps
+    assert steps <= launches["adam"] <= 2 * steps         # one launch per orientation present in the group
+    for k, (ms, n) in table.items():
+        assert (ms > 0.0) == (n > 0), (k, ms, n)
+        assert ms < 1e4
+    # a second bracket starts from an empty table
+    opt2_W = [wl.make_weight(64, 96, 1, "f32").cuda()]
+    opt2 = gb.GaLore(opt2_W, 8)
+    gb.galore_profile_start(opt2.ctx)
+    empty = gb.galore_profile_stop(opt2.ctx)
+    assert all(v == (0.0, 0) for v in empty.values())
+    # the library's streams are exposed for callers that record events on them
+    handles = [gb.galore_get_stream(opt2.ctx, i) for i in range(3)]
+    assert all(h for h in handles) and len(set(handles)) == 3
+    with pytest.raises(gb.GaloreError):
+        gb.galore_get_stream(opt2.ctx, 3)
+    opt2.close()
