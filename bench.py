@@ -85,6 +85,34 @@ def probe_traffic(layers=3, steps=2, fused_adam=False):
     print("copy done; kernel sources digest", kernel_sources_digest(), flush=True)
 
 
+def probe_refresh():
+    """Workload of the rocprofv3 --pmc runs that read the traffic of ONE subspace refresh: the seven tensors of a
+    LLaMA-7B-shaped layer set (Gaussian bf16 gradients generated on the device; the launch sequence of a refresh does not
+    depend on the values, only the number of Jacobi sweeps that still rotate does), r = 1024, four rounds, then the same
+    1 GiB calibration copy as probe_traffic."""
+    import torch
+    from paper_2403_03507_amd import binding as gb
+    from paper_2403_03507_amd import workloads as wl
+    torch.cuda.set_device(0)
+    c = wl.CONFIGS["llama7b"]
+    shapes = wl.layer_shapes(c["d"], c["f"])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(6)
+    W = [(torch.randn(m, n, generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for (m, n) in shapes]
+    G = [(torch.randn(m, n, generator=gen, device="cuda") * 0.01).to(torch.bfloat16) for (m, n) in shapes]
+    opt = gb.GaLore(W, c["rank"], auto_refresh=False, refresh_iters=4)
+    gb.galore_set_concurrency(opt.ctx, 1)
+    opt.refresh(G)
+    torch.cuda.synchronize()
+    print("refresh done", flush=True)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    print("copy done", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +124,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-traffic", action="store_true",
                     help="run only the workload of the rocprofv3 --pmc traffic runs (see probe_traffic) and exit")
+    ap.add_argument("--probe-refresh", action="store_true",
+                    help="run only one subspace refresh of a 7B layer set plus the calibration copy (see probe_refresh) and exit")
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
@@ -133,6 +163,9 @@ def main():
     gb.lib()
     if args.probe_traffic:
         probe_traffic(fused_adam=bool(args.fused_adam))
+        return
+    if args.probe_refresh:
+        probe_refresh()
         return
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
