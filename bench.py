@@ -380,7 +380,8 @@ def main():
                                                                                    "fp32" if args.moments == "f32" else "8-bit", r,
                                                                                    "per-layer" if LPC == 1 else "%d-layer" % LPC, POOL),
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
-                   "adam": "in the projection GEMM's epilogue" if args.fused_adam else "separate kernel",
+                   "adam": ("in the projection GEMM's epilogue" if (args.fused_adam and args.moments == "f32" and dtype == "bf16")
+                            else "separate kernel"),  # the fused epilogue exists for fp32 moments on the large-tile kernel only
                    "schedule": "consecutive calls overlap on %d library streams, one join per step" % overlap if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},
         "roofline": roofline,
