@@ -129,9 +129,16 @@ def main():
     ap.add_argument("--lanes", type=int, default=3, help="concurrent chains inside one galore_step call (1 = serial)")
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32",
                     help="f32: fp32 moments (the headline configuration); q8: 8-bit block-wise moments (reported under its own metric name)")
-    ap.add_argument("--fused-adam", type=int, choices=[0, 1], default=0,
-                    help="1: Adam in the epilogue of the projection GEMM (two kernels per step); 0: separate Adam kernel (three)")
-    ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="overlapped calls: calls in flight (library streams used)")
+    ap.add_argument("--fused-adam", type=int, choices=[0, 1], default=None,
+                    help="1: Adam in the epilogue of the projection GEMM (two kernels per step); 0: separate Adam kernel (three).  Same "
+                         "bits either way.  Default: whichever is faster in the stack's schedule (measured): 1 for llama7b, llama350m and "
+                         "llama130m, 0 for llama1b; the fp32 llama60m stack has no fused epilogue")
+    ap.add_argument("--in-flight", type=int, choices=[2, 3], default=None,
+                    help="overlapped calls: calls in flight (library streams used) on ordinary steps.  Default: 2 for llama7b (measured "
+                         "faster than 3 there: the tail of one call's GEMM hides under the next call's, a third call only adds "
+                         "pressure on L2), 3 for the smaller stacks")
+    ap.add_argument("--refresh-in-flight", type=int, choices=[2, 3], default=3,
+                    help="calls in flight on the steps that carry a subspace refresh (its launches leave most of the chip idle, so three overlap well)")
     ap.add_argument("--layers-per-call", type=int, default=None,
                     help="layers handed to one galore_step call (0 = the whole stack in one call; the library cuts a call "
                          "into launch groups of at most 16 tensors).  Default: 1 for llama7b (the per-layer update the "
@@ -147,6 +154,11 @@ def main():
     args = ap.parse_args()
     if args.layers_per_call is None:
         args.layers_per_call = 1 if args.config == "llama7b" else 2
+    probe_fused = bool(args.fused_adam)  # the counter probes run the separate Adam kernel unless --fused-adam 1 is given
+    if args.fused_adam is None:
+        args.fused_adam = 1 if args.config in ("llama7b", "llama350m", "llama130m") else 0
+    if args.in_flight is None:
+        args.in_flight = 2 if args.config == "llama7b" else 3
     if args.refresh_layers_per_call is None:
         args.refresh_layers_per_call = max(args.layers_per_call, 2) if args.layers_per_call > 0 else 0
     if args.gpus != 1:
@@ -162,7 +174,7 @@ def main():
         lib_build.build()
     gb.lib()
     if args.probe_traffic:
-        probe_traffic(fused_adam=bool(args.fused_adam))
+        probe_traffic(fused_adam=probe_fused)
         return
     if args.probe_refresh:
         probe_refresh()
@@ -196,10 +208,11 @@ def main():
 
     # one call's workspace per call in flight: overlapped calls then overlap their subspace refreshes as well
     opt = gb.GaLore(W, r, update_gap=cfg["update_gap"], refresh_iters=args.refresh_iters, auto_refresh=True, moments=args.moments,
-                    workspace_factor=args.in_flight * min(max(args.layers_per_call, args.refresh_layers_per_call, 1), 2))
+                    workspace_factor=max(args.in_flight, args.refresh_in_flight) * min(max(args.layers_per_call, args.refresh_layers_per_call, 1), 2))
     gb.galore_set_concurrency(opt.ctx, args.lanes)
     gb.galore_set_fused_adam(opt.ctx, args.fused_adam)
     overlap = args.in_flight if (not args.join_every_call and args.lanes > 1) else 0
+    overlap_refresh = args.refresh_in_flight if overlap else 0
     gb.galore_set_call_overlap(opt.ctx, overlap)
     w_descs = [[gb.desc(w) for w in W[n_per_layer * l: n_per_layer * (l + 1)]] for l in range(L)]
     g_descs = [[gb.desc(g) for g in Gpool[s]] for s in range(POOL)]
@@ -218,12 +231,16 @@ def main():
     if LPC_REFRESH not in grouping:
         grouping[LPC_REFRESH] = call_arrays(LPC_REFRESH)
 
-    def one_step(step_index, refresh=False):
+    def one_step(step_index, refresh=False, serial=False):
         lpc = LPC_REFRESH if refresh else LPC
         call_w, call_g = grouping[lpc]
+        if refresh and not serial and overlap_refresh != overlap:  # everything is joined between steps
+            gb.galore_set_call_overlap(opt.ctx, overlap_refresh)
         for l in reversed(range(0, L, lpc)):  # backward order, one layer (or lpc layers) per call
             gb.galore_step(opt.ctx, call_w[l], call_g[(l // lpc + step_index) % POOL][l], n_per_layer * l, len(call_w[l]), lr)
         gb.galore_join(opt.ctx)  # the next forward pass needs the weights: one join per step
+        if refresh and not serial and overlap_refresh != overlap:
+            gb.galore_set_call_overlap(opt.ctx, overlap)
 
     def timed(fn):
         torch.cuda.synchronize()
@@ -257,7 +274,7 @@ def main():
     for i in range(len(W)):
         opt.set_step(i, 0)
     gb.galore_profile_start(opt.ctx)
-    one_step(0, refresh=True)
+    one_step(0, refresh=True, serial=True)
     torch.cuda.synchronize()
     refresh_serial_ms = gb.galore_profile_stop(opt.ctx)["refresh"][0]
     gb.galore_set_concurrency(opt.ctx, args.lanes)
@@ -295,6 +312,11 @@ def main():
                     "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None}
     roofline["launch_ms"] = stage_ms[dominant]
+    if dominant == "project_left" and args.fused_adam and args.moments == "f32" and dtype == "bf16":
+        roofline["note"] = ("this launch also runs the Adam update of Algorithm 2 in its epilogue (18 bytes of moments and N per entry of R, "
+                            "%.2f GB per launch: %.3f ms at the HBM peak) beside the flops counted here; the other GEMM of the step is "
+                            "stages.back" % (sum(r * max(m, n) * (16 + sN) for m, n in shapes) * L * K / max(prof["project_left"][1], 1) / 1e9,
+                                             sum(r * max(m, n) * (16 + sN) for m, n in shapes) * L * K / max(prof["project_left"][1], 1) / PEAK_HBM_GBS / 1e6))
     if args.config == "llama7b":
         if MEASURED_TRAFFIC_7B["sources"] == kernel_sources_digest():
             key = "project_left_fused_adam" if (dominant == "project_left" and args.fused_adam) else dominant
@@ -382,7 +404,7 @@ def main():
                    "tensors": L * n_per_layer, "rank": r, "update_gap": cfg["update_gap"], "refresh_iters": args.refresh_iters,
                    "adam": ("in the projection GEMM's epilogue" if (args.fused_adam and args.moments == "f32" and dtype == "bf16")
                             else "separate kernel"),  # the fused epilogue exists for fp32 moments on the large-tile kernel only
-                   "schedule": "consecutive calls overlap on %d library streams, one join per step" % overlap if overlap else
+                   "schedule": ("consecutive calls overlap on %d library streams (%d on a step with a refresh), one join per step" % (overlap, overlap_refresh)) if overlap else
                                "%d concurrent chains inside each call, joined every call" % args.lanes},
         "roofline": roofline,
         "cpu_baseline": cpu,
