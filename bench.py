@@ -321,7 +321,7 @@ def main():
         if MEASURED_TRAFFIC_7B["sources"] == kernel_sources_digest():
             key = "project_left_fused_adam" if (dominant == "project_left" and args.fused_adam) else dominant
             roofline["traffic"] = MEASURED_TRAFFIC_7B["bytes"].get(key) if LPC == 1 else None
-            roofline["traffic_unit"] = ("bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of `bench.py --probe-traffic`, scaled by a "
+            roofline["traffic_unit"] = ("bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of `bench.py --probe-traffic%s`, scaled by a " % (" --fused-adam 1" if key == "project_left_fused_adam" else "") +
                                         "1 GiB copy; hits in the 256 MB MALL are included; read on these kernel sources, not in this run)")
         else:
             roofline["traffic_unit"] = "null: the kernel sources changed since the counters were last read"
