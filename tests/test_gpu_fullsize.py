@@ -1,7 +1,7 @@
 """Parity at the benchmark's full size and launch configuration: one LLaMA-7B-shaped layer set
 (4x 4096x4096, 2x 4096x11008, 11008x4096; bf16; r = 1024) stepped by one galore_step call per step,
-either with the default three concurrent chains inside the call or as bench.py schedules it (overlapped
-calls, three in flight, one join at the end).
+either with the default three concurrent chains inside the call or with overlapped calls and one join at the
+end, among them bench.py's default schedule for this stack (two calls in flight, Adam in the projection's epilogue).
 
 The oracle cannot afford the whole thing, but the step is separable: for a LEFT tensor column j of
 W, M, V depends only on column j of G (R[:, j] = P^T G[:, j], Adam is entry-wise, dW[:, j] = P N[:, j]);
@@ -19,7 +19,7 @@ from paper_2403_03507_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("schedule", ["chains", "overlapped_calls", "overlapped_calls_fused_adam"])
+@pytest.mark.parametrize("schedule", ["chains", "overlapped_calls_3", "overlapped_calls_3_fused_adam", "overlapped_calls_2_fused_adam"])
 def test_llama7b_layer_set_sampled_columns(schedule):
     c = wl.CONFIGS["llama7b"]
     shapes = wl.layer_shapes(c["d"], c["f"])
@@ -32,7 +32,7 @@ def test_llama7b_layer_set_sampled_columns(schedule):
     W0 = [w.clone() for w in W]
     opt = gb.GaLore(W, r, auto_refresh=False, workspace_factor=3)   # default: three concurrent chains inside a call
     if schedule.startswith("overlapped_calls"):
-        opt.set_call_overlap(3)
+        opt.set_call_overlap(int(schedule.split("_")[2]))
     if schedule.endswith("fused_adam"):   # Adam in the projection's epilogue
         opt.set_fused_adam(True)
     for i, p in enumerate(opt.proj):
