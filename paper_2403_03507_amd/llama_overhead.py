@@ -79,6 +79,8 @@ def main(argv=None):
     ap.add_argument("--seq", type=int, default=2048)
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--moments", choices=["f32", "q8"], default="f32")
+    ap.add_argument("--in-flight", type=int, choices=[2, 3], default=3, help="GaLore calls in flight on the library's streams")
+    ap.add_argument("--fused-adam", type=int, choices=[0, 1], default=0, help="1: Adam in the epilogue of the projection GEMM")
     args = ap.parse_args(argv)
     torch.cuda.set_device(0)
     dtype = torch.bfloat16
@@ -115,9 +117,10 @@ def main(argv=None):
     ms_adamw = timed(with_adamw, args.reps)
     del adamw
 
-    # three calls in flight, and a workspace share for each so that the refreshes of the first step overlap too
-    drv = PerLayerGaLore([blk.matrices() for blk in blocks], args.rank, 1e-4, overlap_calls=3, update_gap=200,
-                         refresh_iters=4, moments=args.moments, workspace_factor=3)
+    # calls in flight, and a workspace share for each so that the refreshes of the first step overlap too
+    drv = PerLayerGaLore([blk.matrices() for blk in blocks], args.rank, 1e-4, overlap_calls=args.in_flight, update_gap=200,
+                         refresh_iters=4, moments=args.moments, workspace_factor=args.in_flight)
+    drv.opt.set_fused_adam(bool(args.fused_adam))
     # the first step refreshes every projector; time it apart
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -137,7 +140,7 @@ def main(argv=None):
     out = {
         "what": "forward + backward of a LLaMA-shaped decoder stack, with and without per-layer GaLore updates",
         "config": {"d": args.d, "f": args.f, "heads": args.heads, "layers": args.layers, "rank": args.rank, "tokens": tokens,
-                   "dtype": "bf16", "moments": args.moments},
+                   "dtype": "bf16", "moments": args.moments, "calls_in_flight": args.in_flight, "fused_adam": args.fused_adam},
         "ms_forward_backward": ms_plain, "ms_with_galore": ms_galore, "ms_with_fused_adamw": ms_adamw,
         "ms_first_step_with_refresh": ms_first,
         "tokens_per_s_forward_backward": tokens / ms_plain * 1e3,
